@@ -1,0 +1,145 @@
+"""ctypes loader of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only tests, the smoke check and the bench's CPU-baseline leg may import this
+package.  It builds `oracle.c` with gcc on first use and exposes numpy-array
+wrappers; it imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+INF = 1 << 52
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no SIMD intrinsics, OpenMP across problems only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_plan_cost.restype = ctypes.c_int64
+        _lib.oracle_owner.restype = ctypes.c_int64
+        _lib.oracle_owner.argtypes = [ctypes.c_int64] * 3
+        _lib.oracle_axis_bytes.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _chk(a, dtype, name):
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"{name}: need C-contiguous {dtype}")
+    return a
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def chain(c: np.ndarray, R: np.ndarray, nthreads: int = 1, shared_R: bool = False):
+    """c[B][N][Kp], R[B][N-1][Kp][Kp] (or [N-1][Kp][Kp] with shared_R) ->
+    arg uint16[B][N-1][Kp], vfinal[B][Kp], total[B], last[B]."""
+    _chk(c, np.int64, "c"); _chk(R, np.int64, "R")
+    B, N, Kp = c.shape
+    if shared_R:
+        assert R.shape == (N - 1, Kp, Kp)
+        r_bs = 0
+    else:
+        assert R.shape == (B, N - 1, Kp, Kp)
+        r_bs = (N - 1) * Kp * Kp
+    arg = np.zeros((B, max(N - 1, 0), Kp), dtype=np.uint16)
+    vfinal = np.zeros((B, Kp), dtype=np.int64)
+    total = np.zeros(B, dtype=np.int64)
+    last = np.zeros(B, dtype=np.int32)
+    rc = lib().oracle_chain(ctypes.c_int32(B), ctypes.c_int32(N), ctypes.c_int32(Kp), _p(c),
+                            ctypes.c_int64(N * Kp), _p(R), ctypes.c_int64(r_bs), _p(arg),
+                            _p(vfinal), _p(total), _p(last), ctypes.c_int32(nthreads))
+    if rc != 0:
+        raise ValueError(f"oracle_chain rc={rc}")
+    return arg, vfinal, total, last
+
+
+def backtrack(arg: np.ndarray, last: np.ndarray) -> np.ndarray:
+    _chk(arg, np.uint16, "arg"); _chk(last, np.int32, "last")
+    B, Nm1, Kp = arg.shape
+    plan = np.zeros((B, Nm1 + 1), dtype=np.int32)
+    rc = lib().oracle_backtrack(ctypes.c_int32(B), ctypes.c_int32(Nm1 + 1), ctypes.c_int32(Kp),
+                                _p(arg), _p(last), _p(plan))
+    if rc != 0:
+        raise ValueError(f"oracle_backtrack rc={rc}")
+    return plan
+
+
+def plan_cost(c: np.ndarray, R: np.ndarray, plan: np.ndarray) -> int:
+    """Objective of one plan on one problem: c[N][Kp], R[N-1][Kp][Kp], plan int32[N]."""
+    _chk(c, np.int64, "c"); _chk(R, np.int64, "R"); _chk(plan, np.int32, "plan")
+    N, Kp = c.shape
+    return int(lib().oracle_plan_cost(ctypes.c_int32(N), ctypes.c_int32(Kp), _p(c), _p(R), _p(plan)))
+
+
+def stage_dp(cost: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
+    """cost[B][L] -> bottleneck[B][S], cut int32[B][S][L+1], bounds int32[B][s_query+1] or None."""
+    _chk(cost, np.int64, "cost")
+    B, L = cost.shape
+    bott = np.zeros((B, S), dtype=np.int64)
+    cut = np.zeros((B, S, L + 1), dtype=np.int32)
+    bounds = np.zeros((B, s_query + 1), dtype=np.int32) if s_query > 0 else None
+    rc = lib().oracle_stage_dp(ctypes.c_int32(B), ctypes.c_int32(L), ctypes.c_int32(S), _p(cost),
+                               _p(bott), _p(cut), ctypes.c_int32(s_query),
+                               _p(bounds) if bounds is not None else None,
+                               ctypes.c_int32(nthreads))
+    if rc != 0:
+        raise ValueError(f"oracle_stage_dp rc={rc}")
+    return bott, cut, bounds
+
+
+def build_reshard(m, bw_bytes_per_us, alpha_ns, K: np.ndarray, out_spec: np.ndarray,
+                  in_spec: np.ndarray, dims: np.ndarray, elem_bytes: np.ndarray) -> np.ndarray:
+    """Specs uint32[n_edges+1][Kp], dims int64[n_edges][4], elem_bytes int32[n_edges],
+    K int32[n_edges+1] -> R int64[n_edges][Kp][Kp]."""
+    _chk(K, np.int32, "K"); _chk(out_spec, np.uint32, "out_spec"); _chk(in_spec, np.uint32, "in_spec")
+    _chk(dims, np.int64, "dims"); _chk(elem_bytes, np.int32, "elem_bytes")
+    n_ops, Kp = out_spec.shape
+    n_edges = n_ops - 1
+    assert in_spec.shape == (n_ops, Kp) and K.shape == (n_ops,)
+    assert dims.shape == (n_edges, 4) and elem_bytes.shape == (n_edges,)
+    naxes = len(m)
+    mm = np.array(list(m) + [1] * (2 - naxes), dtype=np.int32)
+    bw = np.array(list(bw_bytes_per_us) + [1] * (2 - naxes), dtype=np.int64)
+    al = np.array(list(alpha_ns) + [0] * (2 - naxes), dtype=np.int64)
+    R = np.zeros((n_edges, Kp, Kp), dtype=np.int64)
+    rc = lib().oracle_build_reshard(ctypes.c_int32(naxes), _p(mm), _p(bw), _p(al),
+                                    ctypes.c_int32(n_edges), ctypes.c_int32(Kp), _p(K),
+                                    _p(out_spec), _p(in_spec), _p(dims), _p(elem_bytes), _p(R))
+    if rc != 0:
+        raise ValueError(f"oracle_build_reshard rc={rc}")
+    return R
+
+
+def axis_bytes(p_byte: int, q_byte: int, dims, m: int, T: int) -> int:
+    """Bytes one device receives on one mesh axis of size m for the transition p -> q
+    of a local tensor of T bytes with extents dims[4]; -1 = impossible, -2 = invalid spec."""
+    d = np.array(list(dims) + [1] * (4 - len(dims)), dtype=np.int64)
+    return int(lib().oracle_axis_bytes(ctypes.c_uint32(p_byte), ctypes.c_uint32(q_byte), _p(d),
+                                       ctypes.c_int32(m), ctypes.c_int64(T)))
+
+
+def owner(u: int, stride: int, m: int) -> int:
+    return int(lib().oracle_owner(u, stride, m))

@@ -1,0 +1,394 @@
+/*
+ * CPU oracle for plan scoring (TEST INFRASTRUCTURE ONLY).
+ *
+ * This file is the slow, plain statement of what the GPU library must
+ * compute.  It is linked into tests, the smoke check and the bench's CPU
+ * baseline leg, and into nothing else; it shares no code, header, table or
+ * constant generator with the HIP sources.  Everything is int64 nanoseconds.
+ *
+ * What follows the paper and where:
+ *   - objective C = sum_i comp_i[x_i] + sum_(i,i+1) comm_i[x_i][x_{i+1}]
+ *     (Sec. 4.2, "Problem Definition", the equation for C) on a path graph;
+ *   - "stitched with dynamic programming" over the linear chain of segments
+ *     (Sec. 4.3.2) -> oracle_chain / oracle_backtrack;
+ *   - sharding spec (dim, stride), stride = consecutive units per block,
+ *     maximum stride = extent / shards, plus "replicate" and "partial"
+ *     (Sec. 4.1 and Sec. 4.3.3) -> oracle_owner, oracle_build_reshard;
+ *   - sharding applied recursively per device-mesh dimension (Sec. 4);
+ *   - resharding by All-Gather / Reduce-Scatter / All-Reduce / All-To-All
+ *     when producer and consumer specs differ (Sec. 2.1);
+ *   - balanced pipeline stages (Sec. 2.1, Sec. 5.1-5.2) on a chain:
+ *     min over cut sets of the max stage sum -> oracle_stage_dp.
+ *
+ * The paper prints neither the chain recurrence, nor per-collective byte
+ * volumes, nor a stage DP.  The readings taken here are:
+ *   chain:   v_0 = c_0, v_{i+1}[b] = c_{i+1}[b] + min_a (v_i[a] + R_i[a][b]),
+ *            ties -> lowest a, final tie -> lowest b, forward sweep;
+ *            INF = 2^52 marks "infeasible", sums saturate at INF;
+ *   reshard: per mesh axis, bytes a device must RECEIVE, found by counting
+ *            tensor units it needs but does not own; axis 0 converted first,
+ *            then axis 1; time = floor(bytes*1000 / bytes_per_us) + alpha;
+ *   stages:  dp[1][j] = P(j); dp[s][j] = min_{s-1<=i<j} max(dp[s-1][i],
+ *            P(j)-P(i)), ties -> lowest i, no empty stage.
+ *
+ * Parity pins (tests, CPU only): brute force over all K^N plans, layered
+ * shortest path by a library routine, closed forms, invariances, hand-worked
+ * collective volumes, element-level ownership on a tiny tensor, brute force
+ * over all cut sets, binary search + greedy for the bottleneck.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_INF ((int64_t)1 << 52)
+
+typedef unsigned __int128 u128;
+
+/* ------------------------------------------------------------------ */
+/* saturating non-negative add: anything that reaches INF stays INF    */
+static int64_t sat_add(int64_t x, int64_t y)
+{
+    if (x >= ORC_INF || y >= ORC_INF) return ORC_INF;
+    int64_t s = x + y;
+    return s >= ORC_INF ? ORC_INF : s;
+}
+
+/* ------------------------------------------------------------------ */
+/* Chain DP on a path of N operators with Kp (padded) candidates each.  */
+/* c: [B][N][Kp] (batch stride c_bs elements), R: [B][N-1][Kp][Kp]      */
+/* (batch stride R_bs elements, 0 = one R shared by every problem).     */
+/* arg[B][N-1][Kp]: arg_i[b] = minimising a for column b of edge i.     */
+static void chain_one(int N, int Kp, const int64_t *c, const int64_t *R,
+                      uint16_t *arg, int64_t *vfinal, int64_t *total,
+                      int32_t *last)
+{
+    int64_t *v = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
+    int64_t *w = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
+    for (int j = 0; j < Kp; ++j) v[j] = c[j] >= ORC_INF ? ORC_INF : c[j];
+    for (int i = 0; i + 1 < N; ++i) {
+        const int64_t *Ri = R + (size_t)i * Kp * Kp;
+        const int64_t *cn = c + (size_t)(i + 1) * Kp;
+        for (int b = 0; b < Kp; ++b) {
+            int64_t best = sat_add(v[0], Ri[b]);
+            int besta = 0;
+            for (int a = 1; a < Kp; ++a) {
+                int64_t t = sat_add(v[a], Ri[(size_t)a * Kp + b]);
+                if (t < best) { best = t; besta = a; }
+            }
+            w[b] = sat_add(cn[b], best);
+            arg[(size_t)i * Kp + b] = (uint16_t)besta;
+        }
+        int64_t *t = v; v = w; w = t;
+    }
+    int64_t best = v[0];
+    int bestb = 0;
+    for (int b = 1; b < Kp; ++b)
+        if (v[b] < best) { best = v[b]; bestb = b; }
+    if (vfinal) memcpy(vfinal, v, sizeof(int64_t) * (size_t)Kp);
+    *total = best;
+    *last = bestb;
+    free(v);
+    free(w);
+}
+
+int oracle_chain(int32_t B, int32_t N, int32_t Kp, const int64_t *c,
+                 int64_t c_bs, const int64_t *R, int64_t R_bs, uint16_t *arg,
+                 int64_t *vfinal, int64_t *total, int32_t *last,
+                 int32_t nthreads)
+{
+    if (B < 0 || N < 1 || Kp < 1 || Kp > 65535) return -1;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int p = 0; p < B; ++p) {
+        chain_one(N, Kp, c + (size_t)p * c_bs, R + (size_t)p * R_bs,
+                  arg + (size_t)p * (N - 1) * Kp,
+                  vfinal ? vfinal + (size_t)p * Kp : NULL, total + p,
+                  last + p);
+    }
+    return 0;
+}
+
+/* plan[N-1] = last; plan[i] = arg_i[plan[i+1]]                         */
+int oracle_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t *arg,
+                     const int32_t *last, int32_t *plan)
+{
+    if (B < 0 || N < 1 || Kp < 1) return -1;
+    for (int p = 0; p < B; ++p) {
+        const uint16_t *ap = arg + (size_t)p * (N - 1) * Kp;
+        int32_t *pl = plan + (size_t)p * N;
+        pl[N - 1] = last[p];
+        for (int i = N - 2; i >= 0; --i)
+            pl[i] = ap[(size_t)i * Kp + pl[i + 1]];
+    }
+    return 0;
+}
+
+/* The objective itself, for one given plan (Sec. 4.2, equation for C). */
+int64_t oracle_plan_cost(int32_t N, int32_t Kp, const int64_t *c,
+                         const int64_t *R, const int32_t *plan)
+{
+    int64_t s = 0;
+    for (int i = 0; i < N; ++i) s = sat_add(s, c[(size_t)i * Kp + plan[i]]);
+    for (int i = 0; i + 1 < N; ++i)
+        s = sat_add(s, R[((size_t)i * Kp + plan[i]) * Kp + plan[i + 1]]);
+    return s;
+}
+
+/* ------------------------------------------------------------------ */
+/* Pipeline stages on a chain of L segments.                            */
+/* bottleneck[B][S]: entry s-1 = dp[s][L].  cut[B][S][L+1]: entry       */
+/* [s-1][j] = minimising i (lowest on ties), 0 for s = 1, -1 where      */
+/* j < s (no split of j segments into s non-empty stages exists).       */
+/* bounds[B][s_query+1] (optional): stage t covers segments             */
+/* [bounds[t-1], bounds[t]).                                            */
+int oracle_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t *cost,
+                    int64_t *bottleneck, int32_t *cut, int32_t s_query,
+                    int32_t *bounds, int32_t nthreads)
+{
+    if (B < 0 || L < 1 || S < 1 || S > L) return -1;
+    if (s_query < 0 || s_query > S) return -1;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int p = 0; p < B; ++p) {
+        const int64_t *cs = cost + (size_t)p * L;
+        int32_t *ct = cut + (size_t)p * S * (L + 1);
+        int64_t *P = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        int64_t *prev = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        int64_t *cur = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        P[0] = 0;
+        for (int l = 0; l < L; ++l) P[l + 1] = P[l] + cs[l];
+        /* one stage: the stage is the whole prefix */
+        for (int j = 0; j <= L; ++j) {
+            prev[j] = P[j];
+            ct[j] = j >= 1 ? 0 : -1;
+        }
+        bottleneck[(size_t)p * S] = prev[L];
+        for (int s = 2; s <= S; ++s) {
+            int32_t *cts = ct + (size_t)(s - 1) * (L + 1);
+            for (int j = 0; j <= L; ++j) {
+                if (j < s) { cur[j] = ORC_INF; cts[j] = -1; continue; }
+                int64_t best = ORC_INF;
+                int besti = -1;
+                for (int i = s - 1; i < j; ++i) {
+                    int64_t tail = P[j] - P[i];
+                    int64_t m = prev[i] > tail ? prev[i] : tail;
+                    if (besti < 0 || m < best) { best = m; besti = i; }
+                }
+                cur[j] = best;
+                cts[j] = besti;
+            }
+            bottleneck[(size_t)p * S + (s - 1)] = cur[L];
+            int64_t *t = prev; prev = cur; cur = t;
+        }
+        if (bounds && s_query > 0) {
+            int32_t *bd = bounds + (size_t)p * (s_query + 1);
+            bd[s_query] = L;
+            for (int t = s_query; t >= 1; --t)
+                bd[t - 1] = ct[(size_t)(t - 1) * (L + 1) + bd[t]];
+        }
+        free(P); free(prev); free(cur);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Sharding specs.  One byte per mesh axis inside a 32-bit word         */
+/* (axis 0 = bits 0..7, axis 1 = bits 8..15):                           */
+/*   bits 0..1 state: 0 replicate, 1 split, 2 partial (3 = invalid)     */
+/*   bits 2..4 dim   (tensor dimension that is split, 0..3)             */
+/*   bits 5..7 lgdiv (stride = (extent / m) >> lgdiv)                   */
+/* 0xFFFFFFFF marks an empty (padding) slot.                            */
+enum { ST_R = 0, ST_S = 1, ST_P = 2 };
+
+typedef struct {
+    int valid;
+    int state[2];
+    int dim[2];
+    int64_t stride[2];
+} spec_t;
+
+/* unit u of a dimension split with the given stride over m shards      */
+/* belongs to shard (u div stride) mod m  (Sec. 4.1: stride = number of */
+/* consecutive units per block)                                         */
+int64_t oracle_owner(int64_t u, int64_t stride, int64_t m)
+{
+    return (u / stride) % m;
+}
+
+static spec_t decode_spec(uint32_t w, const int64_t *dims, const int32_t *m,
+                          int naxes)
+{
+    spec_t s;
+    memset(&s, 0, sizeof s);
+    s.valid = 1;
+    if (w == 0xFFFFFFFFu) { s.valid = 0; return s; }
+    for (int x = 0; x < 2; ++x) {
+        unsigned byte = (w >> (8 * x)) & 0xFFu;
+        int st = byte & 3, d = (byte >> 2) & 7, lg = (byte >> 5) & 7;
+        s.state[x] = ST_R; s.dim[x] = 0; s.stride[x] = 0;
+        if (x >= naxes) continue;          /* axis not present: ignored */
+        if (st == 3) { s.valid = 0; return s; }
+        s.state[x] = st;
+        if (st == ST_S) {
+            if (d > 3) { s.valid = 0; return s; }
+            int64_t n = dims[d];
+            int64_t blocks = (int64_t)m[x] << lg;
+            if (n % blocks != 0) { s.valid = 0; return s; }
+            s.dim[x] = d;
+            s.stride[x] = n / blocks;      /* (n / m) >> lg, exact */
+        }
+    }
+    if (naxes == 2 && s.state[0] == ST_S && s.state[1] == ST_S &&
+        s.dim[0] == s.dim[1])
+        s.valid = 0;                       /* one dim on both axes: not a candidate */
+    return s;
+}
+
+static int64_t shards_of(const spec_t *s, int x, const int32_t *m)
+{
+    return s->state[x] == ST_S ? m[x] : 1;
+}
+
+/* Bytes one device receives on one mesh axis of size m when its local  */
+/* tensor of T bytes goes from state p to state q.  Returns -1 if the   */
+/* transition cannot be done.  Found by counting units.                 */
+static int64_t axis_bytes(int ps, int pd, int64_t pst, int qs, int qd,
+                          int64_t qst, const int64_t *dims, int64_t m,
+                          int64_t T)
+{
+    if (ps == qs && (ps != ST_S || (pd == qd && pst == qst))) return 0;
+    if (qs == ST_P) return -1;             /* nothing turns into "partial" */
+    if (ps == ST_R) return 0;              /* replicate -> split: local slice */
+    if (ps == ST_S && qs == ST_R) {
+        /* all-gather: device 0 needs every unit, owns some */
+        int64_t n = dims[pd], missing = 0;
+        for (int64_t u = 0; u < n; ++u)
+            if (oracle_owner(u, pst, m) != 0) ++missing;
+        return (int64_t)((u128)T * (u128)missing / (u128)n);
+    }
+    if (ps == ST_S && qs == ST_S && pd == qd) {
+        /* same dim, other stride: a unit stays iff both layouts put it  */
+        /* on the same device; per-device average of the moved units     */
+        int64_t n = dims[pd], keep = 0;
+        for (int64_t u = 0; u < n; ++u)
+            if (oracle_owner(u, pst, m) == oracle_owner(u, qst, m)) ++keep;
+        return (int64_t)((u128)T * (u128)(n - keep) / ((u128)n * (u128)m));
+    }
+    if (ps == ST_S && qs == ST_S) {
+        /* other dim: device 0 needs its slab of dim qd and already owns */
+        /* the part of it that lies in its slab of dim pd                */
+        int64_t n1 = dims[pd], n2 = dims[qd], need = 0, foreign = 0;
+        for (int64_t u = 0; u < n2; ++u)
+            if (oracle_owner(u, qst, m) == 0) ++need;
+        for (int64_t u = 0; u < n1; ++u)
+            if (oracle_owner(u, pst, m) != 0) ++foreign;
+        return (int64_t)((u128)T * (u128)need * (u128)foreign /
+                         ((u128)n1 * (u128)n2));
+    }
+    if (ps == ST_P && qs == ST_S) {
+        /* reduce-scatter: every needed unit takes m-1 remote partials   */
+        int64_t n = dims[qd], need = 0;
+        for (int64_t u = 0; u < n; ++u)
+            if (oracle_owner(u, qst, m) == 0) ++need;
+        return (int64_t)((u128)T * (u128)need * (u128)(m - 1) / (u128)n);
+    }
+    /* partial -> replicate: all-reduce = reduce-scatter + all-gather,  */
+    /* each moving (m-1)/m of the local bytes                            */
+    int64_t half = (int64_t)((u128)T * (u128)(m - 1) / (u128)m);
+    return half + half;
+}
+
+/* mesh given as plain arrays: m[2], bw_bytes_per_us[2], alpha_ns[2]    */
+/* K[n_edges+1]: real candidate counts; slots >= K[i] are padding.      */
+/* dims[n_edges][4], elem_bytes[n_edges] describe the tensor on edge i, */
+/* produced by operator i (out_spec[i][a]) and consumed by operator     */
+/* i+1 (in_spec[i+1][b]).  R[n_edges][Kp][Kp].                          */
+int oracle_build_reshard(int32_t naxes, const int32_t *m,
+                         const int64_t *bw_bytes_per_us,
+                         const int64_t *alpha_ns, int32_t n_edges, int32_t Kp,
+                         const int32_t *K, const uint32_t *out_spec,
+                         const uint32_t *in_spec, const int64_t *dims,
+                         const int32_t *elem_bytes, int64_t *R)
+{
+    if (naxes < 1 || naxes > 2 || n_edges < 0 || Kp < 1) return -1;
+    const size_t memo_n = 2u * 256u * 256u * 2u;
+    int32_t *memo_edge = (int32_t *)calloc(memo_n, sizeof(int32_t));
+    int64_t *memo_T = (int64_t *)calloc(memo_n, sizeof(int64_t));
+    int64_t *memo_V = (int64_t *)calloc(memo_n, sizeof(int64_t));
+    for (int e = 0; e < n_edges; ++e) {
+        const int64_t *dm = dims + (size_t)e * 4;
+        int64_t total = elem_bytes[e];
+        for (int d = 0; d < 4; ++d) total *= dm[d];
+        spec_t *ps = (spec_t *)malloc(sizeof(spec_t) * (size_t)Kp);
+        spec_t *qs = (spec_t *)malloc(sizeof(spec_t) * (size_t)Kp);
+        for (int j = 0; j < Kp; ++j) {
+            ps[j] = decode_spec(out_spec[(size_t)e * Kp + j], dm, m, naxes);
+            qs[j] = decode_spec(in_spec[(size_t)(e + 1) * Kp + j], dm, m, naxes);
+            if (j >= K[e]) ps[j].valid = 0;
+            if (j >= K[e + 1]) qs[j].valid = 0;
+        }
+        for (int a = 0; a < Kp; ++a)
+            for (int b = 0; b < Kp; ++b) {
+                int64_t *out = R + ((size_t)e * Kp + a) * Kp + b;
+                if (!ps[a].valid || !qs[b].valid) { *out = ORC_INF; continue; }
+                int64_t t = 0;
+                for (int x = 0; x < naxes && t < ORC_INF; ++x) {
+                    /* axes before x already hold q, axes after x still p */
+                    int64_t sh = 1;
+                    for (int y = 0; y < x; ++y) sh *= shards_of(&qs[b], y, m);
+                    for (int y = x + 1; y < naxes; ++y) sh *= shards_of(&ps[a], y, m);
+                    int64_t T = total / sh;
+                    /* identical arguments recur K^2 times per edge: keep  */
+                    /* the counted result per (axis, p byte, q byte, T)    */
+                    unsigned pb = (out_spec[(size_t)e * Kp + a] >> (8 * x)) & 0xFFu;
+                    unsigned qb = (in_spec[(size_t)(e + 1) * Kp + b] >> (8 * x)) & 0xFFu;
+                    size_t slot = (((size_t)x * 256 + pb) * 256 + qb) * 2 + (sh > 1);
+                    int64_t V;
+                    if (memo_edge[slot] == e + 1 && memo_T[slot] == T) {
+                        V = memo_V[slot];
+                    } else {
+                        V = axis_bytes(ps[a].state[x], ps[a].dim[x],
+                                       ps[a].stride[x], qs[b].state[x],
+                                       qs[b].dim[x], qs[b].stride[x], dm,
+                                       m[x], T);
+                        memo_edge[slot] = e + 1; memo_T[slot] = T; memo_V[slot] = V;
+                    }
+                    if (V < 0) { t = ORC_INF; break; }
+                    if (V > 0) {
+                        int64_t ns = (int64_t)((u128)V * 1000u /
+                                               (u128)bw_bytes_per_us[x]) +
+                                     alpha_ns[x];
+                        t = sat_add(t, ns);
+                    }
+                }
+                *out = t;
+            }
+        free(ps); free(qs);
+    }
+    free(memo_edge); free(memo_T); free(memo_V);
+    return 0;
+}
+
+/* received bytes only (no time), one axis, for hand-worked volume pins */
+int64_t oracle_axis_bytes(uint32_t p_byte, uint32_t q_byte,
+                          const int64_t *dims, int32_t m, int64_t T)
+{
+    int32_t mm[2] = { m, 1 };
+    spec_t p = decode_spec(p_byte & 0xFFu, dims, mm, 1);
+    spec_t q = decode_spec(q_byte & 0xFFu, dims, mm, 1);
+    if (!p.valid || !q.valid) return -2;
+    return axis_bytes(p.state[0], p.dim[0], p.stride[0], q.state[0], q.dim[0],
+                      q.stride[0], dims, m, T);
+}
+
+int32_t oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
