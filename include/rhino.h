@@ -1,0 +1,197 @@
+/*
+ * rhino.h -- plan scoring for automatic parallelization, C ABI.
+ *
+ * The library scores candidate parallel execution plans of a linearised
+ * operator graph, as the strategy search of "Auto-Parallelizing Large Models
+ * with Rhino" (arXiv 2302.08141) needs it:
+ *
+ *   operators i = 0..N-1, operator i has K_i candidate sharding strategies;
+ *   comp cost c_i[j] per (operator, strategy) and comm cost R_i[a][b] per
+ *   (edge i -> i+1, strategy pair)          -- Sec. 4.2, "Problem Definition";
+ *   the plan minimising C = sum c_i[x_i] + sum R_i[x_i][x_{i+1}] on the
+ *   chain is found by dynamic programming   -- Sec. 4.3.2 (cones, and the
+ *   linear chain of segments between critical nodes).
+ *
+ * All costs are int64 nanoseconds.  All pointers are DEVICE pointers unless a
+ * parameter says "host".  The caller owns every buffer; the library allocates
+ * nothing and keeps no state.  Every call only enqueues kernels on `stream`
+ * (a hipStream_t passed as void*, NULL = the default stream) and returns; the
+ * caller synchronises.  Calls on different streams may run concurrently.
+ * Return value: RH_OK or a negative RH_ERR_* code; argument errors are found
+ * on the host before anything is launched, so a failing call writes nothing.
+ *
+ * Cost contract: a finite cost lies in [0, 2^36) ns; RH_INF (2^52) means
+ * "infeasible"; any sum that reaches RH_INF is RH_INF.  N <= 2^14 keeps every
+ * finite total below 2^51.
+ */
+#ifndef RHINO_H
+#define RHINO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RH_INF ((int64_t)1 << 52)
+#define RH_KMIN 16   /* padded candidate count: a power of two in [16, 1024] */
+#define RH_KMAX 1024
+#define RH_NMAX 16384
+
+#define RH_OK 0
+#define RH_ERR_NULL (-1)      /* a required pointer is NULL */
+#define RH_ERR_SHAPE (-2)     /* a size is out of range or inconsistent */
+#define RH_ERR_K_RANGE (-3)   /* Kp is not a power of two in [RH_KMIN, RH_KMAX] */
+#define RH_ERR_WORKSPACE (-4) /* workspace missing or too small */
+#define RH_ERR_OVERFLOW (-5)  /* a cost violates the cost contract (rh_check_costs) */
+#define RH_ERR_HIP (-6)       /* the HIP runtime refused a launch */
+
+/* Logical device mesh the plans are searched for (Sec. 4: devices form a
+ * mesh and sharding is applied per mesh axis).  A search input: no device
+ * of the mesh is ever touched.  Host struct, read during the call. */
+typedef struct rh_mesh_t {
+    int32_t naxes;              /* 1 or 2 */
+    int32_t m[2];               /* axis sizes, powers of two, <= 1024 */
+    int64_t bw_bytes_per_us[2]; /* link bandwidth along each axis, > 0 */
+    int64_t alpha_ns[2];        /* latency added when an axis moves > 0 bytes */
+} rh_mesh_t;
+
+/*
+ * Sharding spec word (Sec. 4.1: a spec is (dim, stride), stride = number of
+ * consecutive units per block, maximum stride = extent / shards; Sec. 4.3.3:
+ * plus "replicate" and "partial").  One byte per mesh axis, axis 0 in bits
+ * 0..7, axis 1 in bits 8..15:
+ *     bits 0..1 state  0 replicate, 1 split, 2 partial
+ *     bits 2..4 dim    split tensor dimension, 0..3
+ *     bits 5..7 lgdiv  stride = (extent[dim] / m[axis]) >> lgdiv
+ * 0xFFFFFFFF = empty slot.  A word is an invalid candidate (all its costs are
+ * RH_INF) if its state is 3, if m[axis] << lgdiv does not divide the extent,
+ * or if both axes split the same dimension.
+ */
+#define RH_SPEC_EMPTY 0xFFFFFFFFu
+
+/*
+ * rh_build_reshard -- comm cost tables from sharding specs.
+ *
+ * R[e][a][b] = time to bring the tensor on edge e from the layout operator e
+ * produces under its strategy a (out_spec[e][a]) to the layout operator e+1
+ * consumes under its strategy b (in_spec[e+1][b]); the collectives of Sec. 2.1
+ * (All-Gather, Reduce-Scatter, All-Reduce, All-To-All) costed by the bytes
+ * one device receives.  Mesh axis 0 is converted first, then axis 1; while
+ * axis x is converted the local tensor is the whole tensor divided by the
+ * shard counts of the other axes (already-converted axes in the consumer's
+ * state).  With local bytes T and axis size m:
+ *     same state (same dim and stride if split)   0
+ *     replicate -> split                          0
+ *     split -> replicate     (all-gather)         T*(m-1)/m
+ *     split -> split, other dim or other stride
+ *                            (all-to-all)         T*(m-1)/m^2
+ *     partial -> split       (reduce-scatter)     T*(m-1)/m
+ *     partial -> replicate   (all-reduce)         2*(T*(m-1)/m)
+ *     anything else -> partial                    infeasible
+ * (divisions round down); time = bytes*1000 / bw_bytes_per_us (round down)
+ * + alpha_ns if bytes > 0; R = sum over axes, RH_INF if infeasible or if
+ * either slot is empty, invalid or >= its operator's K.
+ *
+ *   mesh        host
+ *   n_edges     >= 0 (0: nothing is written)
+ *   Kp          row length of every table, power of two in [RH_KMIN, RH_KMAX]
+ *   K           [n_edges+1] real candidate counts, 0 <= K[i] <= Kp
+ *   out_spec    [n_edges+1][Kp] (row n_edges unused)
+ *   in_spec     [n_edges+1][Kp] (row 0 unused)
+ *   dims        [n_edges][4] extents of the tensor on edge e, unused dims = 1
+ *   elem_bytes  [n_edges]
+ *   R           [n_edges][Kp][Kp] out, row a (producer), column b contiguous
+ * Whole-tensor bytes must stay below 2^50.
+ */
+int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
+                     const int32_t* K, const uint32_t* out_spec,
+                     const uint32_t* in_spec, const int64_t* dims,
+                     const int32_t* elem_bytes, int64_t* R, void* stream);
+
+/*
+ * rh_minplus_chain -- the chain dynamic program, B independent problems
+ * (e.g. one per candidate device-mesh shape, Sec. 3 / Sec. 4: mesh
+ * configurations are searched in parallel).
+ *
+ *     v_0 = c_0
+ *     v_{i+1}[b] = c_{i+1}[b] + min_a ( v_i[a] + R_i[a][b] )
+ *     arg_i[b]   = the minimising a, lowest a on ties (0 if column b is infeasible)
+ *     total      = min_b v_{N-1}[b],  last = lowest such b
+ * which minimises the objective C of Sec. 4.2 on a path graph.
+ *
+ *   B >= 0, 1 <= N <= RH_NMAX, Kp power of two in [RH_KMIN, RH_KMAX]
+ *   c       [B][N][Kp], problem p starts at c + p*c_batch_stride (elements);
+ *           empty slots hold RH_INF
+ *   R       [B][N-1][Kp][Kp], problem p starts at R + p*R_batch_stride;
+ *           R_batch_stride = 0 shares one R among all problems; rows/columns
+ *           of empty slots hold RH_INF.  May be NULL if N == 1.
+ *   arg     [B][N-1][Kp] out (dense)
+ *   vfinal  [B][Kp] out, v_{N-1}; may be NULL
+ *   total   [B] out;  last [B] out
+ *   workspace  unused by the current kernels (rh_workspace_size gives 0);
+ *           pass NULL, 0
+ * Base pointers and batch strides must keep every row 16-byte aligned.
+ */
+int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
+                     int64_t c_batch_stride, const int64_t* R,
+                     int64_t R_batch_stride, uint16_t* arg, int64_t* vfinal,
+                     int64_t* total, int32_t* last, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/*
+ * rh_backtrack -- the plan X of Sec. 4.2 in index form:
+ *     plan[N-1] = last;  plan[i] = arg_i[plan[i+1]],  i = N-2 .. 0.
+ *   arg [B][N-1][Kp], last [B] (values in [0,Kp)), plan [B][N] out.
+ */
+int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
+                 const int32_t* last, int32_t* plan, void* stream);
+
+/*
+ * rh_stage_dp -- balanced pipeline stages on a chain of L segments (Sec. 2.1:
+ * stages should balance computation time; Sec. 5.1: stage ids never decrease
+ * along an edge; Sec. 5.2: time_per_stage = total / stages is the ideal).
+ * With P(j) = cost[0] + .. + cost[j-1]:
+ *     dp[1][j] = P(j)
+ *     dp[s][j] = min_{s-1 <= i < j} max( dp[s-1][i], P(j) - P(i) ),  j >= s
+ *     cut[s][j] = the minimising i, lowest on ties
+ * for every s = 1..S in one call.
+ *
+ *   B >= 0, 1 <= S <= L <= 65536, S <= 1024; cost[l] in [0, 2^36)
+ *   seg_cost    [B][L]
+ *   bottleneck  [B][S] out, entry s-1 = dp[s][L]
+ *   cut         [B][S][L+1] out, entry [s-1][j]; 0 for s = 1, -1 where j < s
+ *   s_query     0 (no bounds wanted) or 1..S
+ *   bounds      [B][s_query+1] out: stage t = segments [bounds[t-1], bounds[t]);
+ *               may be NULL if s_query == 0
+ *   workspace   rh_workspace_size(RH_WS_STAGE_DP, B, L, S) bytes, 256-byte
+ *               aligned; contents undefined before and after the call
+ */
+int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
+                int64_t* bottleneck, int32_t* cut, int32_t s_query,
+                int32_t* bounds, void* workspace, size_t workspace_bytes,
+                void* stream);
+
+#define RH_WS_MINPLUS_CHAIN 0
+#define RH_WS_STAGE_DP 1
+/* Bytes of workspace the call `which` needs for these sizes (0 if none or
+ * if the sizes are invalid). */
+size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,
+                         int32_t Kp_or_S);
+
+/*
+ * rh_check_costs -- optional guard for the cost contract.  Counts the entries
+ * of x[0..n) that are neither in [0, 2^36) nor equal to RH_INF and adds the
+ * count to *violations (device, caller-zeroed).  Never part of a timed path.
+ */
+int rh_check_costs(const int64_t* x, int64_t n, int64_t* violations,
+                   void* stream);
+
+const char* rh_strerror(int code);
+int rh_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RHINO_H */

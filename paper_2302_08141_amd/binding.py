@@ -1,0 +1,155 @@
+"""ctypes binding of librhino.so: same entry-point names, argument marshalling only.
+
+Tensors are torch CUDA tensors (PyTorch is used for device memory and streams,
+nothing else); every call is enqueued on torch's current stream.  There is no
+CPU path: a missing library raises at first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librhino.so")
+
+INF = 1 << 52
+KMIN, KMAX, NMAX = 16, 1024, 16384
+WS_MINPLUS_CHAIN, WS_STAGE_DP = 0, 1
+
+
+class RhinoError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+        self.code = code
+
+
+class Mesh(ctypes.Structure):
+    """Mirror of rh_mesh_t."""
+    _fields_ = [("naxes", ctypes.c_int32), ("m", ctypes.c_int32 * 2),
+                ("bw_bytes_per_us", ctypes.c_int64 * 2), ("alpha_ns", ctypes.c_int64 * 2)]
+
+    @classmethod
+    def make(cls, m, bw_bytes_per_us, alpha_ns=None):
+        n = len(m)
+        alpha_ns = [0] * n if alpha_ns is None else list(alpha_ns)
+        pad = lambda xs, v: list(xs) + [v] * (2 - n)
+        return cls(n, (ctypes.c_int32 * 2)(*pad(m, 1)), (ctypes.c_int64 * 2)(*pad(bw_bytes_per_us, 1)),
+                   (ctypes.c_int64 * 2)(*pad(alpha_ns, 0)))
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library built in-tree; fail loudly if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2302_08141_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.rh_build_reshard.argtypes = [ctypes.POINTER(Mesh), i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.rh_minplus_chain.argtypes = [i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.rh_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        L.rh_stage_dp.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
+        L.rh_workspace_size.restype = sz
+        L.rh_check_costs.argtypes = [vp, i64, vp, vp]
+        L.rh_strerror.argtypes = [ctypes.c_int]
+        L.rh_strerror.restype = ctypes.c_char_p
+        for f in (L.rh_build_reshard, L.rh_minplus_chain, L.rh_backtrack, L.rh_stage_dp, L.rh_check_costs,
+                  L.rh_version):
+            f.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().rh_strerror(code).decode()
+
+
+def rh_version() -> int:
+    return lib().rh_version()
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype, name, need: int = 0):
+    """Device pointer of t after checking type, layout and that it holds at least `need` elements
+    (the kernels index by the sizes passed, so a short buffer must never reach them)."""
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous CUDA tensor of {dtype}")
+    if t.numel() < need:
+        raise ValueError(f"{name}: {t.numel()} elements, the call needs {need}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RhinoError(rc, what)
+
+
+def rh_build_reshard(mesh: Mesh, n_edges: int, Kp: int, K, out_spec, in_spec, dims, elem_bytes, R):
+    """K int32[n_edges+1]; out_spec, in_spec int32-typed words [n_edges+1][Kp]; dims int64[n_edges][4];
+    elem_bytes int32[n_edges]; R int64[n_edges][Kp][Kp] (out)."""
+    e, k = max(n_edges, 0), max(Kp, 0)
+    _check(lib().rh_build_reshard(ctypes.byref(mesh), n_edges, Kp, _ptr(K, torch.int32, "K", e + 1),
+                                  _ptr(out_spec, torch.int32, "out_spec", (e + 1) * k),
+                                  _ptr(in_spec, torch.int32, "in_spec", (e + 1) * k),
+                                  _ptr(dims, torch.int64, "dims", 4 * e),
+                                  _ptr(elem_bytes, torch.int32, "elem_bytes", e),
+                                  _ptr(R, torch.int64, "R", e * k * k), _stream()), "rh_build_reshard")
+
+
+def rh_minplus_chain(B: int, N: int, Kp: int, c, c_batch_stride: int, R, R_batch_stride: int, arg, vfinal,
+                     total, last, workspace=None, workspace_bytes: int = 0):
+    """c int64[B][N][Kp]; R int64[B][N-1][Kp][Kp] (or one shared table with R_batch_stride 0);
+    arg: int16-typed storage for uint16[B][N-1][Kp] (out); vfinal int64[B][Kp] or None; total int64[B];
+    last int32[B]."""
+    b, n, k = max(B, 0), max(N, 1), max(Kp, 0)
+    span = lambda stride, one: (b - 1) * stride + one if b > 0 else 0     # elements the batch touches
+    _check(lib().rh_minplus_chain(B, N, Kp, _ptr(c, torch.int64, "c", span(c_batch_stride, n * k)),
+                                  c_batch_stride,
+                                  _ptr(R, torch.int64, "R", span(R_batch_stride, (n - 1) * k * k)),
+                                  R_batch_stride, _ptr(arg, torch.int16, "arg", b * (n - 1) * k),
+                                  _ptr(vfinal, torch.int64, "vfinal", b * k), _ptr(total, torch.int64, "total", b),
+                                  _ptr(last, torch.int32, "last", b),
+                                  ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None,
+                                  workspace_bytes, _stream()), "rh_minplus_chain")
+
+
+def rh_backtrack(B: int, N: int, Kp: int, arg, last, plan):
+    b, n, k = max(B, 0), max(N, 1), max(Kp, 0)
+    _check(lib().rh_backtrack(B, N, Kp, _ptr(arg, torch.int16, "arg", b * (n - 1) * k),
+                              _ptr(last, torch.int32, "last", b), _ptr(plan, torch.int32, "plan", b * n),
+                              _stream()), "rh_backtrack")
+
+
+def rh_workspace_size(which: int, B: int, N_or_L: int, Kp_or_S: int) -> int:
+    return int(lib().rh_workspace_size(which, B, N_or_L, Kp_or_S))
+
+
+def rh_stage_dp(B: int, L: int, S: int, seg_cost, bottleneck, cut, s_query: int, bounds, workspace):
+    """seg_cost int64[B][L]; bottleneck int64[B][S]; cut int32[B][S][L+1]; bounds int32[B][s_query+1] or None;
+    workspace: uint8 CUDA tensor of at least rh_workspace_size(WS_STAGE_DP, B, L, S) bytes."""
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    b, l, s_ = max(B, 0), max(L, 0), max(S, 0)
+    _check(lib().rh_stage_dp(B, L, S, _ptr(seg_cost, torch.int64, "seg_cost", b * l),
+                             _ptr(bottleneck, torch.int64, "bottleneck", b * s_),
+                             _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)), s_query,
+                             _ptr(bounds, torch.int32, "bounds", b * (max(s_query, 0) + 1)), ws_ptr, ws_bytes,
+                             _stream()), "rh_stage_dp")
+
+
+def rh_check_costs(x, violations):
+    """Adds to violations (int64[1], caller-zeroed) the number of entries of x outside the cost contract."""
+    _check(lib().rh_check_costs(_ptr(x, torch.int64, "x"), x.numel(), _ptr(violations, torch.int64, "violations"),
+                                _stream()), "rh_check_costs")

@@ -1,0 +1,36 @@
+// Internal launch interface between the C-ABI layer and the gfx950 kernels.
+// Every launcher only enqueues work on `stream`; arguments are already validated.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rh {
+
+constexpr int64_t kInf = (int64_t)1 << 52;
+
+struct Mesh {
+    int32_t naxes;
+    int32_t lgm[2];             // log2 of the axis sizes
+    int64_t bw_bytes_per_us[2];
+    int64_t alpha_ns[2];
+};
+
+hipError_t launch_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs,
+                        const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
+                        int64_t* total, int32_t* last, hipStream_t stream);
+
+hipError_t launch_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
+                            const int32_t* last, int32_t* plan, hipStream_t stream);
+
+hipError_t launch_reshard(const Mesh& mesh, int32_t n_edges, int32_t Kp, const int32_t* K,
+                          const uint32_t* out_spec, const uint32_t* in_spec, const int64_t* dims,
+                          const int32_t* elem_bytes, int64_t* R, hipStream_t stream);
+
+size_t stage_workspace_bytes(int32_t B, int32_t L, int32_t S);
+hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
+                           int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds,
+                           void* workspace, hipStream_t stream);
+
+hipError_t launch_check_costs(const int64_t* x, int64_t n, int64_t* violations, hipStream_t stream);
+
+}  // namespace rh

@@ -1,0 +1,131 @@
+// C-ABI layer: argument validation on the host, then kernel launches on the caller's stream.
+// Nothing is allocated, nothing is synchronised, no state is kept.
+#include "../../include/rhino.h"
+
+#include "kernels.h"
+
+namespace {
+
+bool valid_kp(int32_t Kp) { return Kp >= RH_KMIN && Kp <= RH_KMAX && (Kp & (Kp - 1)) == 0; }
+
+int lg2_exact(int64_t x) {   // log2 of a power of two, -1 otherwise
+    if (x <= 0 || (x & (x - 1)) != 0) return -1;
+    int l = 0;
+    while (((int64_t)1 << l) < x) ++l;
+    return l;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int from_hip(hipError_t e) { return e == hipSuccess ? RH_OK : RH_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp, const int32_t* K,
+                     const uint32_t* out_spec, const uint32_t* in_spec, const int64_t* dims,
+                     const int32_t* elem_bytes, int64_t* R, void* stream) {
+    if (mesh == nullptr) return RH_ERR_NULL;
+    if (n_edges < 0) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (mesh->naxes < 1 || mesh->naxes > 2) return RH_ERR_SHAPE;
+    rh::Mesh m{};
+    m.naxes = mesh->naxes;
+    for (int x = 0; x < 2; ++x) {
+        m.lgm[x] = 0;
+        m.bw_bytes_per_us[x] = 1;
+        m.alpha_ns[x] = 0;
+        if (x >= mesh->naxes) continue;
+        const int lg = lg2_exact(mesh->m[x]);
+        if (lg < 0 || lg > 10) return RH_ERR_SHAPE;
+        if (mesh->bw_bytes_per_us[x] <= 0 || mesh->alpha_ns[x] < 0) return RH_ERR_SHAPE;
+        m.lgm[x] = lg;
+        m.bw_bytes_per_us[x] = mesh->bw_bytes_per_us[x];
+        m.alpha_ns[x] = mesh->alpha_ns[x];
+    }
+    if (n_edges == 0) return RH_OK;
+    if (!K || !out_spec || !in_spec || !dims || !elem_bytes || !R) return RH_ERR_NULL;
+    if (!aligned16(R) || (reinterpret_cast<uintptr_t>(in_spec) & 7u) != 0) return RH_ERR_SHAPE;
+    return from_hip(rh::launch_reshard(m, n_edges, Kp, K, out_spec, in_spec, dims, elem_bytes, R,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_batch_stride,
+                     const int64_t* R, int64_t R_batch_stride, uint16_t* arg, int64_t* vfinal,
+                     int64_t* total, int32_t* last, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (B < 0 || N < 1 || N > RH_NMAX) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (B == 0) return RH_OK;
+    if (!c || !total || !last) return RH_ERR_NULL;
+    if (N > 1 && (!R || !arg)) return RH_ERR_NULL;
+    if (c_batch_stride < 0 || R_batch_stride < 0) return RH_ERR_SHAPE;
+    if (B > 1 && c_batch_stride < (int64_t)N * Kp) return RH_ERR_SHAPE;
+    if (B > 1 && R_batch_stride != 0 && R_batch_stride < (int64_t)(N - 1) * Kp * Kp) return RH_ERR_SHAPE;
+    // 16-byte loads and stores: rows start on 16-byte boundaries
+    if (!aligned16(c) || (c_batch_stride & 1) || (R && (!aligned16(R) || (R_batch_stride & 1))))
+        return RH_ERR_SHAPE;
+    if ((arg && (reinterpret_cast<uintptr_t>(arg) & 3u)) || (vfinal && !aligned16(vfinal)))
+        return RH_ERR_SHAPE;
+    return from_hip(rh::launch_chain(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal, total,
+                                     last, static_cast<hipStream_t>(stream)));
+}
+
+int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg, const int32_t* last,
+                 int32_t* plan, void* stream) {
+    if (B < 0 || N < 1 || N > RH_NMAX) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (B == 0) return RH_OK;
+    if (!last || !plan || (N > 1 && !arg)) return RH_ERR_NULL;
+    return from_hip(rh::launch_backtrack(B, N, Kp, arg, last, plan, static_cast<hipStream_t>(stream)));
+}
+
+int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_t* bottleneck,
+                int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
+                size_t workspace_bytes, void* stream) {
+    if (B < 0 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+    if (s_query < 0 || s_query > S) return RH_ERR_SHAPE;
+    if (B == 0) return RH_OK;
+    if (!seg_cost || !bottleneck || !cut) return RH_ERR_NULL;
+    if (s_query > 0 && !bounds) return RH_ERR_NULL;
+    if (!workspace) return RH_ERR_WORKSPACE;
+    if (workspace_bytes < rh::stage_workspace_bytes(B, L, S)) return RH_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return RH_ERR_WORKSPACE;
+    return from_hip(rh::launch_stage_dp(B, L, S, seg_cost, bottleneck, cut, s_query, bounds, workspace,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or_S) {
+    if (which == RH_WS_STAGE_DP) {
+        if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
+        return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);
+    }
+    return 0;
+}
+
+int rh_check_costs(const int64_t* x, int64_t n, int64_t* violations, void* stream) {
+    if (n < 0) return RH_ERR_SHAPE;
+    if (n == 0) return RH_OK;
+    if (!x || !violations) return RH_ERR_NULL;
+    return from_hip(rh::launch_check_costs(x, n, violations, static_cast<hipStream_t>(stream)));
+}
+
+const char* rh_strerror(int code) {
+    switch (code) {
+        case RH_OK: return "ok";
+        case RH_ERR_NULL: return "a required pointer is NULL";
+        case RH_ERR_SHAPE: return "a size, stride or alignment is out of range or inconsistent";
+        case RH_ERR_K_RANGE: return "Kp must be a power of two in [16, 1024]";
+        case RH_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case RH_ERR_OVERFLOW: return "a cost violates the cost contract";
+        case RH_ERR_HIP: return "the HIP runtime refused a launch";
+        default: return "unknown error code";
+    }
+}
+
+int rh_version(void) { return 100; }
+
+}  // extern "C"

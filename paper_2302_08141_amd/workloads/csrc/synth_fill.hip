@@ -1,0 +1,56 @@
+// Device-side filler for synthetic cost tables that are too large to upload.
+// Same definition as the host generator: value at position n of the stream seeded s is
+// ((mix64(s + (n+1)*GOLDEN) >> 32) * range) >> 32 with the SplitMix64 output function
+// (Steele, Lea, Flood, OOPSLA 2014); the stream seed of (problem, table) is
+// mix64(mix64(seed + (problem+1)*GOLDEN) + tag*GOLDEN).  Input generation only: no part of
+// plan scoring lives here.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__host__ __device__ inline uint64_t stream_seed(uint64_t seed, uint64_t problem, uint64_t tag) {
+    return mix64(mix64(seed + (problem + 1) * kGolden) + tag * kGolden);
+}
+
+// One problem per blockIdx.y; table of `count` int64 per problem, batch stride in elements.
+// diag_k > 0: positions whose (row, column) inside a diag_k x diag_k tile coincide are zero.
+__global__ void __launch_bounds__(256)
+fill_kernel(int64_t* __restrict__ dst, int64_t batch_stride, int64_t count, uint64_t seed,
+            uint64_t first_problem, uint64_t tag, uint64_t range, int64_t lo, int32_t diag_k) {
+    const uint64_t s = stream_seed(seed, first_problem + blockIdx.y, tag);
+    int64_t* out = dst + (int64_t)blockIdx.y * batch_stride;
+    for (int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; n < count;
+         n += (int64_t)gridDim.x * blockDim.x) {
+        const uint64_t z = mix64(s + ((uint64_t)n + 1) * kGolden);
+        int64_t v = (int64_t)(((z >> 32) * range) >> 32) + lo;
+        if (diag_k > 0) {
+            const int64_t b = n % diag_k, a = (n / diag_k) % diag_k;
+            if (a == b) v = 0;
+        }
+        out[n] = v;
+    }
+}
+
+}  // namespace
+
+extern "C" int synth_fill_uniform(int64_t* dst, int64_t batch_stride, int64_t count, int32_t n_problems,
+                                  uint64_t seed, uint64_t first_problem, uint64_t tag, uint64_t range,
+                                  int64_t lo, int32_t diag_k, void* stream) {
+    if (!dst || count < 0 || n_problems < 0 || range == 0 || range > (1ull << 32)) return -1;
+    if (count == 0 || n_problems == 0) return 0;
+    int64_t bx = (count + 255) / 256;
+    if (bx > 1024) bx = 1024;
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)bx, (unsigned)n_problems), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), dst, batch_stride, count, seed, first_problem,
+                       tag, range, lo, diag_k);
+    return hipGetLastError() == hipSuccess ? 0 : -2;
+}

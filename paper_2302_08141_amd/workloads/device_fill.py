@@ -1,0 +1,52 @@
+"""Device-side filler for synthetic tables too large to upload (binding of libsynthfill.so).
+
+Implements the same SplitMix64 streams as `synthetic.py`; a GPU test compares
+the two element by element.  Input generation only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import synthetic as syn
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsynthfill.so")
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2302_08141_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        L.synth_fill_uniform.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                         ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
+                                         ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p]
+        L.synth_fill_uniform.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def fill_uniform(dst: torch.Tensor, first_problem: int, tag: int, rng: int, lo: int = 0, diag_k: int = 0,
+                 seed: int = syn.BASE_SEED) -> None:
+    """dst int64[n_problems][...]: problem p of the batch gets stream (seed, first_problem+p, tag)."""
+    assert dst.is_cuda and dst.dtype == torch.int64 and dst.is_contiguous() and dst.dim() >= 2
+    n = dst.shape[0]
+    count = dst[0].numel()
+    rc = lib().synth_fill_uniform(ctypes.c_void_p(dst.data_ptr()), count, count, n, seed, first_problem, tag, rng,
+                                  lo, diag_k, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"synth_fill_uniform rc={rc}")
+
+
+def fill_random_chain(c: torch.Tensor, R: torch.Tensor, first_problem: int, c_range: int, r_range: int,
+                      seed: int = syn.BASE_SEED, c_lo: int = 0) -> None:
+    """c[B][N][K], R[B][N-1][K][K] with K unpadded: the device twin of synthetic.random_chain_batch."""
+    K = c.shape[-1]
+    fill_uniform(c, first_problem, syn.TAG_NODE, c_range, c_lo, 0, seed)
+    if R.numel():
+        fill_uniform(R, first_problem, syn.TAG_EDGE, r_range, 0, K, seed)

@@ -1,0 +1,38 @@
+"""The C-ABI library loads without a GPU and exports every entry point the header declares."""
+import ctypes
+import os
+import re
+
+from paper_2302_08141_amd import binding as rh
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rhino.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rh_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_functions()
+    assert {"rh_build_reshard", "rh_minplus_chain", "rh_backtrack", "rh_stage_dp", "rh_workspace_size",
+            "rh_strerror", "rh_version", "rh_check_costs"} <= set(names)
+    lib = ctypes.CDLL(rh.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_host_only_calls():
+    assert rh.rh_version() >= 100
+    assert rh.strerror(0) == "ok" and "NULL" in rh.strerror(-1)
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 4096, 512, 128) == 0
+    assert rh.rh_workspace_size(rh.WS_STAGE_DP, 2, 4096, 64) == 2 * 2 * 4097 * 16
+    # argument errors are found before anything touches a device
+    L = rh.lib()
+    assert L.rh_minplus_chain(1, 2, 100, None, 0, None, 0, None, None, None, None, None, 0, None) == -3
+    assert L.rh_minplus_chain(1, 2, 128, None, 0, None, 0, None, None, None, None, None, 0, None) == -1
+    assert L.rh_stage_dp(1, 10, 11, None, None, None, 0, None, None, 0, None) == -2
+    assert L.rh_backtrack(-1, 2, 128, None, None, None, None) == -2
+    assert L.rh_build_reshard(None, 1, 128, None, None, None, None, None, None, None) == -1
+    assert L.rh_check_costs(None, 5, None, None) == -1

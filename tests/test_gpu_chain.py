@@ -1,0 +1,136 @@
+"""GPU parity of the chain DP and backtrack against the CPU oracle (bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_08141_amd import binding as rh
+from paper_2302_08141_amd.workloads import device_fill, synthetic as syn
+
+pytestmark = pytest.mark.gpu
+INF = oracle.INF
+DEV = "cuda:0"
+
+
+def gpu_chain(c, R, shared_R=False, want_vfinal=True):
+    B, N, Kp = c.shape
+    dc = torch.from_numpy(c).to(DEV)
+    dR = torch.from_numpy(R).to(DEV) if R.size else None
+    arg = torch.full((B, max(N - 1, 0), Kp), -1, dtype=torch.int16, device=DEV)
+    vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV) if want_vfinal else None
+    total = torch.zeros(B, dtype=torch.int64, device=DEV)
+    last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    plan = torch.full((B, N), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, 0 if shared_R else (N - 1) * Kp * Kp, arg if N > 1 else None,
+                        vfinal, total, last)
+    rh.rh_backtrack(B, N, Kp, arg if N > 1 else None, last, plan)
+    torch.cuda.synchronize()
+    return (arg.cpu().numpy().view(np.uint16), vfinal.cpu().numpy() if want_vfinal else None,
+            total.cpu().numpy(), last.cpu().numpy(), plan.cpu().numpy())
+
+
+def check(c, R, shared_R=False):
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R, nthreads=4, shared_R=shared_R)
+    o_plan = oracle.backtrack(o_arg, o_last)
+    g_arg, g_vf, g_total, g_last, g_plan = gpu_chain(c, R, shared_R)
+    assert np.array_equal(g_total, o_total)
+    assert np.array_equal(g_last, o_last)
+    assert np.array_equal(g_vf, o_vf)
+    assert np.array_equal(g_arg, o_arg)
+    assert np.array_equal(g_plan, o_plan)
+
+
+def test_tiny_chain_config():
+    w = syn.TINY_CHAIN
+    c, R = syn.random_chain_batch([0], w["N"], w["K"], w["c_range"], w["r_range"], Kp=16)
+    check(c, R)
+
+
+@pytest.mark.parametrize("Kp", [16, 32, 64, 128, 256, 512, 1024])
+def test_every_tile_width(Kp):
+    # several edges per problem, a ragged number of problems per workgroup, full and padded K
+    B, N = (7, 5) if Kp <= 256 else (3, 3)
+    K = Kp if Kp % 32 == 0 and Kp != 64 else Kp - 3
+    c, R = syn.random_chain_batch(range(B), N, K, 1000, 5000, Kp=Kp)
+    check(c, R)
+
+
+@pytest.mark.parametrize("Kp,N,B", [(128, 40, 9), (64, 33, 13), (256, 9, 5)])
+def test_longer_chains(Kp, N, B):
+    c, R = syn.random_chain_batch(range(100, 100 + B), N, Kp, 1_000_000, 10_000_000, Kp=Kp)
+    check(c, R)
+
+
+@pytest.mark.parametrize("Kp", [16, 64, 128])
+def test_ties_ragged_and_infeasible(Kp):
+    rng = np.random.default_rng(Kp)
+    B, N = 6, 7
+    c = rng.integers(0, 3, size=(B, N, Kp)).astype(np.int64)          # {0,1,2}: ties everywhere
+    R = rng.integers(0, 3, size=(B, N - 1, Kp, Kp)).astype(np.int64)
+    for p in range(B):
+        Ki = rng.integers(1, Kp + 1, size=N)
+        for i in range(N):
+            c[p, i, Ki[i]:] = INF
+            if i < N - 1:
+                R[p, i, Ki[i]:, :] = INF
+            if i > 0:
+                R[p, i - 1, :, Ki[i]:] = INF
+    R[1][rng.random(R[1].shape) < 0.5] = INF
+    c[2, 3, :] = INF                                                  # problem 2 has no feasible plan
+    check(c, R)
+    _, _, total, last, plan = gpu_chain(c, R)
+    assert total[2] == INF and last[2] == 0 and not plan[2, 3:].any()   # nothing feasible from operator 3 on
+
+
+def test_shared_R_single_operator_and_empty_batch():
+    c, R = syn.random_chain_batch(range(4), 6, 64, 1000, 5000)
+    check(c, np.ascontiguousarray(R[0]), shared_R=True)
+    c1 = c[:, :1].copy()                                              # N = 1: total = min c_0
+    _, vf, total, last, plan = gpu_chain(c1, np.zeros((4, 0, 64, 64), np.int64))
+    assert np.array_equal(total, c1[:, 0].min(axis=1)) and np.array_equal(last, c1[:, 0].argmin(axis=1))
+    assert np.array_equal(plan[:, 0], last) and np.array_equal(vf, c1[:, 0])
+    e = torch.empty(0, dtype=torch.int64, device=DEV)
+    rh.rh_minplus_chain(0, 5, 64, e, 0, e, 0, None, None, e, torch.empty(0, dtype=torch.int32, device=DEV))
+
+
+def test_argument_errors_launch_nothing():
+    # straight through the C ABI: the checks run on the host before any launch
+    import ctypes
+    L = rh.lib()
+    t64 = torch.zeros(64 * 64 * 2, dtype=torch.int64, device=DEV)
+    t32 = torch.zeros(64, dtype=torch.int32, device=DEV)
+    t16 = torch.zeros(64 * 2, dtype=torch.int16, device=DEV)
+    P = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
+
+    def call(B=1, N=2, Kp=64, c=P(t64), R=P(t64), total=P(t64)):
+        return L.rh_minplus_chain(B, N, Kp, c, 128, R, 4096, P(t16), None, total, P(t32), None, 0, None)
+
+    assert call() == 0
+    assert call(Kp=48) == -3 and call(Kp=8) == -3 and call(Kp=2048) == -3
+    assert call(N=0) == -2 and call(N=20000) == -2 and call(B=-1) == -2
+    assert call(c=None) == -1 and call(R=None) == -1 and call(total=None) == -1
+    assert call(c=P(t64, 8)) == -2                                    # rows not 16-byte aligned
+    assert L.rh_backtrack(1, 2, 63, P(t16), P(t32), P(t32), None) == -3
+    assert L.rh_backtrack(1, 2, 64, P(t16), None, P(t32), None) == -1
+    torch.cuda.synchronize()
+    assert "power of two" in rh.strerror(-3)
+    # the binding refuses buffers shorter than the sizes say
+    with pytest.raises(ValueError):
+        rh.rh_minplus_chain(4, 2, 64, t64[:256], 128, t64, 4096, t16, None, t64, t32)
+
+
+def test_device_fill_matches_host_generator():
+    B, N, K = 5, 4, 64
+    c = torch.empty((B, N, K), dtype=torch.int64, device=DEV)
+    R = torch.empty((B, N - 1, K, K), dtype=torch.int64, device=DEV)
+    device_fill.fill_random_chain(c, R, first_problem=37, c_range=1_000_000, r_range=10_000_000)
+    hc, hR = syn.random_chain_batch(range(37, 37 + B), N, K, 1_000_000, 10_000_000)
+    assert np.array_equal(c.cpu().numpy(), hc) and np.array_equal(R.cpu().numpy(), hR)
+
+
+def test_check_costs_counts_contract_violations():
+    x = torch.tensor([0, 5, INF, (1 << 36) - 1, 1 << 36, -1, INF + 1], dtype=torch.int64, device=DEV)
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    rh.rh_check_costs(x, bad)
+    torch.cuda.synchronize()
+    assert bad.item() == 3
