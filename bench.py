@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of plan scoring on one MI355X.
+
+A step is one pass of the scoring path over the batched-random-chains workload
+(B=4096 independent chains, N=512 operators, K=128 candidates; node costs
+uniform [0,1e6), edge tables uniform [0,1e7) with zero diagonal, one SplitMix64
+stream per problem): rh_minplus_chain over all problems, then rh_backtrack.
+The cost tables are generated on the device before the timed region and stay
+resident in HBM (274.3 GB of edge tables).  The metric is min-plus cell
+relaxations per second (one cell = one (a, b) pair of one edge of one problem).
+
+The same run also reports, outside the timed steps: the roofline of the chain
+kernel from per-launch HIP-event times, the CPU oracle on the host cores on a
+sample of the same problems, and the other rows of the path on their own
+workloads (reshard-table generation + chain + backtrack on the MoE-shaped
+graph, the pipeline-stage DP with per-segment chains).
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--problems", type=int, default=0, help="override B (debugging only; 0 = the workload's 4096)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-rows", action="store_true")
+    return ap.parse_args()
+
+
+def kernel_source_hash() -> str:
+    src = os.path.join(ROOT, "paper_2302_08141_amd", "csrc", "chain_dp.hip")
+    return hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+
+
+def recorded_traffic(kernel_hash: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if it was taken on this kernel source."""
+    path = os.path.join(ROOT, "profiles", "chain_wave_kernel_batched_chains_pmc.md")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    h = re.search(r"kernel_source_sha256_16:\s*([0-9a-f]+)", text)
+    t = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
+    if not h or not t or h.group(1) != kernel_hash:
+        return None
+    return float(t.group(1))
+
+
+def host_threads() -> int:
+    n = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit() and int(env) > 0:
+        n = min(n, int(env))
+    return max(n, 1)
+
+
+def cpu_baseline(c, R, B, N, K, sample_problems=2048, batch=64):
+    """The oracle as it stands, on the host cores, on the first `sample_problems` problems of the batch
+    (copied back from HBM in slices; copies are not timed)."""
+    import numpy as np
+    import oracle
+    threads = host_threads()
+    n = min(sample_problems, B)
+    spent, done = 0.0, 0
+    while done < n:
+        m = min(batch, n - done)
+        hc = c[done:done + m].cpu().numpy()
+        hR = R[done:done + m].cpu().numpy()
+        t0 = time.perf_counter()
+        arg, _, total, last = oracle.chain(hc, hR, nthreads=threads)
+        oracle.backtrack(arg, last)
+        spent += time.perf_counter() - t0
+        done += m
+        del hc, hR
+    cells = n * (N - 1) * K * K
+    return {"value": cells / spent, "unit": "cells/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} of {B} problems (N={N}, K={K}), {spent:.1f} s of oracle time, "
+                      f"one problem per thread"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2302_08141_amd import binding as rh
+    from paper_2302_08141_amd.workloads import device_fill, synthetic as syn
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    rh.lib()
+    dev = "cuda:0"
+    w = syn.BATCHED_CHAINS
+    B, N, K = (args.problems or w["B"]), w["N"], w["K"]
+
+    need = B * ((N - 1) * K * K * 8 + N * K * 8 + (N - 1) * K * 2 + N * 4 + 16)
+    free, _ = torch.cuda.mem_get_info()
+    if need > free - (2 << 30):
+        print(f"the workload needs {need / 2**30:.1f} GiB resident, {free / 2**30:.1f} GiB are free", file=sys.stderr)
+        sys.exit(3)
+
+    c = torch.empty((B, N, K), dtype=torch.int64, device=dev)
+    R = torch.empty((B, N - 1, K, K), dtype=torch.int64, device=dev)
+    arg = torch.empty((B, N - 1, K), dtype=torch.int16, device=dev)
+    total = torch.empty(B, dtype=torch.int64, device=dev)
+    last = torch.empty(B, dtype=torch.int32, device=dev)
+    plan = torch.empty((B, N), dtype=torch.int32, device=dev)
+    # fill in slices so that one launch stays short
+    for p0 in range(0, B, 256):
+        p1 = min(B, p0 + 256)
+        device_fill.fill_random_chain(c[p0:p1], R[p0:p1], p0, w["c_range"], w["r_range"])
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        if events is not None:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        rh.rh_minplus_chain(B, N, K, c, N * K, R, (N - 1) * K * K, arg, None, total, last)
+        if events is not None:
+            e1.record()
+            events.append((e0, e1))
+        rh.rh_backtrack(B, N, K, arg, last, plan)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    cells = B * (N - 1) * K * K
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = cells * args.steps / elapsed
+
+    # roofline of the chain kernel: algorithmic bytes per launch / mean launch time (HIP events on the launch stream)
+    kern_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
+    bytes_per_cell = 8.0 * (1.0 + 1.25 / K)                 # R once, plus c read and arg written per edge row
+    algo_bytes = cells * bytes_per_cell
+    achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
+    khash = kernel_source_hash()
+    roofline = {"bound": "hbm", "kernel": f"chain_wave_kernel<{K}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(khash),
+                "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": kern_ms}
+
+    out = {"metric": "min-plus cell relaxations/sec (K^2 per edge, batched)", "value": value, "unit": "cells/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"batched random chains: B={B} N={N} K={K}, c~U[0,1e6) R~U[0,1e7) zero diagonal, "
+                                  f"all tables resident in HBM; step = rh_minplus_chain + rh_backtrack",
+                      "B": B, "N": N, "K": K, "seed": syn.BASE_SEED},
+           "achieved_hbm_gbps": achieved, "roofline": roofline}
+
+    # yardsticks on the same box: a plain read-only stream over part of R and a plain copy of known size
+    sink = torch.zeros(1, dtype=torch.int64, device=dev)
+    probe = R[: min(B, 512)]
+    copy_src = R[: min(B, 64)]
+    copy_dst = torch.empty_like(copy_src)
+    rates = {}
+    for name, fn, nbytes in (("read", lambda: device_fill.stream_read(probe, sink), probe.numel() * 8),
+                             ("copy", lambda: device_fill.stream_copy(copy_dst, copy_src), copy_src.numel() * 8)):
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1)
+            best = t if best is None or t < best else best
+        rates[name] = nbytes / (best * 1e-3) / 1e9
+    del copy_dst
+    out["streaming_read_ceiling_gbps"] = rates["read"]
+    out["streaming_copy_gbps_read_plus_write"] = 2 * rates["copy"]
+    out["roofline"]["frac_of_measured_read_ceiling"] = achieved / rates["read"]
+    out["roofline"]["copy_kernel_bytes_each_way"] = copy_src.numel() * 8
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(c, R, B, N, K)
+        out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
+
+    del c, R, arg, plan
+    torch.cuda.empty_cache()
+    if not args.no_other_rows:
+        try:
+            from paper_2302_08141_amd import other_rows
+            out["other_rows"] = other_rows.measure(dev)
+        except ImportError:
+            pass
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

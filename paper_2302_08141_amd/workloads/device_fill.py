@@ -27,6 +27,11 @@ def lib():
                                          ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                          ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p]
         L.synth_fill_uniform.restype = ctypes.c_int
+        L.synth_stream_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                        ctypes.c_void_p]
+        L.synth_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32,
+                                        ctypes.c_void_p]
+        L.synth_stream_copy.restype = L.synth_stream_read.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -50,3 +55,25 @@ def fill_random_chain(c: torch.Tensor, R: torch.Tensor, first_problem: int, c_ra
     fill_uniform(c, first_problem, syn.TAG_NODE, c_range, c_lo, 0, seed)
     if R.numel():
         fill_uniform(R, first_problem, syn.TAG_EDGE, r_range, 0, K, seed)
+
+
+def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 8192) -> None:
+    """Plain 16-byte-per-lane copy kernel of known size (yardstick for bandwidth and byte counters)."""
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes and nbytes % 16 == 0
+    rc = lib().synth_stream_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes, blocks,
+                                 ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"synth_stream_copy rc={rc}")
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 8192) -> None:
+    """Plain read-only streaming kernel over src (yardstick for the achievable HBM read rate)."""
+    assert src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.dtype == torch.int64 and sink.numel() >= 1
+    nbytes = src.numel() * src.element_size()
+    assert nbytes % 16 == 0
+    rc = lib().synth_stream_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()), blocks,
+                                 ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"synth_stream_read rc={rc}")
