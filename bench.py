@@ -51,7 +51,7 @@ def kernel_source_hash() -> str:
 
 def recorded_traffic(kernel_hash: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if it was taken on this kernel source."""
-    path = os.path.join(ROOT, "profiles", "chain_wave_kernel_batched_chains_pmc.md")
+    path = os.path.join(ROOT, "profiles", "chain_coop_kernel_batched_chains_pmc.md")
     if not os.path.exists(path):
         return None
     text = open(path).read()
@@ -160,7 +160,7 @@ def main():
     algo_bytes = cells * bytes_per_cell
     achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
     khash = kernel_source_hash()
-    roofline = {"bound": "hbm", "kernel": f"chain_wave_kernel<{K}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+    roofline = {"bound": "hbm", "kernel": f"chain_coop_kernel<{K},16>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(khash),
                 "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": kern_ms}
 
@@ -179,6 +179,8 @@ def main():
     copy_dst = torch.empty_like(copy_src)
     rates = {}
     for name, fn, nbytes in (("read", lambda: device_fill.stream_read(probe, sink), probe.numel() * 8),
+                             ("read_wide", lambda: device_fill.stream_read(probe, sink, blocks=2048, wide=True),
+                              probe.numel() * 8),
                              ("copy", lambda: device_fill.stream_copy(copy_dst, copy_src), copy_src.numel() * 8)):
         best = None
         for _ in range(3):
@@ -189,6 +191,7 @@ def main():
             best = t if best is None or t < best else best
         rates[name] = nbytes / (best * 1e-3) / 1e9
     del copy_dst
+    rates["read"] = max(rates["read"], rates.pop("read_wide"))
     out["streaming_read_ceiling_gbps"] = rates["read"]
     out["streaming_copy_gbps_read_plus_write"] = 2 * rates["copy"]
     out["roofline"]["frac_of_measured_read_ceiling"] = achieved / rates["read"]
@@ -201,11 +204,8 @@ def main():
     del c, R, arg, plan
     torch.cuda.empty_cache()
     if not args.no_other_rows:
-        try:
-            from paper_2302_08141_amd import other_rows
-            out["other_rows"] = other_rows.measure(dev)
-        except ImportError:
-            pass
+        from paper_2302_08141_amd import other_rows
+        out["other_rows"] = other_rows.measure(dev)
     print(json.dumps(out))
 
 

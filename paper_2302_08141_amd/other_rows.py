@@ -1,0 +1,79 @@
+"""Timings of the path's other rows on their own workloads (called by bench.py after the timed steps).
+
+Each figure is the best of a few repetitions, taken with events on the launch
+stream, inputs resident on the device:
+  * the MoE-shaped graph (8192 operators, K=256, logical 32x32 mesh): reshard tables from specs
+    (4.29 GB written), chain DP and backtrack of the single long chain;
+  * the GPT-like chain (242 operators, K=64, logical 8x8 mesh): the same three calls;
+  * the stage partition (L=4096 segments, S=64): per-segment chains (8 operators, K=64) then the stage DP.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as rh
+from .workloads import device_fill, graphs, synthetic as syn
+
+
+def _best_ms(fn, reps=3):
+    best = None
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1)
+        best = t if best is None or t < best else best
+    return best
+
+
+def _graph_rows(g, dev):
+    N, Kp = g["N"], g["Kp"]
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mesh = rh.Mesh.make(g["m"], g["bw_bytes_per_us"], g["alpha_ns"])
+    K, osp, isp = to(g["K"]), to(g["out_spec"].view(np.int32)), to(g["in_spec"].view(np.int32))
+    dims, eb, c = to(g["dims"]), to(g["elem_bytes"]), to(g["c"][None])
+    R = torch.empty((N - 1, Kp, Kp), dtype=torch.int64, device=dev)
+    arg = torch.empty((1, N - 1, Kp), dtype=torch.int16, device=dev)
+    total = torch.empty(1, dtype=torch.int64, device=dev)
+    last = torch.empty(1, dtype=torch.int32, device=dev)
+    plan = torch.empty((1, N), dtype=torch.int32, device=dev)
+    t_build = _best_ms(lambda: rh.rh_build_reshard(mesh, N - 1, Kp, K, osp, isp, dims, eb, R))
+    t_chain = _best_ms(lambda: rh.rh_minplus_chain(1, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, None, total, last))
+    t_back = _best_ms(lambda: rh.rh_backtrack(1, N, Kp, arg, last, plan))
+    cells = (N - 1) * Kp * Kp
+    return {"N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
+            "reshard_ms": t_build, "reshard_write_gbps": cells * 8 / (t_build * 1e-3) / 1e9,
+            "chain_ms": t_chain, "chain_cells_per_s": cells / (t_chain * 1e-3),
+            "chain_hbm_gbps": cells * 8 * (1 + 1.25 / Kp) / (t_chain * 1e-3) / 1e9,
+            "backtrack_ms": t_back}
+
+
+def _stage_rows(dev):
+    w = syn.STAGE_PARTITION
+    L, S, M, K = w["L"], w["S"], w["seg_ops"], w["seg_K"]
+    c = torch.empty((L, M, K), dtype=torch.int64, device=dev)
+    R = torch.empty((L, M - 1, K, K), dtype=torch.int64, device=dev)
+    device_fill.fill_random_chain(c, R, 0, w["seg_c_range"], w["seg_r_range"], c_lo=w["seg_c_lo"])
+    arg = torch.empty((L, M - 1, K), dtype=torch.int16, device=dev)
+    seg = torch.empty(L, dtype=torch.int64, device=dev)
+    last = torch.empty(L, dtype=torch.int32, device=dev)
+    t_seg = _best_ms(lambda: rh.rh_minplus_chain(L, M, K, c, M * K, R, (M - 1) * K * K, arg, None, seg, last))
+    bott = torch.empty((1, S), dtype=torch.int64, device=dev)
+    cut = torch.empty((1, S, L + 1), dtype=torch.int32, device=dev)
+    bounds = torch.empty((1, S + 1), dtype=torch.int32, device=dev)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP, 1, L, S), dtype=torch.uint8, device=dev)
+    cost = seg.reshape(1, L)
+    t_dp = _best_ms(lambda: rh.rh_stage_dp(1, L, S, cost, bott, cut, S, bounds, ws))
+    cells = sum((L - s + 1) * (L - s + 2) // 2 for s in range(2, S + 1))      # (i, j) pairs with s-1 <= i < j <= L
+    return {"L": L, "S": S, "segment_chain": {"ops": M, "K": K}, "segment_chains_ms": t_seg,
+            "stage_dp_ms": t_dp, "stage_dp_cells": cells, "stage_dp_cells_per_s": cells / (t_dp * 1e-3),
+            "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
+
+
+def measure(dev="cuda:0"):
+    return {"moe_shaped_graph": _graph_rows(graphs.moe_chain(), dev),
+            "gpt_like_chain": _graph_rows(graphs.gpt_chain(), dev),
+            "stage_partition": _stage_rows(dev)}

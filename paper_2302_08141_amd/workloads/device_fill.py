@@ -31,7 +31,8 @@ def lib():
                                         ctypes.c_void_p]
         L.synth_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32,
                                         ctypes.c_void_p]
-        L.synth_stream_copy.restype = L.synth_stream_read.restype = ctypes.c_int
+        L.synth_stream_read_wide.argtypes = L.synth_stream_read.argtypes
+        L.synth_stream_copy.restype = L.synth_stream_read.restype = L.synth_stream_read_wide.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -68,12 +69,14 @@ def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 8192) -> Non
         raise RuntimeError(f"synth_stream_copy rc={rc}")
 
 
-def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 8192) -> None:
-    """Plain read-only streaming kernel over src (yardstick for the achievable HBM read rate)."""
+def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 8192, wide: bool = False) -> None:
+    """Plain read-only streaming kernel over src (yardstick for the achievable HBM read rate).
+    wide: 1024-thread workgroups on contiguous 256 KiB chunks with 16 loads per lane in flight."""
     assert src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.dtype == torch.int64 and sink.numel() >= 1
     nbytes = src.numel() * src.element_size()
-    assert nbytes % 16 == 0
-    rc = lib().synth_stream_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()), blocks,
-                                 ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert nbytes % (262144 if wide else 16) == 0
+    fn = lib().synth_stream_read_wide if wide else lib().synth_stream_read
+    rc = fn(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()), blocks,
+            ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if rc != 0:
-        raise RuntimeError(f"synth_stream_read rc={rc}")
+        raise RuntimeError(f"stream_read rc={rc}")

@@ -55,7 +55,32 @@ def test_every_tile_width(Kp):
     check(c, R)
 
 
-@pytest.mark.parametrize("Kp,N,B", [(128, 40, 9), (64, 33, 13), (256, 9, 5)])
+@pytest.mark.parametrize("Kp,N", [(16, 4), (32, 4), (64, 4), (128, 3), (256, 3), (512, 2), (1024, 2)])
+def test_many_problems_one_wave_each(Kp, N):
+    # 2048 problems and more run one wavefront per problem; fewer run a workgroup per problem
+    B = 2048 + 3
+    c = torch.empty((B, N, Kp), dtype=torch.int64, device=DEV)
+    R = torch.empty((B, N - 1, Kp, Kp), dtype=torch.int64, device=DEV)
+    device_fill.fill_random_chain(c, R, 5000, 1000, 5000)
+    arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+    vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+    total = torch.zeros(B, dtype=torch.int64, device=DEV)
+    last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    plan = torch.full((B, N), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(B, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, vfinal, total, last)
+    rh.rh_backtrack(B, N, Kp, arg, last, plan)
+    torch.cuda.synchronize()
+    sel = list(range(B)) if Kp <= 128 else [0, 1, 2, 3, 64, 999, 2047, 2048, 2049, 2050]
+    idx = torch.tensor(sel, device=DEV)
+    o_arg, o_vf, o_total, o_last = oracle.chain(c[idx].cpu().numpy(), R[idx].cpu().numpy(), nthreads=8)
+    assert np.array_equal(total[idx].cpu().numpy(), o_total) and np.array_equal(last[idx].cpu().numpy(), o_last)
+    assert np.array_equal(vfinal[idx].cpu().numpy(), o_vf)
+    assert np.array_equal(arg[idx].cpu().numpy().view(np.uint16), o_arg)
+    assert np.array_equal(plan[idx].cpu().numpy(), oracle.backtrack(o_arg, o_last))
+
+
+@pytest.mark.parametrize("Kp,N,B", [(128, 40, 9), (64, 33, 13), (256, 9, 5), (128, 6, 700), (256, 5, 600),
+                                     (32, 9, 100), (512, 4, 3), (1024, 3, 2)])
 def test_longer_chains(Kp, N, B):
     c, R = syn.random_chain_batch(range(100, 100 + B), N, Kp, 1_000_000, 10_000_000, Kp=Kp)
     check(c, R)
