@@ -4,10 +4,12 @@
 // one kernel launch per s because dp[s] needs all of dp[s-1].
 //
 // A workgroup owns 64 consecutive j (one per lane); its 16 waves split the i range into
-// contiguous chunks.  i is uniform across a wave, so (dp[s-1][i], P(i)) -- stored interleaved
-// in the workspace -- arrive through scalar loads and a cell is sub / max / min on the vector
-// ALU with no cross-lane traffic.  The 16 partial minima per j are merged through LDS in
-// chunk order, which keeps the lowest i on ties.
+// contiguous chunks.  i is uniform across a wave, so (dp[s-1][i], -P(i)) -- stored interleaved
+// in the workspace -- arrive through scalar loads, eight i at a time, and a cell is add / max /
+// min on the vector ALU with no cross-lane traffic.  The 16 partial minima per j are merged
+// through LDS in chunk order, which keeps the lowest i on ties.  When there are few problems
+// the i range of a tile is also split over several workgroups, so that the long tiles do not
+// serialise on one CU, and a small second kernel merges the partial minima of each tile.
 #include "kernels.h"
 
 namespace rh {
@@ -19,8 +21,35 @@ constexpr int kJTile = 64;
 constexpr int kWaves = 16;
 constexpr int kScanThreads = 256;
 
-// workspace per problem: two buffers of (dp, P) pairs, L+1 entries each
+// workspace: per problem two buffers of (dp, -P) pairs, L+1 entries each; then, if tiles are split,
+// partial minima [B][tiles][splits][64] (value, index)
 __host__ __device__ inline size_t pairs_per_problem(int32_t L) { return 2 * ((size_t)L + 1); }
+inline int tiles_of(int32_t L) { return (L + 1 + kJTile - 1) / kJTile; }
+
+// Workgroups along i per tile: enough to put about a thousand workgroups on the chip, never
+// less than 256 i per workgroup.
+inline int splits_of(int32_t B, int32_t L) {
+    const int64_t wgs = (int64_t)B * tiles_of(L);
+    int64_t want = wgs >= 1024 ? 1 : (1024 + wgs - 1) / wgs;
+    const int64_t most = ((int64_t)L + 255) / 256;
+    want = want < most ? want : most;
+    want = want < 32 ? want : 32;
+    return (int)(want < 1 ? 1 : want);
+}
+
+struct StageLayout {
+    size_t pairs_bytes, pval_off, pidx_off, total;
+};
+inline StageLayout layout_of(int32_t B, int32_t L) {
+    StageLayout o{};
+    const size_t splits = (size_t)splits_of(B, L), tiles = (size_t)tiles_of(L);
+    o.pairs_bytes = (size_t)B * pairs_per_problem(L) * 16;
+    o.pval_off = (o.pairs_bytes + 255) & ~(size_t)255;
+    const size_t parts = splits > 1 ? (size_t)B * tiles * splits * kJTile : 0;
+    o.pidx_off = o.pval_off + parts * 8;
+    o.total = o.pidx_off + parts * 4;
+    return o;
+}
 
 // P and the s = 1 row.  One workgroup per problem; thread t sums a contiguous slice.
 __global__ void __launch_bounds__(kScanThreads)
@@ -56,76 +85,101 @@ stage_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, ll2* _
     }
     for (int l = lo; l < hi; ++l) {
         run += cs[l];
-        ll2 v; v.x = run; v.y = run;      // dp[1][j] = P(j)
+        ll2 v; v.x = run; v.y = -run;     // dp[1][j] = P(j)
         buf0[l + 1] = v;
         v.x = kInf;
-        buf1[l + 1] = v;                  // P is kept in both buffers
+        buf1[l + 1] = v;                  // -P is kept in both buffers
         ct[l + 1] = 0;
         if (l + 1 == L) bottleneck[(int64_t)p * S] = run;
     }
 }
 
 __global__ void __launch_bounds__(kWaves * 64)
-stage_step_kernel(int32_t L, int32_t S, int32_t s, ll2* __restrict__ ws,
+stage_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, const ll2* __restrict__ prev_all,
+                  ll2* __restrict__ cur_all, int64_t* __restrict__ pval, int32_t* __restrict__ pidx,
                   int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
     __shared__ int64_t pv[kWaves][kJTile];
     __shared__ int32_t pi[kWaves][kJTile];
 
     const int p = blockIdx.y;
+    const int tile = blockIdx.x / splits;
+    const int split = blockIdx.x - tile * splits;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    ll2* base = ws + (size_t)p * pairs_per_problem(L);
-    const ll2* __restrict__ prev = base + (size_t)(s & 1) * (L + 1);     // s-1 odd -> buffer 0
-    ll2* cur = base + (size_t)((s & 1) ^ 1) * (L + 1);
-    // s = 2 reads buffer 0 (written by init), writes buffer 1; s = 3 reads 1, writes 0; ...
-    const int j0 = blockIdx.x * kJTile;          // first j of this tile
+    // prev_all / cur_all: the workspace buffers holding dp[s-1] (read only here) and dp[s]
+    const ll2* __restrict__ prev = prev_all + (size_t)p * pairs_per_problem(L);
+    ll2* __restrict__ cur = cur_all + (size_t)p * pairs_per_problem(L);
+    const int j0 = tile * kJTile;                // first j of this tile
     const int j = j0 + lane;
     const int jhi = j0 + kJTile - 1 < L ? j0 + kJTile - 1 : L;   // largest j of the tile
     if (jhi < s) {
         // no j of this tile can be split into s non-empty stages
-        if (threadIdx.x < kJTile && j <= L) {
+        if (split == 0 && threadIdx.x < kJTile && j <= L) {
             cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = -1;
             ll2 v = cur[j]; v.x = kInf; cur[j] = v;
         }
         return;
     }
-    const int64_t Pj = j <= L ? prev[j].y : 0;
-
-    // i in [s-1, jhi): 16 contiguous chunks
+    // i in [s-1, jhi) goes to `used` workgroups in pieces of wg_chunk (a multiple of 16 * 8)
     const int lo = s - 1;
     const int span = jhi - lo;
-    const int chunk = (span + kWaves - 1) / kWaves;
-    const int ilo = lo + wave * chunk;
+    int wg_chunk = (span + splits - 1) / splits;
+    wg_chunk = (wg_chunk + 127) & ~127;
+    const int used = (span + wg_chunk - 1) / wg_chunk;
+    if (split >= used) return;
+    const int wlo = lo + split * wg_chunk;
+    const int whi = wlo + wg_chunk < jhi ? wlo + wg_chunk : jhi;
+
+    const int64_t negPj = j <= L ? prev[j].y : 0;
+    int64_t Pj = -negPj;
+    asm volatile("" : "+v"(Pj));   // keep "Pj + (-P_i)" one 64-bit add instead of a two-part subtract
+
+    // the workgroup's piece: 16 contiguous chunks, one per wave
+    const int chunk = (whi - wlo + kWaves - 1) / kWaves;
+    const int ilo = wlo + wave * chunk;
     int ihi = ilo + chunk;
-    ihi = ihi < jhi ? ihi : jhi;
+    ihi = ihi < whi ? ihi : whi;
 
     int64_t best = INT64_MAX;
     int32_t besti = -1;
+    constexpr int U = 8;   // pairs fetched per batch of scalar loads
     // i < j0: valid for every lane of the tile
     const int imid = ihi < j0 ? ihi : j0;
-    for (int i = ilo; i < imid; ++i) {
-        const ll2 q = prev[i];                    // uniform address
-        const int64_t tail = Pj - q.y;
-        const int64_t m = q.x > tail ? q.x : tail;
-        const bool lt = m < best;
-        best = lt ? m : best;
-        besti = lt ? i : besti;
+    int i = ilo;
+    for (; i + U <= imid; i += U) {
+        ll2 q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) q[u] = prev[i + u];   // uniform addresses
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t tail = Pj + q[u].y;
+            const int64_t m = q[u].x > tail ? q[u].x : tail;
+            const bool lt = m < best;
+            best = lt ? m : best;
+            besti = lt ? i + u : besti;
+        }
     }
-    // diagonal block: only lanes with i < j take part
-    for (int i = ilo > j0 ? ilo : j0; i < ihi; ++i) {
-        const ll2 q = prev[i];
-        const int64_t tail = Pj - q.y;
-        const int64_t m = q.x > tail ? q.x : tail;
-        const bool lt = (m < best) && (i < j);
-        best = lt ? m : best;
-        besti = lt ? i : besti;
+    // the rest of the chunk, including the diagonal block where only lanes with i < j take part;
+    // reads past ihi stay inside the buffer (index clamped) and are masked out
+    for (; i < ihi; i += U) {
+        ll2 q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) q[u] = prev[i + u < L ? i + u : L];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t tail = Pj + q[u].y;
+            const int64_t m = q[u].x > tail ? q[u].x : tail;
+            const bool lt = (m < best) && (i + u < j) && (i + u < ihi);
+            best = lt ? m : best;
+            besti = lt ? i + u : besti;
+        }
     }
     pv[wave][lane] = best;
     pi[wave][lane] = besti;
     __syncthreads();
-    if (threadIdx.x < kJTile && j <= L) {
-        int64_t b = INT64_MAX;
-        int32_t bi = -1;
+    int64_t b = INT64_MAX;
+    int32_t bi = -1;
+    if (threadIdx.x < kJTile) {
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {        // ascending i: strict < keeps the lowest
             const int64_t x = pv[w][lane];
@@ -134,12 +188,58 @@ stage_step_kernel(int32_t L, int32_t S, int32_t s, ll2* __restrict__ ws,
             b = lt ? x : b;
             bi = lt ? xi : bi;
         }
+    }
+    if (used > 1) {
+        // publish this workgroup's minima; stage_merge_kernel finishes the tile
+        if (threadIdx.x < kJTile) {
+            const size_t slot = (((size_t)p * gridDim.x + blockIdx.x) * kJTile) + lane;   // [p][tile][split][lane]
+            pval[slot] = b;
+            pidx[slot] = bi;
+        }
+        return;
+    }
+    if (threadIdx.x < kJTile && j <= L) {
         const bool ok = j >= s;                   // then i = s-1 < j exists, so bi >= 0
-        ll2 v; v.x = ok ? b : kInf; v.y = Pj;
+        ll2 v; v.x = ok ? b : kInf; v.y = negPj;
         cur[j] = v;
         cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = ok ? bi : -1;
         if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v.x;
     }
+}
+
+// Tiles whose i range went to several workgroups: merge their minima (pieces ascend in i, so
+// strict < keeps the lowest i) and finish dp[s][j], cut[s][j].  Same geometry as the step kernel.
+__global__ void __launch_bounds__(kJTile)
+stage_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, ll2* __restrict__ cur_all,
+                   const int64_t* __restrict__ pval, const int32_t* __restrict__ pidx,
+                   int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+    const int p = blockIdx.y, tile = blockIdx.x, lane = threadIdx.x;
+    const int j0 = tile * kJTile;
+    const int j = j0 + lane;
+    const int jhi = j0 + kJTile - 1 < L ? j0 + kJTile - 1 : L;
+    if (jhi < s) return;
+    const int span = jhi - (s - 1);
+    int wg_chunk = (span + splits - 1) / splits;
+    wg_chunk = (wg_chunk + 127) & ~127;
+    const int used = (span + wg_chunk - 1) / wg_chunk;
+    if (used <= 1 || j > L) return;             // the step kernel finished this tile itself
+    ll2* cur = cur_all + (size_t)p * pairs_per_problem(L);
+    const size_t first = (((size_t)p * gridDim.x + tile) * splits * kJTile) + lane;
+    int64_t b = INT64_MAX;
+    int32_t bi = -1;
+    for (int k = 0; k < used; ++k) {
+        const int64_t x = pval[first + (size_t)k * kJTile];
+        const int32_t xi = pidx[first + (size_t)k * kJTile];
+        const bool lt = x < b && xi >= 0;
+        b = lt ? x : b;
+        bi = lt ? xi : bi;
+    }
+    const bool ok = j >= s;
+    ll2 v = cur[j];                             // keeps -P(j)
+    v.x = ok ? b : kInf;
+    cur[j] = v;
+    cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = ok ? bi : -1;
+    if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v.x;
 }
 
 __global__ void __launch_bounds__(64)
@@ -162,20 +262,34 @@ stage_bounds_kernel(int32_t B, int32_t L, int32_t S, int32_t s_query,
 
 size_t stage_workspace_bytes(int32_t B, int32_t L, int32_t S) {
     (void)S;
-    return (size_t)B * pairs_per_problem(L) * sizeof(ll2);
+    return layout_of(B, L).total;
 }
 
 hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                            int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds,
                            void* workspace, hipStream_t stream) {
     if (B == 0) return hipSuccess;
-    ll2* ws = static_cast<ll2*>(workspace);
+    const StageLayout lay = layout_of(B, L);
+    const int splits = splits_of(B, L), tiles = tiles_of(L);
+    char* wsb = static_cast<char*>(workspace);
+    ll2* ws = reinterpret_cast<ll2*>(wsb);
+    int64_t* pval = reinterpret_cast<int64_t*>(wsb + lay.pval_off);
+    int32_t* pidx = reinterpret_cast<int32_t*>(wsb + lay.pidx_off);
     hipLaunchKernelGGL(stage_init_kernel, dim3(B), dim3(kScanThreads), 0, stream, L, S, seg_cost, ws,
                        bottleneck, cut);
-    const dim3 grid((unsigned)((L + 1 + kJTile - 1) / kJTile), (unsigned)B);
-    for (int s = 2; s <= S; ++s)
-        hipLaunchKernelGGL(stage_step_kernel, grid, dim3(kWaves * 64), 0, stream, L, S, s, ws,
-                           bottleneck, cut);
+    const dim3 grid((unsigned)(tiles * splits), (unsigned)B);
+    const dim3 merge_grid((unsigned)tiles, (unsigned)B);
+    for (int s = 2; s <= S; ++s) {
+        // dp[s-1] lives in buffer (s-1) odd ? 0 : 1 of each problem: s = 2 reads buffer 0, which the
+        // init kernel wrote, and writes buffer 1; s = 3 reads 1, writes 0; ...
+        const ll2* prev_all = ws + (size_t)(s & 1) * (L + 1);
+        ll2* cur_all = ws + (size_t)((s & 1) ^ 1) * (L + 1);
+        hipLaunchKernelGGL(stage_step_kernel, grid, dim3(kWaves * 64), 0, stream, L, S, s, splits, prev_all,
+                           cur_all, pval, pidx, bottleneck, cut);
+        if (splits > 1)
+            hipLaunchKernelGGL(stage_merge_kernel, merge_grid, dim3(kJTile), 0, stream, L, S, s, splits,
+                               cur_all, pval, pidx, bottleneck, cut);
+    }
     if (s_query > 0 && bounds != nullptr)
         hipLaunchKernelGGL(stage_bounds_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, B, L, S,
                            s_query, cut, bounds);

@@ -27,7 +27,10 @@ def test_host_only_calls():
     assert rh.rh_version() >= 100
     assert rh.strerror(0) == "ok" and "NULL" in rh.strerror(-1)
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 4096, 512, 128) == 0
-    assert rh.rh_workspace_size(rh.WS_STAGE_DP, 2, 4096, 64) == 2 * 2 * 4097 * 16
+    pairs = 2 * 4097 * 16                      # two buffers of 16-byte pairs per problem
+    assert rh.rh_workspace_size(rh.WS_STAGE_DP, 2, 4096, 64) >= 2 * pairs
+    assert rh.rh_workspace_size(rh.WS_STAGE_DP, 64, 4096, 64) == 64 * pairs     # many problems: no split tiles
+    assert rh.rh_workspace_size(rh.WS_STAGE_DP, 1, 10, 11) == 0                 # S > L is not a valid call
     # argument errors are found before anything touches a device
     L = rh.lib()
     assert L.rh_minplus_chain(1, 2, 100, None, 0, None, 0, None, None, None, None, None, 0, None) == -3
