@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--problems", type=int, default=0, help="override B (debugging only; 0 = the workload's 4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-rows", action="store_true")
+    ap.add_argument("--rows-only", action="store_true",
+                    help="only time the other rows of the path (for profiling them); prints their JSON")
     return ap.parse_args()
 
 
@@ -109,6 +111,10 @@ def main():
         sys.exit(2)
     rh.lib()
     dev = "cuda:0"
+    if args.rows_only:
+        from paper_2302_08141_amd import other_rows
+        print(json.dumps({"other_rows": other_rows.measure(dev)}))
+        return
     w = syn.BATCHED_CHAINS
     B, N, K = (args.problems or w["B"]), w["N"], w["K"]
 
