@@ -109,10 +109,11 @@ def rh_build_reshard(mesh: Mesh, n_edges: int, Kp: int, K, out_spec, in_spec, di
 
 
 def rh_minplus_chain(B: int, N: int, Kp: int, c, c_batch_stride: int, R, R_batch_stride: int, arg, vfinal,
-                     total, last, workspace=None, workspace_bytes: int = 0):
+                     total, last, workspace=None):
     """c int64[B][N][Kp]; R int64[B][N-1][Kp][Kp] (or one shared table with R_batch_stride 0);
     arg: int16-typed storage for uint16[B][N-1][Kp] (out); vfinal int64[B][Kp] or None; total int64[B];
-    last int32[B]."""
+    last int32[B]; workspace: optional uint8 CUDA tensor of rh_workspace_size(WS_MINPLUS_CHAIN, B, N, Kp) bytes."""
+    workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     b, n, k = max(B, 0), max(N, 1), max(Kp, 0)
     span = lambda stride, one: (b - 1) * stride + one if b > 0 else 0     # elements the batch touches
     _check(lib().rh_minplus_chain(B, N, Kp, _ptr(c, torch.int64, "c", span(c_batch_stride, n * k)),

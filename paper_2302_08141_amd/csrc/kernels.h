@@ -19,6 +19,12 @@ hipError_t launch_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int6
                         const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
                         int64_t* total, int32_t* last, hipStream_t stream);
 
+// Few long chains of wide tables: eight workgroups per problem (needs a workspace).
+size_t gang_workspace_bytes(int32_t B, int32_t N, int32_t Kp);   // 0 = not applicable to these sizes
+hipError_t launch_chain_gang(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs,
+                             const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
+                             int64_t* total, int32_t* last, void* workspace, hipStream_t stream);
+
 hipError_t launch_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
                             const int32_t* last, int32_t* plan, hipStream_t stream);
 

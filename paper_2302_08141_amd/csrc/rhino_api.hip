@@ -55,8 +55,6 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t
                      const int64_t* R, int64_t R_batch_stride, uint16_t* arg, int64_t* vfinal,
                      int64_t* total, int32_t* last, void* workspace, size_t workspace_bytes,
                      void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     if (B < 0 || N < 1 || N > RH_NMAX) return RH_ERR_SHAPE;
     if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
     if (B == 0) return RH_OK;
@@ -70,6 +68,12 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t
         return RH_ERR_SHAPE;
     if ((arg && (reinterpret_cast<uintptr_t>(arg) & 3u)) || (vfinal && !aligned16(vfinal)))
         return RH_ERR_SHAPE;
+    if (workspace != nullptr && (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
+        return RH_ERR_WORKSPACE;
+    const size_t gang = rh::gang_workspace_bytes(B, N, Kp);
+    if (gang != 0 && workspace != nullptr && workspace_bytes >= gang)
+        return from_hip(rh::launch_chain_gang(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal,
+                                              total, last, workspace, static_cast<hipStream_t>(stream)));
     return from_hip(rh::launch_chain(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal, total,
                                      last, static_cast<hipStream_t>(stream)));
 }
@@ -99,6 +103,7 @@ int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_
 }
 
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or_S) {
+    if (which == RH_WS_MINPLUS_CHAIN) return rh::gang_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_STAGE_DP) {
         if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);

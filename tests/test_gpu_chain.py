@@ -86,6 +86,43 @@ def test_longer_chains(Kp, N, B):
     check(c, R)
 
 
+@pytest.mark.parametrize("Kp,N,B", [(256, 64, 1), (256, 131, 3), (128, 64, 2), (128, 257, 32), (256, 70, 32)])
+def test_few_long_chains_spread_over_several_workgroups(Kp, N, B):
+    # with a workspace, few long chains of wide tables run eight workgroups per problem
+    need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp)
+    assert need > 0
+    rng = np.random.default_rng(B * 1000 + N)
+    c, R = syn.random_chain_batch(range(40, 40 + B), N, Kp, 1_000_000, 10_000_000)
+    if B > 1:
+        # problem 1: ties everywhere and infeasible entries
+        c[1] = rng.integers(0, 3, size=c[1].shape)
+        R[1] = rng.integers(0, 3, size=R[1].shape)
+        R[1][rng.random(R[1].shape) < 0.4] = INF
+        c[1, N // 2, Kp // 3:] = INF
+    if B > 2:
+        c[2, N // 3, :] = INF                                         # nothing feasible from there on
+    # empty candidate slots: whole rows and columns of R are infeasible, as in tables built from specs
+    c[0, :, Kp - 37:] = INF
+    R[0, :, Kp - 37:, :] = INF
+    R[0, :, :, Kp - 37:] = INF
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R, nthreads=8)
+    dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    for use_ws in (True, False, True):
+        arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+        vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+        total = torch.zeros(B, dtype=torch.int64, device=DEV)
+        last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+        ws = torch.full((need,), 0xAB, dtype=torch.uint8, device=DEV) if use_ws else None   # stale contents
+        rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(total.cpu().numpy(), o_total), use_ws
+        assert np.array_equal(last.cpu().numpy(), o_last)
+        assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+        assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 33, N, Kp) == 0   # too many problems to keep every gang resident
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 63, Kp) == 0 and rh.rh_workspace_size(0, B, N, 64) == 0
+
+
 @pytest.mark.parametrize("Kp", [16, 64, 128])
 def test_ties_ragged_and_infeasible(Kp):
     rng = np.random.default_rng(Kp)

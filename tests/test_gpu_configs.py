@@ -32,13 +32,17 @@ def gpu_reshard(g, n_edges=None):
     return R
 
 
-def gpu_chain(c, R, B, N, Kp, r_stride=None):
+def gpu_chain(c, R, B, N, Kp, r_stride=None, workspace=False):
     arg = torch.empty((B, N - 1, Kp), dtype=torch.int16, device=DEV)
     total = torch.empty(B, dtype=torch.int64, device=DEV)
     last = torch.empty(B, dtype=torch.int32, device=DEV)
     plan = torch.empty((B, N), dtype=torch.int32, device=DEV)
+    ws = None
+    if workspace:
+        ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp), dtype=torch.uint8, device=DEV)
+        assert ws.numel() > 0
     rh.rh_minplus_chain(B, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp if r_stride is None else r_stride, arg, None,
-                        total, last)
+                        total, last, ws)
     rh.rh_backtrack(B, N, Kp, arg, last, plan)
     torch.cuda.synchronize()
     return arg, total, last, plan
@@ -144,11 +148,12 @@ def test_moe_shaped_graph_full_size():
     got = R.cpu().numpy()
     assert np.array_equal(got, want)
     c = dev(g["c"][None])
-    arg, total, last, plan = gpu_chain(c, R, 1, N, Kp)
     o_arg, _, o_total, o_last = oracle.chain(g["c"][None], want[None])
-    assert total.item() == o_total[0] < INF and last.item() == o_last[0]
-    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
-    assert np.array_equal(plan.cpu().numpy(), oracle.backtrack(o_arg, o_last))
+    for workspace in (False, True):                          # one workgroup, then eight, on the one chain
+        arg, total, last, plan = gpu_chain(c, R, 1, N, Kp, workspace=workspace)
+        assert total.item() == o_total[0] < INF and last.item() == o_last[0]
+        assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+        assert np.array_equal(plan.cpu().numpy(), oracle.backtrack(o_arg, o_last))
 
 
 def test_stage_partition_with_per_segment_chains():
