@@ -155,6 +155,38 @@ int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
                  const int32_t* last, int32_t* plan, void* stream);
 
 /*
+ * rh_cone_merge -- join the branches of cones at their roots (Sec. 4.3.2, level 1:
+ * a cone is one root operator with several inputs whose other nodes have one
+ * input each; given the root's strategy the other nodes are optimised by dynamic
+ * programming, and every root strategy is kept for the next level).
+ *
+ * The branches of a cone are chains that end in its root.  Run all branches of all
+ * cones as one rh_minplus_chain batch, each with the root appended as its last
+ * operator with cost 0 (shorter branches padded in front with zero-cost operators
+ * and identity tables: 0 on the diagonal, RH_INF elsewhere); then w = vfinal holds,
+ * per branch b and root strategy r, the branch's best cost given r, and
+ *     table[q][r]    = c_root[q][r] + sum over the branches b of cone q of w[b][r]
+ *     total[q]       = min_r table[q][r],  root_choice[q] = lowest such r
+ *     branch_last[b] = root_choice of b's cone  (the `last` input of rh_backtrack
+ *                      on the branch batch, which then yields every node's strategy)
+ * with sums saturating at RH_INF.
+ *
+ *   n_cones >= 0, n_branches >= 0
+ *   branch_start  [n_cones+1] ascending offsets into the branch batch; the branches
+ *                 of cone q are branch_start[q] .. branch_start[q+1]-1 (offsets
+ *                 outside [0, n_branches] are clamped)
+ *   w             [n_branches][Kp]
+ *   c_root        [n_cones][Kp]
+ *   table         [n_cones][Kp] out, may be NULL
+ *   total         [n_cones] out;  root_choice [n_cones] out
+ *   branch_last   [n_branches] out, may be NULL
+ */
+int rh_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp,
+                  const int32_t* branch_start, const int64_t* w,
+                  const int64_t* c_root, int64_t* table, int64_t* total,
+                  int32_t* root_choice, int32_t* branch_last, void* stream);
+
+/*
  * rh_stage_dp -- balanced pipeline stages on a chain of L segments (Sec. 2.1:
  * stages should balance computation time; Sec. 5.1: stage ids never decrease
  * along an edge; Sec. 5.2: time_per_stage = total / stages is the ideal).

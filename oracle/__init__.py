@@ -94,6 +94,31 @@ def plan_cost(c: np.ndarray, R: np.ndarray, plan: np.ndarray) -> int:
     return int(lib().oracle_plan_cost(ctypes.c_int32(N), ctypes.c_int32(Kp), _p(c), _p(R), _p(plan)))
 
 
+def cone(branches, c_root: np.ndarray):
+    """branches: list of (c[len][Kp], R[len][Kp][Kp]) with the last R the edge into the root; c_root[Kp] ->
+    table[Kp], total, root_choice, [plan per branch]."""
+    _chk(c_root, np.int64, "c_root")
+    Kp = c_root.shape[0]
+    n = len(branches)
+    lens = np.array([b[0].shape[0] for b in branches], dtype=np.int32)
+    for cb, Rb in branches:
+        _chk(cb, np.int64, "branch c"); _chk(Rb, np.int64, "branch R")
+        assert cb.shape[1] == Kp and Rb.shape == (cb.shape[0], Kp, Kp)
+    PP = ctypes.c_void_p * max(n, 1)
+    cps = PP(*[b[0].ctypes.data for b in branches])
+    rps = PP(*[b[1].ctypes.data for b in branches])
+    plans = [np.zeros(int(l), dtype=np.int32) for l in lens]
+    pps = PP(*[p.ctypes.data for p in plans])
+    table = np.zeros(Kp, dtype=np.int64)
+    total = np.zeros(1, dtype=np.int64)
+    choice = np.zeros(1, dtype=np.int32)
+    rc = lib().oracle_cone(ctypes.c_int32(n), ctypes.c_int32(Kp), _p(lens), cps, rps, _p(c_root), _p(table),
+                           _p(total), _p(choice), pps)
+    if rc != 0:
+        raise ValueError(f"oracle_cone rc={rc}")
+    return table, int(total[0]), int(choice[0]), plans
+
+
 def stage_dp(cost: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
     """cost[B][L] -> bottleneck[B][S], cut int32[B][S][L+1], bounds int32[B][s_query+1] or None."""
     _chk(cost, np.int64, "cost")

@@ -138,6 +138,68 @@ int64_t oracle_plan_cost(int32_t N, int32_t Kp, const int64_t *c,
 }
 
 /* ------------------------------------------------------------------ */
+/* Cone: one root operator with several inputs, every other node has   */
+/* exactly one input (Sec. 4.3.2, level 1), i.e. n_br chains ("branches")*/
+/* that end in the root.  For each root strategy r the best strategies  */
+/* of all other nodes are found branch by branch:                       */
+/*   table[r] = c_root[r] + sum_b min over plans of branch b of         */
+/*              ( sum c + sum R along the branch + R_last->root[.][r] ) */
+/* Branch b has len[b] >= 1 operators with tables cb[b] ([len][Kp]) and */
+/* Rb[b] ([len][Kp][Kp], the last table is the edge into the root).     */
+/* branch_plan[b][len[b]] is the plan of branch b for the best root     */
+/* strategy (lowest index on ties, per branch the same tie rule as the  */
+/* chain).                                                              */
+int oracle_cone(int32_t n_br, int32_t Kp, const int32_t *len,
+                const int64_t *const *cb, const int64_t *const *Rb,
+                const int64_t *c_root, int64_t *table, int64_t *total,
+                int32_t *root_choice, int32_t *const *branch_plan)
+{
+    if (n_br < 0 || Kp < 1) return -1;
+    int64_t *w = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
+    int64_t *v = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
+    uint16_t **args = (uint16_t **)malloc(sizeof(uint16_t *) * (size_t)(n_br > 0 ? n_br : 1));
+    for (int r = 0; r < Kp; ++r) table[r] = c_root[r] >= ORC_INF ? ORC_INF : c_root[r];
+    for (int b = 0; b < n_br; ++b) {
+        const int n = len[b];
+        args[b] = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n * Kp);
+        for (int j = 0; j < Kp; ++j) v[j] = cb[b][j] >= ORC_INF ? ORC_INF : cb[b][j];
+        for (int i = 0; i < n; ++i) {
+            const int64_t *Ri = Rb[b] + (size_t)i * Kp * Kp;
+            for (int x = 0; x < Kp; ++x) {
+                int64_t best = sat_add(v[0], Ri[x]);
+                int besta = 0;
+                for (int a = 1; a < Kp; ++a) {
+                    int64_t t = sat_add(v[a], Ri[(size_t)a * Kp + x]);
+                    if (t < best) { best = t; besta = a; }
+                }
+                args[b][(size_t)i * Kp + x] = (uint16_t)besta;
+                /* inside the branch the next operator's own cost is added; the */
+                /* root's cost is added once, outside */
+                w[x] = i + 1 < n ? sat_add(cb[b][(size_t)(i + 1) * Kp + x], best) : best;
+            }
+            memcpy(v, w, sizeof(int64_t) * (size_t)Kp);
+        }
+        for (int r = 0; r < Kp; ++r) table[r] = sat_add(table[r], v[r]);
+    }
+    int64_t best = table[0];
+    int bestr = 0;
+    for (int r = 1; r < Kp; ++r)
+        if (table[r] < best) { best = table[r]; bestr = r; }
+    *total = best;
+    *root_choice = bestr;
+    for (int b = 0; b < n_br; ++b) {
+        int x = bestr;
+        for (int i = len[b] - 1; i >= 0; --i) {
+            x = args[b][(size_t)i * Kp + x];
+            branch_plan[b][i] = x;
+        }
+        free(args[b]);
+    }
+    free(args); free(w); free(v);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Pipeline stages on a chain of L segments.                            */
 /* bottleneck[B][S]: entry s-1 = dp[s][L].  cut[B][S][L+1]: entry       */
 /* [s-1][j] = minimising i (lowest on ties), 0 for s = 1, -1 where      */

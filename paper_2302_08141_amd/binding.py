@@ -55,6 +55,8 @@ def lib():
         L.rh_minplus_chain.argtypes = [i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         L.rh_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp]
         L.rh_stage_dp.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.rh_cone_merge.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.rh_cone_merge.restype = ctypes.c_int
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
         L.rh_workspace_size.restype = sz
         L.rh_check_costs.argtypes = [vp, i64, vp, vp]
@@ -131,6 +133,18 @@ def rh_backtrack(B: int, N: int, Kp: int, arg, last, plan):
     _check(lib().rh_backtrack(B, N, Kp, _ptr(arg, torch.int16, "arg", b * (n - 1) * k),
                               _ptr(last, torch.int32, "last", b), _ptr(plan, torch.int32, "plan", b * n),
                               _stream()), "rh_backtrack")
+
+
+def rh_cone_merge(n_cones: int, n_branches: int, Kp: int, branch_start, w, c_root, table, total, root_choice,
+                  branch_last):
+    """branch_start int32[n_cones+1]; w int64[n_branches][Kp]; c_root int64[n_cones][Kp]; table int64[n_cones][Kp] or
+    None; total int64[n_cones]; root_choice int32[n_cones]; branch_last int32[n_branches] or None."""
+    q, b, k = max(n_cones, 0), max(n_branches, 0), max(Kp, 0)
+    _check(lib().rh_cone_merge(n_cones, n_branches, Kp, _ptr(branch_start, torch.int32, "branch_start", q + 1),
+                               _ptr(w, torch.int64, "w", b * k), _ptr(c_root, torch.int64, "c_root", q * k),
+                               _ptr(table, torch.int64, "table", q * k), _ptr(total, torch.int64, "total", q),
+                               _ptr(root_choice, torch.int32, "root_choice", q),
+                               _ptr(branch_last, torch.int32, "branch_last", b), _stream()), "rh_cone_merge")
 
 
 def rh_workspace_size(which: int, B: int, N_or_L: int, Kp_or_S: int) -> int:

@@ -32,6 +32,10 @@ hipError_t launch_reshard(const Mesh& mesh, int32_t n_edges, int32_t Kp, const i
                           const uint32_t* out_spec, const uint32_t* in_spec, const int64_t* dims,
                           const int32_t* elem_bytes, int64_t* R, hipStream_t stream);
 
+hipError_t launch_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp, const int32_t* branch_start,
+                             const int64_t* w, const int64_t* c_root, int64_t* table, int64_t* total,
+                             int32_t* root_choice, int32_t* branch_last, hipStream_t stream);
+
 size_t stage_workspace_bytes(int32_t B, int32_t L, int32_t S);
 hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                            int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds,

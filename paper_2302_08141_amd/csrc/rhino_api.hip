@@ -87,6 +87,17 @@ int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg, const in
     return from_hip(rh::launch_backtrack(B, N, Kp, arg, last, plan, static_cast<hipStream_t>(stream)));
 }
 
+int rh_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp, const int32_t* branch_start,
+                  const int64_t* w, const int64_t* c_root, int64_t* table, int64_t* total,
+                  int32_t* root_choice, int32_t* branch_last, void* stream) {
+    if (n_cones < 0 || n_branches < 0) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (n_cones == 0) return RH_OK;
+    if (!branch_start || !c_root || !total || !root_choice || (n_branches > 0 && !w)) return RH_ERR_NULL;
+    return from_hip(rh::launch_cone_merge(n_cones, n_branches, Kp, branch_start, w, c_root, table, total,
+                                          root_choice, branch_last, static_cast<hipStream_t>(stream)));
+}
+
 int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_t* bottleneck,
                 int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                 size_t workspace_bytes, void* stream) {

@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 from . import binding as rh
-from .workloads import device_fill, graphs, synthetic as syn
+from .workloads import cones as wc, device_fill, graphs, synthetic as syn
 
 
 def _best_ms(fn, reps=3):
@@ -77,7 +77,35 @@ def _stage_rows(dev):
             "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
 
 
+def _cone_rows(dev, n_cones=1024, K=64):
+    """Cones (one root, up to four chain branches of up to six operators): branch batch through the chain DP,
+    merge at the roots, backtrack every branch."""
+    pk = wc.pack(wc.random_cones(n_cones, K), K)
+    c, R = torch.from_numpy(pk["c"]).to(dev), torch.from_numpy(pk["R"]).to(dev)
+    Bb, N, Kp = pk["c"].shape
+    start, c_root = torch.from_numpy(pk["branch_start"]).to(dev), torch.from_numpy(pk["c_root"]).to(dev)
+    arg = torch.empty((Bb, N - 1, Kp), dtype=torch.int16, device=dev)
+    w = torch.empty((Bb, Kp), dtype=torch.int64, device=dev)
+    tot_b = torch.empty(Bb, dtype=torch.int64, device=dev)
+    last_b = torch.empty(Bb, dtype=torch.int32, device=dev)
+    table = torch.empty((n_cones, Kp), dtype=torch.int64, device=dev)
+    total = torch.empty(n_cones, dtype=torch.int64, device=dev)
+    choice = torch.empty(n_cones, dtype=torch.int32, device=dev)
+    branch_last = torch.empty(Bb, dtype=torch.int32, device=dev)
+    plan = torch.empty((Bb, N), dtype=torch.int32, device=dev)
+
+    def run():
+        rh.rh_minplus_chain(Bb, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, w, tot_b, last_b)
+        rh.rh_cone_merge(n_cones, Bb, Kp, start, w, c_root, table, total, choice, branch_last)
+        rh.rh_backtrack(Bb, N, Kp, arg, branch_last, plan)
+
+    t = _best_ms(run)
+    return {"cones": n_cones, "branches": Bb, "K": K, "ops_per_branch_padded": N, "chain_merge_backtrack_ms": t,
+            "cones_per_s": n_cones / (t * 1e-3)}
+
+
 def measure(dev="cuda:0"):
     return {"moe_shaped_graph": _graph_rows(graphs.moe_chain(), dev),
             "gpt_like_chain": _graph_rows(graphs.gpt_chain(), dev),
-            "stage_partition": _stage_rows(dev)}
+            "stage_partition": _stage_rows(dev),
+            "cones": _cone_rows(dev)}
