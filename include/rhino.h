@@ -187,6 +187,35 @@ int rh_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp,
                   int32_t* root_choice, int32_t* branch_last, void* stream);
 
 /*
+ * rh_mask_replicated, rh_plan_memory -- the memory-constrained search of Sec. 4.4:
+ * sort the parameters by size, mark the k largest, remove the candidates that
+ * replicate a marked parameter, search again, and take the smallest k whose plan
+ * fits the device memory.  The sweep over k is ONE rh_minplus_chain batch: problem t
+ * uses the node costs masked for k = k0 + t and all problems share the edge tables
+ * (R_batch_stride = 0).
+ *
+ * rh_mask_replicated writes those node-cost tables:
+ *     rank(i) = number of operators l with param_bytes[l] > param_bytes[i], or equal and l < i
+ *     c_out[t][i][j] = RH_INF  if param_bytes[i] > 0, repl[i][j] != 0 and rank(i) < k0 + t
+ *                    = c[i][j] otherwise
+ *   1 <= N <= RH_NMAX, n_k >= 0, k0 >= 0
+ *   c [N][Kp]; param_bytes [N] (0 = the operator has no parameter); repl [N][Kp] bytes;
+ *   c_out [n_k][N][Kp] out
+ *
+ * rh_plan_memory adds up what the plans keep per device and picks the first feasible one:
+ *     plan_mem[b] = sum_i mem[i][plan[b][i]]
+ *     *first = smallest b with total[b] < RH_INF and plan_mem[b] <= limit, or -1
+ *   plan [B][N] (from rh_backtrack); mem [N][Kp]; total [B] (from rh_minplus_chain);
+ *   plan_mem [B] out; first [1] out, may be NULL (then total may be NULL too)
+ */
+int rh_mask_replicated(int32_t N, int32_t Kp, int32_t n_k, int32_t k0,
+                       const int64_t* c, const int64_t* param_bytes,
+                       const uint8_t* repl, int64_t* c_out, void* stream);
+int rh_plan_memory(int32_t B, int32_t N, int32_t Kp, const int32_t* plan,
+                   const int64_t* mem, const int64_t* total, int64_t limit,
+                   int64_t* plan_mem, int32_t* first, void* stream);
+
+/*
  * rh_stage_dp -- balanced pipeline stages on a chain of L segments (Sec. 2.1:
  * stages should balance computation time; Sec. 5.1: stage ids never decrease
  * along an edge; Sec. 5.2: time_per_stage = total / stages is the ideal).

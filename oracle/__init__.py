@@ -119,6 +119,24 @@ def cone(branches, c_root: np.ndarray):
     return table, int(total[0]), int(choice[0]), plans
 
 
+def memory_sweep(c, R, param_bytes, repl, mem, limit: int, n_k: int, k0: int = 0):
+    """c[N][Kp], R[N-1][Kp][Kp], param_bytes int64[N], repl uint8[N][Kp], mem int64[N][Kp] ->
+    total[n_k], plan int32[n_k][N], plan_mem[n_k], first (offset of the smallest feasible k, or -1)."""
+    _chk(c, np.int64, "c"); _chk(R, np.int64, "R"); _chk(param_bytes, np.int64, "param_bytes")
+    _chk(repl, np.uint8, "repl"); _chk(mem, np.int64, "mem")
+    N, Kp = c.shape
+    total = np.zeros(n_k, dtype=np.int64)
+    plan = np.zeros((n_k, N), dtype=np.int32)
+    plan_mem = np.zeros(n_k, dtype=np.int64)
+    first = np.zeros(1, dtype=np.int32)
+    rc = lib().oracle_memory_sweep(ctypes.c_int32(N), ctypes.c_int32(Kp), ctypes.c_int32(n_k), ctypes.c_int32(k0),
+                                   _p(c), _p(R), _p(param_bytes), _p(repl), _p(mem), ctypes.c_int64(limit),
+                                   _p(total), _p(plan), _p(plan_mem), _p(first))
+    if rc != 0:
+        raise ValueError(f"oracle_memory_sweep rc={rc}")
+    return total, plan, plan_mem, int(first[0])
+
+
 def stage_dp(cost: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
     """cost[B][L] -> bottleneck[B][S], cut int32[B][S][L+1], bounds int32[B][s_query+1] or None."""
     _chk(cost, np.int64, "cost")

@@ -200,6 +200,56 @@ int oracle_cone(int32_t n_br, int32_t Kp, const int32_t *len,
 }
 
 /* ------------------------------------------------------------------ */
+/* Memory-constrained search (Sec. 4.4).  Parameters are ranked by size, */
+/* largest first (equal sizes: lower operator index first); for          */
+/* k = k0 .. k0+n_k-1 the candidates that replicate one of the k largest */
+/* parameters are removed (cost INF), the chain is solved, and the plan  */
+/* is feasible if it exists and its parameter memory fits the limit.     */
+/*   param_bytes[N]  size of operator i's parameter tensor (0: none)     */
+/*   repl[N][Kp]     1 if candidate j of operator i replicates it        */
+/*   mem[N][Kp]      bytes per device that candidate j keeps for it      */
+/* Outputs per k: total[n_k], plan[n_k][N], plan_mem[n_k]; *first = the  */
+/* smallest offset k-k0 whose plan is feasible, or -1.                   */
+int oracle_memory_sweep(int32_t N, int32_t Kp, int32_t n_k, int32_t k0,
+                        const int64_t *c, const int64_t *R,
+                        const int64_t *param_bytes, const uint8_t *repl,
+                        const int64_t *mem, int64_t limit, int64_t *total,
+                        int32_t *plan, int64_t *plan_mem, int32_t *first)
+{
+    if (N < 1 || Kp < 1 || n_k < 0 || k0 < 0) return -1;
+    int32_t *rank = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    for (int i = 0; i < N; ++i) {
+        int r = 0;
+        for (int l = 0; l < N; ++l)
+            if (param_bytes[l] > param_bytes[i] || (param_bytes[l] == param_bytes[i] && l < i)) ++r;
+        rank[i] = r;
+    }
+    int64_t *cm = (int64_t *)malloc(sizeof(int64_t) * (size_t)N * Kp);
+    uint16_t *arg = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(N > 1 ? N - 1 : 1) * Kp);
+    *first = -1;
+    for (int t = 0; t < n_k; ++t) {
+        const int k = k0 + t;
+        for (int i = 0; i < N; ++i)
+            for (int j = 0; j < Kp; ++j) {
+                const size_t x = (size_t)i * Kp + j;
+                /* only operators that own a parameter can be marked */
+                cm[x] = (rank[i] < k && param_bytes[i] > 0 && repl[x]) ? ORC_INF : c[x];
+            }
+        int32_t last;
+        chain_one(N, Kp, cm, R, arg, NULL, total + t, &last);
+        int32_t *pl = plan + (size_t)t * N;
+        pl[N - 1] = last;
+        for (int i = N - 2; i >= 0; --i) pl[i] = arg[(size_t)i * Kp + pl[i + 1]];
+        int64_t m = 0;
+        for (int i = 0; i < N; ++i) m += mem[(size_t)i * Kp + pl[i]];
+        plan_mem[t] = m;
+        if (*first < 0 && total[t] < ORC_INF && m <= limit) *first = t;
+    }
+    free(rank); free(cm); free(arg);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Pipeline stages on a chain of L segments.                            */
 /* bottleneck[B][S]: entry s-1 = dp[s][L].  cut[B][S][L+1]: entry       */
 /* [s-1][j] = minimising i (lowest on ties), 0 for s = 1, -1 where      */

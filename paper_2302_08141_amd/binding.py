@@ -57,6 +57,9 @@ def lib():
         L.rh_stage_dp.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_cone_merge.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.rh_cone_merge.restype = ctypes.c_int
+        L.rh_mask_replicated.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.rh_plan_memory.argtypes = [i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
+        L.rh_mask_replicated.restype = L.rh_plan_memory.restype = ctypes.c_int
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
         L.rh_workspace_size.restype = sz
         L.rh_check_costs.argtypes = [vp, i64, vp, vp]
@@ -145,6 +148,24 @@ def rh_cone_merge(n_cones: int, n_branches: int, Kp: int, branch_start, w, c_roo
                                _ptr(table, torch.int64, "table", q * k), _ptr(total, torch.int64, "total", q),
                                _ptr(root_choice, torch.int32, "root_choice", q),
                                _ptr(branch_last, torch.int32, "branch_last", b), _stream()), "rh_cone_merge")
+
+
+def rh_mask_replicated(N: int, Kp: int, n_k: int, k0: int, c, param_bytes, repl, c_out):
+    """c int64[N][Kp]; param_bytes int64[N]; repl uint8[N][Kp]; c_out int64[n_k][N][Kp] (out)."""
+    n, k, t = max(N, 0), max(Kp, 0), max(n_k, 0)
+    _check(lib().rh_mask_replicated(N, Kp, n_k, k0, _ptr(c, torch.int64, "c", n * k),
+                                    _ptr(param_bytes, torch.int64, "param_bytes", n),
+                                    _ptr(repl, torch.uint8, "repl", n * k),
+                                    _ptr(c_out, torch.int64, "c_out", t * n * k), _stream()), "rh_mask_replicated")
+
+
+def rh_plan_memory(B: int, N: int, Kp: int, plan, mem, total, limit: int, plan_mem, first):
+    """plan int32[B][N]; mem int64[N][Kp]; total int64[B]; plan_mem int64[B] (out); first int32[1] (out) or None."""
+    b, n, k = max(B, 0), max(N, 0), max(Kp, 0)
+    _check(lib().rh_plan_memory(B, N, Kp, _ptr(plan, torch.int32, "plan", b * n), _ptr(mem, torch.int64, "mem", n * k),
+                                _ptr(total, torch.int64, "total", b), limit,
+                                _ptr(plan_mem, torch.int64, "plan_mem", b), _ptr(first, torch.int32, "first", 1),
+                                _stream()), "rh_plan_memory")
 
 
 def rh_workspace_size(which: int, B: int, N_or_L: int, Kp_or_S: int) -> int:

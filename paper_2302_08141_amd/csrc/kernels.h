@@ -36,6 +36,13 @@ hipError_t launch_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp, co
                              const int64_t* w, const int64_t* c_root, int64_t* table, int64_t* total,
                              int32_t* root_choice, int32_t* branch_last, hipStream_t stream);
 
+hipError_t launch_mask_replicated(int32_t N, int32_t Kp, int32_t n_k, int32_t k0, const int64_t* c,
+                                  const int64_t* param_bytes, const uint8_t* repl, int64_t* c_out,
+                                  hipStream_t stream);
+hipError_t launch_plan_memory(int32_t B, int32_t N, int32_t Kp, const int32_t* plan, const int64_t* mem,
+                              const int64_t* total, int64_t limit, int64_t* plan_mem, int32_t* first,
+                              hipStream_t stream);
+
 size_t stage_workspace_bytes(int32_t B, int32_t L, int32_t S);
 hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                            int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds,

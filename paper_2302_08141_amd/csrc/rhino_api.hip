@@ -98,6 +98,27 @@ int rh_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp, const int32_t
                                           root_choice, branch_last, static_cast<hipStream_t>(stream)));
 }
 
+int rh_mask_replicated(int32_t N, int32_t Kp, int32_t n_k, int32_t k0, const int64_t* c,
+                       const int64_t* param_bytes, const uint8_t* repl, int64_t* c_out, void* stream) {
+    if (N < 1 || N > RH_NMAX || n_k < 0 || k0 < 0) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (n_k == 0) return RH_OK;
+    if (!c || !param_bytes || !repl || !c_out) return RH_ERR_NULL;
+    return from_hip(rh::launch_mask_replicated(N, Kp, n_k, k0, c, param_bytes, repl, c_out,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int rh_plan_memory(int32_t B, int32_t N, int32_t Kp, const int32_t* plan, const int64_t* mem,
+                   const int64_t* total, int64_t limit, int64_t* plan_mem, int32_t* first, void* stream) {
+    if (B < 0 || N < 1 || N > RH_NMAX) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (B > 0 && (!plan || !mem || !plan_mem)) return RH_ERR_NULL;
+    if (first != nullptr && B > 0 && !total) return RH_ERR_NULL;
+    if (B == 0 && first == nullptr) return RH_OK;
+    return from_hip(rh::launch_plan_memory(B, N, Kp, plan, mem, total, limit, plan_mem, first,
+                                           static_cast<hipStream_t>(stream)));
+}
+
 int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_t* bottleneck,
                 int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                 size_t workspace_bytes, void* stream) {

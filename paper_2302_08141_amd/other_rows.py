@@ -29,6 +29,35 @@ def _best_ms(fn, reps=3):
     return best
 
 
+def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
+    """Memory-constrained search on the graph: n_k values of k as one chain batch sharing the edge tables."""
+    N, Kp = g["N"], g["Kp"]
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    c, pb, repl, mem = to(g["c"]), to(g["param_bytes"]), to(g["repl"]), to(g["mem"])
+    cm = torch.empty((n_k, N, Kp), dtype=torch.int64, device=dev)
+    arg = torch.empty((n_k, N - 1, Kp), dtype=torch.int16, device=dev)
+    total = torch.empty(n_k, dtype=torch.int64, device=dev)
+    last = torch.empty(n_k, dtype=torch.int32, device=dev)
+    plan = torch.empty((n_k, N), dtype=torch.int32, device=dev)
+    plan_mem = torch.empty(n_k, dtype=torch.int64, device=dev)
+    first = torch.empty(1, dtype=torch.int32, device=dev)
+    ws_bytes = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, n_k, N, Kp)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+    limit = 64 << 30
+
+    def run():
+        rh.rh_mask_replicated(N, Kp, n_k, k0, c, pb, repl, cm)
+        rh.rh_minplus_chain(n_k, N, Kp, cm, N * Kp, R, 0, arg, None, total, last, ws)
+        rh.rh_backtrack(n_k, N, Kp, arg, last, plan)
+        rh.rh_plan_memory(n_k, N, Kp, plan, mem, total, limit, plan_mem, first)
+
+    t = _best_ms(run, reps=2)
+    cells = n_k * (N - 1) * Kp * Kp
+    return {"k_values": n_k, "k0": k0, "limit_bytes": limit, "first_feasible_offset": int(first.item()),
+            "sweep_ms": t, "cells_per_s": cells / (t * 1e-3),
+            "shared_table_gbps": cells * 8 / (t * 1e-3) / 1e9}
+
+
 def _graph_rows(g, dev):
     N, Kp = g["N"], g["Kp"]
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -47,7 +76,8 @@ def _graph_rows(g, dev):
                                                    ws))
     t_back = _best_ms(lambda: rh.rh_backtrack(1, N, Kp, arg, last, plan))
     cells = (N - 1) * Kp * Kp
-    return {"N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
+    extra = {"memory_sweep": _memory_sweep_rows(g, R, dev)} if Kp == 256 else {}
+    return {**extra, "N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
             "reshard_ms": t_build, "reshard_write_gbps": cells * 8 / (t_build * 1e-3) / 1e9,
             "chain_workgroups_per_problem": 8 if ws_bytes else 1,
             "chain_ms": t_chain, "chain_cells_per_s": cells / (t_chain * 1e-3),

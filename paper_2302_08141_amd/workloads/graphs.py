@@ -40,6 +40,7 @@ class Op:
     partial_in: object        # None: partial output impossible; "P": passes through; (dim, lgdiv): split input dim
     flops: int
     bytes: int                # bytes the operator touches when not sharded (inputs + outputs + weights)
+    weight_bytes: int = 0     # size of the operator's parameter tensor (0: none)
 
 
 def elementwise(name, dims, eb, linear=False, n_inputs=1):
@@ -58,7 +59,7 @@ def matmul(name, in_dims, out_dims, eb, k, n, dim_map=None, partial_in=None):
     if partial_in is None:
         partial_in = (last_in, 0)
     return Op(name, in_dims, out_dims, dim_map, partial_in, 2 * rows * k * n,
-              (int(np.prod(in_dims)) + int(np.prod(out_dims)) + k * n) * eb)
+              (int(np.prod(in_dims)) + int(np.prod(out_dims)) + k * n) * eb, weight_bytes=k * n * eb)
 
 
 def pad4(dims):
@@ -99,26 +100,48 @@ def _input_option(op: Op, opt):
     return ("R",) if d_in is None else ("S", d_in, opt[2])
 
 
+def _shards_weight(op: Op, opt) -> bool:
+    """Does this output option split the operator's parameter tensor along the axis?  A split output dim that
+    the input does not carry is a parameter dim (column split); a partial output comes from splitting the
+    contracted dim of input and parameter (row split)."""
+    if opt[0] == "P":
+        return isinstance(op.partial_in, tuple)
+    return opt[0] == "S" and op.dim_map.get(opt[1], None) is None
+
+
 def build_chain(ops, opts, mesh, peak_flop_per_ns, hbm_bytes_per_ns, Kp, eb):
-    """-> dict with K, out_spec, in_spec (uint32[N][Kp]), dims (int64[N-1][4]), elem_bytes, c (int64[N][Kp])."""
+    """-> dict with K, out_spec, in_spec (uint32[N][Kp]), dims (int64[N-1][4]), elem_bytes, c (int64[N][Kp]),
+    and for the memory-constrained search param_bytes (int64[N]), repl (uint8[N][Kp]: the strategy keeps a full
+    copy of the parameter), mem (int64[N][Kp]: parameter bytes per device)."""
     N, no = len(ops), len(opts)
     assert no * no <= Kp
     out_spec = np.full((N, Kp), sp.EMPTY, dtype=np.uint32)
     in_spec = np.full((N, Kp), sp.EMPTY, dtype=np.uint32)
     c = np.full((N, Kp), INF, dtype=np.int64)
+    repl = np.zeros((N, Kp), dtype=np.uint8)
+    mem = np.zeros((N, Kp), dtype=np.int64)
+    param_bytes = np.array([op.weight_bytes for op in ops], dtype=np.int64)
     cache = {}
     for i, op in enumerate(ops):
         key = (op.in_dims, op.out_dims, tuple(sorted(op.dim_map.items(), key=str)), str(op.partial_in), op.flops,
-               op.bytes)
+               op.bytes, op.weight_bytes)
         if key not in cache:
             o_row = np.full(Kp, sp.EMPTY, dtype=np.uint32)
             i_row = np.full(Kp, sp.EMPTY, dtype=np.uint32)
             c_row = np.full(Kp, INF, dtype=np.int64)
+            r_row = np.zeros(Kp, dtype=np.uint8)
+            m_row = np.zeros(Kp, dtype=np.int64)
             for j0, a0 in enumerate(opts):
                 for j1, a1 in enumerate(opts):
                     j = j0 * no + j1
                     ow = sp.word(_byte(a0), _byte(a1))
                     o_row[j] = ow
+                    wshards = 1
+                    for x, a in enumerate((a0, a1)):
+                        if _shards_weight(op, a):
+                            wshards *= mesh[x]
+                    r_row[j] = 1 if (op.weight_bytes > 0 and wshards == 1) else 0
+                    m_row[j] = op.weight_bytes // wshards
                     b0, b1 = _input_option(op, a0), _input_option(op, a1)
                     if b0 is None or b1 is None:
                         continue                      # in_spec stays EMPTY: the operator cannot do this
@@ -132,13 +155,14 @@ def build_chain(ops, opts, mesh, peak_flop_per_ns, hbm_bytes_per_ns, Kp, eb):
                             shards *= mesh[x]
                     cost = op.flops // shards // peak_flop_per_ns + op.bytes // shards // hbm_bytes_per_ns
                     c_row[j] = min(cost, COST_CAP)
-            cache[key] = (o_row, i_row, c_row)
-        out_spec[i], in_spec[i], c[i] = cache[key]
+            cache[key] = (o_row, i_row, c_row, r_row, m_row)
+        out_spec[i], in_spec[i], c[i], repl[i], mem[i] = cache[key]
     for i in range(N - 1):
         assert pad4(ops[i].out_dims) == pad4(ops[i + 1].in_dims), (ops[i].name, ops[i + 1].name)
     dims = np.array([pad4(op.out_dims) for op in ops[:-1]], dtype=np.int64).reshape(N - 1, 4)
     return dict(N=N, Kp=Kp, K=np.full(N, no * no, dtype=np.int32), out_spec=out_spec, in_spec=in_spec, dims=dims,
-                elem_bytes=np.full(N - 1, eb, dtype=np.int32), c=c, names=[op.name for op in ops], mesh=tuple(mesh))
+                elem_bytes=np.full(N - 1, eb, dtype=np.int32), c=c, names=[op.name for op in ops], mesh=tuple(mesh),
+                param_bytes=param_bytes, repl=repl, mem=mem)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -209,28 +233,31 @@ def moe_layer_ops(b, s, h, nh, E, eb):
 
     fwd = [
         aux("ln1", act, linear=False),
-        Op("qkv", act, qkv, {0: 0, 1: 1, 2: None, 3: None}, (2, 0), 2 * b * s * h * 3 * h, (4 * n_act + 3 * h * h) * eb),
+        Op("qkv", act, qkv, {0: 0, 1: 1, 2: None, 3: None}, (2, 0), 2 * b * s * h * 3 * h, (4 * n_act + 3 * h * h) * eb,
+           weight_bytes=3 * h * h * eb),
         aux("qkv_bias", qkv),
         Op("score", qkv, sc, {0: 0, 1: 2, 2: 1, 3: 1}, (3, 0), 2 * b * nh * s * s * hd, (3 * n_act + b * nh * s * s) * eb),
         aux("softmax", sc, linear=False),
         aux("attn_dropout", sc),
         Op("av", sc, heads, {0: 0, 1: 3, 2: 1, 3: None}, (3, 0), 2 * b * nh * s * s * hd, (b * nh * s * s + 2 * n_act) * eb),
         aux("merge_heads", heads),
-        Op("proj", heads, act, {0: 0, 1: 1, 2: None, 3: None}, (2, 0), 2 * b * s * h * h, (2 * n_act + h * h) * eb),
+        Op("proj", heads, act, {0: 0, 1: 1, 2: None, 3: None}, (2, 0), 2 * b * s * h * h, (2 * n_act + h * h) * eb,
+           weight_bytes=h * h * eb),
         aux("proj_bias", act),
         elementwise("add1", act, eb, linear=True, n_inputs=2),
         aux("ln2", act, linear=False),
-        Op("gate", act, gate, {0: 0, 1: 1, 2: None, 3: None}, (2, 0), 2 * b * s * h * E, (n_act + b * s * E + h * E) * eb),
+        Op("gate", act, gate, {0: 0, 1: 1, 2: None, 3: None}, (2, 0), 2 * b * s * h * E, (n_act + b * s * E + h * E) * eb,
+           weight_bytes=h * E * eb),
         aux("gate_softmax", gate, linear=False),
         # routing: the gate scores choose where tokens go; as a chain operator it turns [b, s, E] into [G, E, C, H]
         Op("dispatch", gate, disp, {0: 0, 1: 2, 2: None, 3: None}, None, 2 * b * E * C * h, (n_act + b * E * C * h) * eb),
         aux("dispatch_cast", disp),
         Op("expert_fc1", disp, eff, {0: 0, 1: 1, 2: 2, 3: None}, (3, 0), 2 * b * E * C * h * 4 * h,
-           (5 * b * E * C * h + E * 4 * h * h) * eb),
+           (5 * b * E * C * h + E * 4 * h * h) * eb, weight_bytes=E * 4 * h * h * eb),
         aux("expert_bias1", eff),
         aux("expert_act", eff, linear=False),
         Op("expert_fc2", eff, disp, {0: 0, 1: 1, 2: 2, 3: None}, (3, 0), 2 * b * E * C * h * 4 * h,
-           (5 * b * E * C * h + E * 4 * h * h) * eb),
+           (5 * b * E * C * h + E * 4 * h * h) * eb, weight_bytes=E * 4 * h * h * eb),
         aux("expert_bias2", disp),
         Op("combine", disp, act, {0: 0, 1: None, 2: 3, 3: None}, (1, 0), 2 * b * E * C * h, (n_act + b * E * C * h) * eb),
         aux("combine_cast", act),
