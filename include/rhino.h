@@ -240,8 +240,37 @@ int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                 int32_t* bounds, void* workspace, size_t workspace_bytes,
                 void* stream);
 
+/*
+ * rh_stage_dp_window -- the same partition for exactly S stages, with the transfer at a
+ * stage boundary and the bound tightening of Sec. 5.2.  Sec. 5.1: a tensor that crosses a
+ * stage boundary is communicated; Sec. 5.2: with time_per_stage = total / S an operator may
+ * only sit in a stage within a tolerance eps of the one perfect balance gives it.  On a chain
+ * the accumulated time of the segments before l is both its earliest and its latest start, so
+ *     stage [i, j) takes P(j) - P(i) + (i > 0 ? xfer[i] : 0)
+ *     segment l may sit in stage t only if
+ *         floor(P(l)/tps - eps) <= t <= ceil(P(l)/tps + eps),   tps = P(L)/S, eps = eps_num/eps_den
+ *     dp[1][j] = P(j);  dp[s][j] = min over allowed i of max(dp[s-1][i], P(j) - P(i) + xfer[i])
+ * lowest i on ties.  The bounds prune the search to a band around the balanced cuts.
+ *
+ *   B >= 0, 1 <= S <= L <= 65536, S <= 1024; cost[l], xfer[i] in [0, 2^36)
+ *   seg_cost    [B][L]
+ *   xfer        [B][L+1] time to pass the tensor that crosses a boundary placed before
+ *               segment i (entries 0 and L unused); NULL = no transfer time
+ *   eps_num, eps_den   tolerance as a fraction, 1 <= eps_den <= 2^20; eps_num < 0 = no bounds
+ *   bottleneck  [B] out, dp[S][L], RH_INF if the bounds allow no split into S stages
+ *   cut         [B][S][L+1] out, minimising i per (s, j), -1 where none
+ *   bounds      [B][S+1] out (stage t = segments [bounds[t-1], bounds[t])), all -1 if there
+ *               is no split; may be NULL
+ *   workspace   rh_workspace_size(RH_WS_STAGE_DP_WINDOW, B, L, S) bytes, 256-byte aligned
+ */
+int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
+                       const int64_t* xfer, int64_t eps_num, int64_t eps_den,
+                       int64_t* bottleneck, int32_t* cut, int32_t* bounds,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 #define RH_WS_MINPLUS_CHAIN 0
 #define RH_WS_STAGE_DP 1
+#define RH_WS_STAGE_DP_WINDOW 2
 /* Bytes of workspace the call `which` needs for these sizes (0 if none or
  * if the sizes are invalid). */
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,

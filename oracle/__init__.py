@@ -153,6 +153,24 @@ def stage_dp(cost: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
     return bott, cut, bounds
 
 
+def stage_window(cost: np.ndarray, d: int, xfer=None, eps_num: int = -1, eps_den: int = 1):
+    """cost[B][L], xfer[B][L+1] or None -> bottleneck[B], cut int32[B][d][L+1], bounds int32[B][d+1]."""
+    _chk(cost, np.int64, "cost")
+    B, L = cost.shape
+    if xfer is not None:
+        _chk(xfer, np.int64, "xfer")
+        assert xfer.shape == (B, L + 1)
+    bott = np.zeros(B, dtype=np.int64)
+    cut = np.zeros((B, d, L + 1), dtype=np.int32)
+    bounds = np.zeros((B, d + 1), dtype=np.int32)
+    rc = lib().oracle_stage_window(ctypes.c_int32(B), ctypes.c_int32(L), ctypes.c_int32(d), _p(cost),
+                                   _p(xfer) if xfer is not None else None, ctypes.c_int64(eps_num),
+                                   ctypes.c_int64(eps_den), _p(bott), _p(cut), _p(bounds))
+    if rc != 0:
+        raise ValueError(f"oracle_stage_window rc={rc}")
+    return bott, cut, bounds
+
+
 def build_reshard(m, bw_bytes_per_us, alpha_ns, K: np.ndarray, out_spec: np.ndarray,
                   in_spec: np.ndarray, dims: np.ndarray, elem_bytes: np.ndarray) -> np.ndarray:
     """Specs uint32[n_edges+1][Kp], dims int64[n_edges][4], elem_bytes int32[n_edges],

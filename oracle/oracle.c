@@ -307,6 +307,96 @@ int oracle_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t *cost,
 }
 
 /* ------------------------------------------------------------------ */
+/* Pipeline stages with boundary transfers and bound tightening         */
+/* (Sec. 5.1: a tensor that crosses a stage boundary is communicated;   */
+/* Sec. 5.2: every operator must sit within a tolerance eps of the stage */
+/* that perfect balance would give it).  On a chain of L segments split  */
+/* into exactly d stages, with time_per_stage = P(L)/d:                  */
+/*   stage t = segments [i, j) takes P(j) - P(i) + (i > 0 ? xfer[i] : 0) */
+/*   segment l may sit in stage t only if                                */
+/*       floor(P(l)/tps - eps) <= t <= ceil(P(l)/tps + eps)              */
+/*   (the accumulated time of the segments before l is both its earliest */
+/*   and, on a chain, its latest start), eps = eps_num/eps_den >= 0;     */
+/*   eps_num < 0 switches the bounds off.                                */
+/* dp[1][j] = P(j); dp[s][j] = min over allowed i of                     */
+/*   max(dp[s-1][i], P(j) - P(i) + xfer[i]), lowest i on ties.           */
+/* bottleneck[p] = dp[d][L] (INF if the bounds allow no split);          */
+/* cut[p][s-1][j] = minimising i or -1; bounds[p][0..d] or all -1.       */
+static int64_t floor_div128(__int128 a, __int128 b) { /* b > 0 */
+    __int128 q = a / b;
+    if ((a % b != 0) && (a < 0)) --q;
+    return (int64_t)q;
+}
+
+int oracle_stage_window(int32_t B, int32_t L, int32_t d, const int64_t *cost,
+                        const int64_t *xfer, int64_t eps_num, int64_t eps_den,
+                        int64_t *bottleneck, int32_t *cut, int32_t *bounds)
+{
+    if (B < 0 || L < 1 || d < 1 || d > L || eps_den < 1) return -1;
+    for (int p = 0; p < B; ++p) {
+        const int64_t *cs = cost + (size_t)p * L;
+        const int64_t *xf = xfer ? xfer + (size_t)p * (L + 1) : NULL;
+        int32_t *ct = cut + (size_t)p * d * (L + 1);
+        int64_t *P = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        int32_t *lo = (int32_t *)malloc(sizeof(int32_t) * (size_t)L);
+        int32_t *hi = (int32_t *)malloc(sizeof(int32_t) * (size_t)L);
+        int64_t *prev = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        int64_t *cur = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        P[0] = 0;
+        for (int l = 0; l < L; ++l) P[l + 1] = P[l] + cs[l];
+        for (int l = 0; l < L; ++l) {
+            lo[l] = 0; hi[l] = d - 1;
+            if (eps_num >= 0 && P[L] > 0) {
+                /* P(l)/tps -+ eps = (P(l)*d*den -+ num*P(L)) / (P(L)*den) */
+                __int128 x = (__int128)P[l] * d * eps_den, e = (__int128)eps_num * P[L];
+                __int128 den = (__int128)P[L] * eps_den;
+                int64_t f = floor_div128(x - e, den);
+                int64_t c = -floor_div128(-(x + e), den);
+                lo[l] = (int32_t)(f < 0 ? 0 : (f > d - 1 ? d - 1 : f));
+                hi[l] = (int32_t)(c > d - 1 ? d - 1 : (c < 0 ? 0 : c));
+                if (f > d - 1) lo[l] = d;          /* no stage is late enough: never allowed */
+            }
+        }
+        for (int j = 0; j <= L; ++j) {
+            /* one stage so far (stage 0 = segments [0, j)) */
+            int ok = j >= 1 && lo[j - 1] <= 0;
+            prev[j] = ok ? P[j] : ORC_INF;
+            ct[j] = ok ? 0 : -1;
+        }
+        for (int s = 2; s <= d; ++s) {
+            int32_t *cts = ct + (size_t)(s - 1) * (L + 1);
+            for (int j = 0; j <= L; ++j) {
+                int64_t best = ORC_INF;
+                int besti = -1;
+                if (j >= s && lo[j - 1] <= s - 1) {
+                    for (int i = s - 1; i < j; ++i) {
+                        if (hi[i] < s - 1 || prev[i] >= ORC_INF) continue;
+                        int64_t t = P[j] - P[i] + (xf ? xf[i] : 0);
+                        int64_t m = prev[i] > t ? prev[i] : t;
+                        if (m < best) { best = m; besti = i; }
+                    }
+                }
+                cur[j] = besti < 0 ? ORC_INF : best;
+                cts[j] = besti;
+            }
+            int64_t *t = prev; prev = cur; cur = t;
+        }
+        bottleneck[p] = prev[L];
+        if (bounds) {
+            int32_t *bd = bounds + (size_t)p * (d + 1);
+            if (prev[L] >= ORC_INF) {
+                for (int t = 0; t <= d; ++t) bd[t] = -1;
+            } else {
+                bd[d] = L;
+                for (int t = d; t >= 1; --t) bd[t - 1] = ct[(size_t)(t - 1) * (L + 1) + bd[t]];
+            }
+        }
+        free(P); free(lo); free(hi); free(prev); free(cur);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Sharding specs.  One byte per mesh axis inside a 32-bit word         */
 /* (axis 0 = bits 0..7, axis 1 = bits 8..15):                           */
 /*   bits 0..1 state: 0 replicate, 1 split, 2 partial (3 = invalid)     */

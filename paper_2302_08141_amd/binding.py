@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "librhino.so")
 
 INF = 1 << 52
 KMIN, KMAX, NMAX = 16, 1024, 16384
-WS_MINPLUS_CHAIN, WS_STAGE_DP = 0, 1
+WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW = 0, 1, 2
 
 
 class RhinoError(RuntimeError):
@@ -60,6 +60,8 @@ def lib():
         L.rh_mask_replicated.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.rh_plan_memory.argtypes = [i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
         L.rh_mask_replicated.restype = L.rh_plan_memory.restype = ctypes.c_int
+        L.rh_stage_dp_window.argtypes = [i32, i32, i32, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
+        L.rh_stage_dp_window.restype = ctypes.c_int
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
         L.rh_workspace_size.restype = sz
         L.rh_check_costs.argtypes = [vp, i64, vp, vp]
@@ -183,6 +185,21 @@ def rh_stage_dp(B: int, L: int, S: int, seg_cost, bottleneck, cut, s_query: int,
                              _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)), s_query,
                              _ptr(bounds, torch.int32, "bounds", b * (max(s_query, 0) + 1)), ws_ptr, ws_bytes,
                              _stream()), "rh_stage_dp")
+
+
+def rh_stage_dp_window(B: int, L: int, S: int, seg_cost, xfer, eps_num: int, eps_den: int, bottleneck, cut, bounds,
+                       workspace):
+    """seg_cost int64[B][L]; xfer int64[B][L+1] or None; bottleneck int64[B]; cut int32[B][S][L+1];
+    bounds int32[B][S+1] or None; workspace: uint8 tensor of rh_workspace_size(WS_STAGE_DP_WINDOW, B, L, S) bytes."""
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    b, l, s_ = max(B, 0), max(L, 0), max(S, 0)
+    _check(lib().rh_stage_dp_window(B, L, S, _ptr(seg_cost, torch.int64, "seg_cost", b * l),
+                                    _ptr(xfer, torch.int64, "xfer", b * (l + 1)), eps_num, eps_den,
+                                    _ptr(bottleneck, torch.int64, "bottleneck", b),
+                                    _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)),
+                                    _ptr(bounds, torch.int32, "bounds", b * (s_ + 1)), ws_ptr, ws_bytes, _stream()),
+           "rh_stage_dp_window")
 
 
 def rh_check_costs(x, violations):

@@ -48,6 +48,11 @@ hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_c
                            int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds,
                            void* workspace, hipStream_t stream);
 
+size_t stage_window_workspace_bytes(int32_t B, int32_t L, int32_t S);
+hipError_t launch_stage_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, const int64_t* xfer,
+                               int64_t eps_num, int64_t eps_den, int64_t* bottleneck, int32_t* cut,
+                               int32_t* bounds, void* workspace, hipStream_t stream);
+
 hipError_t launch_check_costs(const int64_t* x, int64_t n, int64_t* violations, hipStream_t stream);
 
 }  // namespace rh

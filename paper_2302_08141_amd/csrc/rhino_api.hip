@@ -134,11 +134,28 @@ int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_
                                         static_cast<hipStream_t>(stream)));
 }
 
+int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, const int64_t* xfer,
+                       int64_t eps_num, int64_t eps_den, int64_t* bottleneck, int32_t* cut, int32_t* bounds,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 0 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+    if (eps_den < 1 || eps_den > (1 << 20) || eps_num > ((int64_t)1 << 30)) return RH_ERR_SHAPE;
+    if (B == 0) return RH_OK;
+    if (!seg_cost || !bottleneck || !cut) return RH_ERR_NULL;
+    if (!workspace || !aligned16(workspace)) return RH_ERR_WORKSPACE;
+    if (workspace_bytes < rh::stage_window_workspace_bytes(B, L, S)) return RH_ERR_WORKSPACE;
+    return from_hip(rh::launch_stage_window(B, L, S, seg_cost, xfer, eps_num, eps_den, bottleneck, cut, bounds,
+                                            workspace, static_cast<hipStream_t>(stream)));
+}
+
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or_S) {
     if (which == RH_WS_MINPLUS_CHAIN) return rh::gang_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_STAGE_DP) {
         if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);
+    }
+    if (which == RH_WS_STAGE_DP_WINDOW) {
+        if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
+        return rh::stage_window_workspace_bytes(B, N_or_L, Kp_or_S);
     }
     return 0;
 }

@@ -39,8 +39,9 @@ inline int splits_of(int32_t B, int32_t L) {
 
 struct StageLayout {
     size_t pairs_bytes, pval_off, pidx_off, total;
+    size_t pfull_off, win_off;   // windowed variant only: P(j) per problem, (first i, last j) per stage count
 };
-inline StageLayout layout_of(int32_t B, int32_t L) {
+inline StageLayout layout_of(int32_t B, int32_t L, int32_t S_window = 0) {
     StageLayout o{};
     const size_t splits = (size_t)splits_of(B, L), tiles = (size_t)tiles_of(L);
     o.pairs_bytes = (size_t)B * pairs_per_problem(L) * 16;
@@ -48,6 +49,11 @@ inline StageLayout layout_of(int32_t B, int32_t L) {
     const size_t parts = splits > 1 ? (size_t)B * tiles * splits * kJTile : 0;
     o.pidx_off = o.pval_off + parts * 8;
     o.total = o.pidx_off + parts * 4;
+    if (S_window > 0) {
+        o.pfull_off = (o.total + 255) & ~(size_t)255;
+        o.win_off = o.pfull_off + (size_t)B * ((size_t)L + 1) * 8;
+        o.total = o.win_off + (size_t)B * (size_t)S_window * 2 * 4;
+    }
     return o;
 }
 
@@ -94,10 +100,109 @@ stage_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, ll2* _
     }
 }
 
+// Variant with boundary transfers and bound tightening (Sec. 5.1, 5.2) for exactly S stages:
+// stage [i, j) takes P(j) - P(i) + xfer[i]; segment l may sit in stage t only if
+// floor(P(l)/tps - eps) <= t <= ceil(P(l)/tps + eps), tps = P(L)/S.  Both bounds grow with l, so
+// for the stage count s they reduce to "i >= first_i[s]" and "j <= last_j[s]".
+typedef __int128 i128;
+
+__device__ inline int64_t floor_div(i128 a, i128 b) {   // b > 0
+    i128 q = a / b;
+    if (a % b != 0 && a < 0) --q;
+    return (int64_t)q;
+}
+
+// lowest / highest stage segment l may sit in; lo = S means "none"
+__device__ inline void stage_bounds_of(int64_t Pl, int64_t PL, int32_t S, int64_t num, int64_t den, int32_t* lo,
+                                       int32_t* hi) {
+    *lo = 0;
+    *hi = S - 1;
+    if (num < 0 || PL <= 0) return;
+    const i128 x = (i128)Pl * S * den, e = (i128)num * PL, d = (i128)PL * den;
+    const int64_t f = floor_div(x - e, d), c = -floor_div(-(x + e), d);
+    *lo = (int32_t)(f < 0 ? 0 : (f > S - 1 ? S : f));
+    *hi = (int32_t)(c > S - 1 ? S - 1 : (c < 0 ? 0 : c));
+}
+
+__global__ void __launch_bounds__(kScanThreads)
+stage_window_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, const int64_t* __restrict__ xfer,
+                         int64_t eps_num, int64_t eps_den, ll2* __restrict__ ws, int64_t* __restrict__ pfull,
+                         int32_t* __restrict__ win, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+    __shared__ int64_t part[kScanThreads];
+    const int p = blockIdx.x, t = threadIdx.x;
+    const int64_t* cs = cost + (int64_t)p * L;
+    const int64_t* xf = xfer != nullptr ? xfer + (int64_t)p * (L + 1) : nullptr;
+    ll2* buf0 = ws + (size_t)p * pairs_per_problem(L);
+    ll2* buf1 = buf0 + (L + 1);
+    int64_t* Pp = pfull + (size_t)p * (L + 1);
+    int32_t* wp = win + (size_t)p * S * 2;
+    int32_t* ct = cut + (int64_t)p * S * (L + 1);
+    const int per = (L + kScanThreads - 1) / kScanThreads;
+    const int lo = t * per < L ? t * per : L;
+    const int hi = lo + per < L ? lo + per : L;
+    int64_t sum = 0;
+    for (int l = lo; l < hi; ++l) sum += cs[l];
+    part[t] = sum;
+    __syncthreads();
+    if (t == 0) {
+        int64_t run = 0;
+        for (int k = 0; k < kScanThreads; ++k) {
+            const int64_t x = part[k];
+            part[k] = run;
+            run += x;
+        }
+        part[0] = 0;
+    }
+    __syncthreads();
+    int64_t run = part[t];
+    if (t == 0) Pp[0] = 0;
+    for (int l = lo; l < hi; ++l) {
+        run += cs[l];
+        Pp[l + 1] = run;
+    }
+    __syncthreads();   // P of this problem is complete (written and read by this workgroup only)
+    const int64_t PL = Pp[L];
+    // windows per stage count s = t+1: first_i = min{ i : hi(i) >= s-1 }, last_j = 1 + max{ l : lo(l) <= s-1 }
+    for (int st = t; st < S; st += kScanThreads) {
+        int a = 0, b = L;                       // first i in [0, L] with hi(i) >= st (hi grows with i)
+        while (a < b) {
+            const int m = (a + b) / 2;
+            int32_t l_, h_;
+            stage_bounds_of(Pp[m], PL, S, eps_num, eps_den, &l_, &h_);
+            if (h_ >= st) b = m; else a = m + 1;
+        }
+        wp[2 * st] = a;
+        int a2 = -1, b2 = L - 1;                // last l in [-1, L-1] with lo(l) <= st (lo grows with l)
+        while (a2 < b2) {
+            const int m = (a2 + b2 + 1) / 2;
+            int32_t l_, h_;
+            stage_bounds_of(Pp[m], PL, S, eps_num, eps_den, &l_, &h_);
+            if (l_ <= st) a2 = m; else b2 = m - 1;
+        }
+        wp[2 * st + 1] = a2 + 1;
+    }
+    __syncthreads();
+    const int last_j1 = wp[1];                  // stage count 1: j <= last_j
+    for (int j = t; j <= L; j += kScanThreads) {
+        const int64_t Pj = Pp[j];
+        const bool ok = j >= 1 && j <= last_j1;
+        ll2 v;
+        v.x = ok ? Pj : kInf;                   // dp[1][j]
+        v.y = (xf != nullptr && j >= 1 && j < L ? xf[j] : 0) - Pj;   // -(P(j) - xfer[j])
+        buf0[j] = v;
+        v.x = kInf;
+        buf1[j] = v;
+        ct[j] = ok ? 0 : -1;
+        if (j == L && S == 1) bottleneck[p] = ok ? Pj : kInf;
+    }
+}
+
+template <bool WIN>
 __global__ void __launch_bounds__(kWaves * 64)
 stage_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, const ll2* __restrict__ prev_all,
                   ll2* __restrict__ cur_all, int64_t* __restrict__ pval, int32_t* __restrict__ pidx,
-                  int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+                  int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut,
+                  const int64_t* __restrict__ pfull, const int32_t* __restrict__ win) {
     __shared__ int64_t pv[kWaves][kJTile];
     __shared__ int32_t pi[kWaves][kJTile];
 
@@ -111,17 +216,24 @@ stage_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, const ll2* __
     ll2* __restrict__ cur = cur_all + (size_t)p * pairs_per_problem(L);
     const int j0 = tile * kJTile;                // first j of this tile
     const int j = j0 + lane;
-    const int jhi = j0 + kJTile - 1 < L ? j0 + kJTile - 1 : L;   // largest j of the tile
-    if (jhi < s) {
-        // no j of this tile can be split into s non-empty stages
+    int lo = s - 1;                              // first i
+    int jcap = L;                                // last j that may end stage s
+    if constexpr (WIN) {
+        const int first_i = win[((size_t)p * S + (s - 1)) * 2], last_j = win[((size_t)p * S + (s - 1)) * 2 + 1];
+        lo = first_i > lo ? first_i : lo;
+        jcap = last_j < jcap ? last_j : jcap;
+    }
+    const int jhi = j0 + kJTile - 1 < jcap ? j0 + kJTile - 1 : jcap;   // largest j of the tile that is allowed
+    if (jhi < s || jhi <= lo || jhi < j0) {
+        // no j of this tile can end stage s
         if (split == 0 && threadIdx.x < kJTile && j <= L) {
             cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = -1;
             ll2 v = cur[j]; v.x = kInf; cur[j] = v;
+            if (WIN && j == L && s == S) bottleneck[p] = kInf;
         }
         return;
     }
-    // i in [s-1, jhi) goes to `used` workgroups in pieces of wg_chunk (a multiple of 16 * 8)
-    const int lo = s - 1;
+    // i in [lo, jhi) goes to `used` workgroups in pieces of wg_chunk (a multiple of 16 * 8)
     const int span = jhi - lo;
     int wg_chunk = (span + splits - 1) / splits;
     wg_chunk = (wg_chunk + 127) & ~127;
@@ -130,8 +242,9 @@ stage_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, const ll2* __
     const int wlo = lo + split * wg_chunk;
     const int whi = wlo + wg_chunk < jhi ? wlo + wg_chunk : jhi;
 
-    const int64_t negPj = j <= L ? prev[j].y : 0;
+    const int64_t negPj = j <= L ? prev[j].y : 0;      // second half of the pair, carried over to dp[s]
     int64_t Pj = -negPj;
+    if constexpr (WIN) Pj = j <= L ? pfull[(size_t)p * (L + 1) + j] : 0;   // the pair holds xfer[j] - P(j) there
     asm volatile("" : "+v"(Pj));   // keep "Pj + (-P_i)" one 64-bit add instead of a two-part subtract
 
     // the workgroup's piece: 16 contiguous chunks, one per wave
@@ -199,26 +312,38 @@ stage_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, const ll2* __
         return;
     }
     if (threadIdx.x < kJTile && j <= L) {
-        const bool ok = j >= s;                   // then i = s-1 < j exists, so bi >= 0
+        // plain: j >= s has i = s-1 < j, so bi >= 0 and b is finite; windowed: every allowed i may be infeasible
+        const bool ok = WIN ? (j >= s && j <= jcap && bi >= 0 && b < kInf) : (j >= s);
         ll2 v; v.x = ok ? b : kInf; v.y = negPj;
         cur[j] = v;
         cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = ok ? bi : -1;
-        if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v.x;
+        if constexpr (WIN) {
+            if (j == L && s == S) bottleneck[p] = v.x;
+        } else {
+            if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v.x;
+        }
     }
 }
 
 // Tiles whose i range went to several workgroups: merge their minima (pieces ascend in i, so
 // strict < keeps the lowest i) and finish dp[s][j], cut[s][j].  Same geometry as the step kernel.
+template <bool WIN>
 __global__ void __launch_bounds__(kJTile)
 stage_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, ll2* __restrict__ cur_all,
                    const int64_t* __restrict__ pval, const int32_t* __restrict__ pidx,
-                   int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+                   int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut, const int32_t* __restrict__ win) {
     const int p = blockIdx.y, tile = blockIdx.x, lane = threadIdx.x;
     const int j0 = tile * kJTile;
     const int j = j0 + lane;
-    const int jhi = j0 + kJTile - 1 < L ? j0 + kJTile - 1 : L;
-    if (jhi < s) return;
-    const int span = jhi - (s - 1);
+    int lo = s - 1, jcap = L;
+    if constexpr (WIN) {
+        const int first_i = win[((size_t)p * S + (s - 1)) * 2], last_j = win[((size_t)p * S + (s - 1)) * 2 + 1];
+        lo = first_i > lo ? first_i : lo;
+        jcap = last_j < jcap ? last_j : jcap;
+    }
+    const int jhi = j0 + kJTile - 1 < jcap ? j0 + kJTile - 1 : jcap;
+    if (jhi < s || jhi <= lo || jhi < j0) return;   // the step kernel wrote this tile off
+    const int span = jhi - lo;
     int wg_chunk = (span + splits - 1) / splits;
     wg_chunk = (wg_chunk + 127) & ~127;
     const int used = (span + wg_chunk - 1) / wg_chunk;
@@ -234,12 +359,37 @@ stage_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, ll2* __restr
         b = lt ? x : b;
         bi = lt ? xi : bi;
     }
-    const bool ok = j >= s;
-    ll2 v = cur[j];                             // keeps -P(j)
+    const bool ok = WIN ? (j >= s && j <= jcap && bi >= 0 && b < kInf) : (j >= s);
+    ll2 v = cur[j];                             // keeps the second half of the pair
     v.x = ok ? b : kInf;
     cur[j] = v;
     cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = ok ? bi : -1;
-    if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v.x;
+    if constexpr (WIN) {
+        if (j == L && s == S) bottleneck[p] = v.x;
+    } else {
+        if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v.x;
+    }
+}
+
+// Boundaries for exactly S stages, or all -1 if the bounds allow no split.
+__global__ void __launch_bounds__(64)
+stage_window_bounds_kernel(int32_t B, int32_t L, int32_t S, const int64_t* __restrict__ bottleneck,
+                           const int32_t* __restrict__ cut, int32_t* __restrict__ bounds) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= B) return;
+    const int32_t* ct = cut + (int64_t)p * S * (L + 1);
+    int32_t* bd = bounds + (int64_t)p * (S + 1);
+    if (bottleneck[p] >= kInf) {
+        for (int t = 0; t <= S; ++t) bd[t] = -1;
+        return;
+    }
+    int32_t x = L;
+    bd[S] = x;
+    for (int t = S; t >= 1; --t) {
+        x = ct[(int64_t)(t - 1) * (L + 1) + x];
+        x = x < 0 ? 0 : (x > L ? L : x);
+        bd[t - 1] = x;
+    }
 }
 
 __global__ void __launch_bounds__(64)
@@ -284,15 +434,48 @@ hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_c
         // init kernel wrote, and writes buffer 1; s = 3 reads 1, writes 0; ...
         const ll2* prev_all = ws + (size_t)(s & 1) * (L + 1);
         ll2* cur_all = ws + (size_t)((s & 1) ^ 1) * (L + 1);
-        hipLaunchKernelGGL(stage_step_kernel, grid, dim3(kWaves * 64), 0, stream, L, S, s, splits, prev_all,
-                           cur_all, pval, pidx, bottleneck, cut);
+        hipLaunchKernelGGL(stage_step_kernel<false>, grid, dim3(kWaves * 64), 0, stream, L, S, s, splits, prev_all,
+                           cur_all, pval, pidx, bottleneck, cut, nullptr, nullptr);
         if (splits > 1)
-            hipLaunchKernelGGL(stage_merge_kernel, merge_grid, dim3(kJTile), 0, stream, L, S, s, splits,
-                               cur_all, pval, pidx, bottleneck, cut);
+            hipLaunchKernelGGL(stage_merge_kernel<false>, merge_grid, dim3(kJTile), 0, stream, L, S, s, splits,
+                               cur_all, pval, pidx, bottleneck, cut, nullptr);
     }
     if (s_query > 0 && bounds != nullptr)
         hipLaunchKernelGGL(stage_bounds_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, B, L, S,
                            s_query, cut, bounds);
+    return hipGetLastError();
+}
+
+size_t stage_window_workspace_bytes(int32_t B, int32_t L, int32_t S) { return layout_of(B, L, S).total; }
+
+hipError_t launch_stage_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, const int64_t* xfer,
+                               int64_t eps_num, int64_t eps_den, int64_t* bottleneck, int32_t* cut,
+                               int32_t* bounds, void* workspace, hipStream_t stream) {
+    if (B == 0) return hipSuccess;
+    const StageLayout lay = layout_of(B, L, S);
+    const int splits = splits_of(B, L), tiles = tiles_of(L);
+    char* wsb = static_cast<char*>(workspace);
+    ll2* ws = reinterpret_cast<ll2*>(wsb);
+    int64_t* pval = reinterpret_cast<int64_t*>(wsb + lay.pval_off);
+    int32_t* pidx = reinterpret_cast<int32_t*>(wsb + lay.pidx_off);
+    int64_t* pfull = reinterpret_cast<int64_t*>(wsb + lay.pfull_off);
+    int32_t* win = reinterpret_cast<int32_t*>(wsb + lay.win_off);
+    hipLaunchKernelGGL(stage_window_init_kernel, dim3(B), dim3(kScanThreads), 0, stream, L, S, seg_cost, xfer,
+                       eps_num, eps_den, ws, pfull, win, bottleneck, cut);
+    const dim3 grid((unsigned)(tiles * splits), (unsigned)B);
+    const dim3 merge_grid((unsigned)tiles, (unsigned)B);
+    for (int s = 2; s <= S; ++s) {
+        const ll2* prev_all = ws + (size_t)(s & 1) * (L + 1);
+        ll2* cur_all = ws + (size_t)((s & 1) ^ 1) * (L + 1);
+        hipLaunchKernelGGL(stage_step_kernel<true>, grid, dim3(kWaves * 64), 0, stream, L, S, s, splits, prev_all,
+                           cur_all, pval, pidx, bottleneck, cut, pfull, win);
+        if (splits > 1)
+            hipLaunchKernelGGL(stage_merge_kernel<true>, merge_grid, dim3(kJTile), 0, stream, L, S, s, splits,
+                               cur_all, pval, pidx, bottleneck, cut, win);
+    }
+    if (bounds != nullptr)
+        hipLaunchKernelGGL(stage_window_bounds_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, B, L, S,
+                           bottleneck, cut, bounds);
     return hipGetLastError();
 }
 

@@ -102,9 +102,16 @@ def _stage_rows(dev):
     cost = seg.reshape(1, L)
     t_dp = _best_ms(lambda: rh.rh_stage_dp(1, L, S, cost, bott, cut, S, bounds, ws))
     cells = sum((L - s + 1) * (L - s + 2) // 2 for s in range(2, S + 1))      # (i, j) pairs with s-1 <= i < j <= L
+    # the same partition for exactly S stages with boundary transfers and a tolerance of half a stage
+    xfer = torch.from_numpy(syn.uniform_at(syn.stream_seed(syn.BASE_SEED, 0, 7), np.arange(L + 1, dtype=np.uint64),
+                                           50000)[None]).to(dev)
+    wb = torch.empty(1, dtype=torch.int64, device=dev)
+    ws2 = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_WINDOW, 1, L, S), dtype=torch.uint8, device=dev)
+    t_win = _best_ms(lambda: rh.rh_stage_dp_window(1, L, S, cost, xfer, 1, 2, wb, cut, bounds, ws2))
     return {"L": L, "S": S, "segment_chain": {"ops": M, "K": K}, "segment_chains_ms": t_seg,
             "stage_dp_ms": t_dp, "stage_dp_cells": cells, "stage_dp_cells_per_s": cells / (t_dp * 1e-3),
-            "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
+            "bottleneck_ns_at_S": int(bott[0, S - 1].item()),
+            "window_eps_half_with_transfers_ms": t_win, "window_bottleneck_ns": int(wb.item())}
 
 
 def _cone_rows(dev, n_cones=1024, K=64):
