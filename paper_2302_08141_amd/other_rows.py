@@ -70,6 +70,9 @@ def _graph_rows(g, dev):
     last = torch.empty(1, dtype=torch.int32, device=dev)
     plan = torch.empty((1, N), dtype=torch.int32, device=dev)
     t_build = _best_ms(lambda: rh.rh_build_reshard(mesh, N - 1, Kp, K, osp, isp, dims, eb, R))
+    scratch = torch.empty_like(R)
+    t_write = _best_ms(lambda: device_fill.stream_write(scratch))   # plain write-only kernel, same number of bytes
+    del scratch
     ws_bytes = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, N, Kp)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
     t_chain = _best_ms(lambda: rh.rh_minplus_chain(1, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, None, total, last,
@@ -79,6 +82,7 @@ def _graph_rows(g, dev):
     extra = {"memory_sweep": _memory_sweep_rows(g, R, dev)} if Kp == 256 else {}
     return {**extra, "N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
             "reshard_ms": t_build, "reshard_write_gbps": cells * 8 / (t_build * 1e-3) / 1e9,
+            "plain_write_kernel_gbps": cells * 8 / (t_write * 1e-3) / 1e9,
             "chain_workgroups_per_problem": 8 if ws_bytes else 1,
             "chain_ms": t_chain, "chain_cells_per_s": cells / (t_chain * 1e-3),
             "chain_hbm_gbps": cells * 8 * (1 + 1.25 / Kp) / (t_chain * 1e-3) / 1e9,

@@ -60,6 +60,15 @@ read_kernel(const ull2* __restrict__ src, int64_t n16, unsigned long long* __res
     if ((acc.x ^ acc.y) == 0x9E3779B97F4A7C15ull) sink[0] = 1;   // practically never: keeps the loads alive
 }
 
+// Write-only stream: every 16-byte word gets the same value (yardstick for write-bound kernels).
+__global__ void __launch_bounds__(256)
+write_kernel(ull2* __restrict__ dst, int64_t n16, unsigned long long value) {
+    const ull2 v = {value, value};
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (int64_t)gridDim.x * blockDim.x)
+        __builtin_nontemporal_store(v, dst + i);
+}
+
 // The same read-only stream with the access shape of a tuned streaming kernel: a 1024-thread
 // workgroup owns contiguous 256 KiB chunks and keeps 16 loads per lane in flight.
 __global__ void __launch_bounds__(1024)
@@ -83,6 +92,14 @@ extern "C" int synth_stream_read_wide(const void* src, int64_t bytes, void* sink
     if (bytes == 0) return 0;
     hipLaunchKernelGGL(read_wide_kernel, dim3((unsigned)blocks), dim3(1024), 0, static_cast<hipStream_t>(stream),
                        static_cast<const ull2*>(src), bytes / 262144, static_cast<unsigned long long*>(sink8));
+    return hipGetLastError() == hipSuccess ? 0 : -2;
+}
+
+extern "C" int synth_stream_write(void* dst, int64_t bytes, uint64_t value, int32_t blocks, void* stream) {
+    if (!dst || bytes < 0 || (bytes & 15) || blocks < 1) return -1;
+    if (bytes == 0) return 0;
+    hipLaunchKernelGGL(write_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<ull2*>(dst), bytes / 16, (unsigned long long)value);
     return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 

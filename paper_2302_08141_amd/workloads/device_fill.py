@@ -31,6 +31,9 @@ def lib():
                                         ctypes.c_void_p]
         L.synth_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32,
                                         ctypes.c_void_p]
+        L.synth_stream_write.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int32,
+                                         ctypes.c_void_p]
+        L.synth_stream_write.restype = ctypes.c_int
         L.synth_stream_read_wide.argtypes = L.synth_stream_read.argtypes
         L.synth_stream_copy.restype = L.synth_stream_read.restype = L.synth_stream_read_wide.restype = ctypes.c_int
         _lib = L
@@ -80,3 +83,14 @@ def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 8192, wide:
             ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if rc != 0:
         raise RuntimeError(f"stream_read rc={rc}")
+
+
+def stream_write(dst: torch.Tensor, value: int = 0, blocks: int = 8192) -> None:
+    """Plain write-only streaming kernel over dst (yardstick for the achievable HBM write rate)."""
+    assert dst.is_cuda and dst.is_contiguous()
+    nbytes = dst.numel() * dst.element_size()
+    assert nbytes % 16 == 0
+    rc = lib().synth_stream_write(ctypes.c_void_p(dst.data_ptr()), nbytes, value, blocks,
+                                  ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"synth_stream_write rc={rc}")
