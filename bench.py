@@ -99,7 +99,7 @@ def cpu_baseline(c, R, B, N, K, sample_problems=2048, batch=64):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
     import torch
