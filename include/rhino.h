@@ -225,7 +225,7 @@ int rh_plan_memory(int32_t B, int32_t N, int32_t Kp, const int32_t* plan,
  *     cut[s][j] = the minimising i, lowest on ties
  * for every s = 1..S in one call.
  *
- *   B >= 0, 1 <= S <= L <= 65536, S <= 1024; cost[l] in [0, 2^36)
+ *   0 <= B <= 65535, 1 <= S <= L <= 65536, S <= 1024; cost[l] in [0, 2^36)
  *   seg_cost    [B][L]
  *   bottleneck  [B][S] out, entry s-1 = dp[s][L]
  *   cut         [B][S][L+1] out, entry [s-1][j]; 0 for s = 1, -1 where j < s
@@ -252,7 +252,7 @@ int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
  *     dp[1][j] = P(j);  dp[s][j] = min over allowed i of max(dp[s-1][i], P(j) - P(i) + xfer[i])
  * lowest i on ties.  The bounds prune the search to a band around the balanced cuts.
  *
- *   B >= 0, 1 <= S <= L <= 65536, S <= 1024; cost[l], xfer[i] in [0, 2^36)
+ *   0 <= B <= 65535, 1 <= S <= L <= 65536, S <= 1024; cost[l], xfer[i] in [0, 2^36)
  *   seg_cost    [B][L]
  *   xfer        [B][L+1] time to pass the tensor that crosses a boundary placed before
  *               segment i (entries 0 and L unused); NULL = no transfer time

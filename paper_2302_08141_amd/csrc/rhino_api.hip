@@ -122,7 +122,7 @@ int rh_plan_memory(int32_t B, int32_t N, int32_t Kp, const int32_t* plan, const 
 int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_t* bottleneck,
                 int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                 size_t workspace_bytes, void* stream) {
-    if (B < 0 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+    if (B < 0 || B > 65535 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
     if (s_query < 0 || s_query > S) return RH_ERR_SHAPE;
     if (B == 0) return RH_OK;
     if (!seg_cost || !bottleneck || !cut) return RH_ERR_NULL;
@@ -137,7 +137,7 @@ int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_
 int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, const int64_t* xfer,
                        int64_t eps_num, int64_t eps_den, int64_t* bottleneck, int32_t* cut, int32_t* bounds,
                        void* workspace, size_t workspace_bytes, void* stream) {
-    if (B < 0 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+    if (B < 0 || B > 65535 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
     if (eps_den < 1 || eps_den > (1 << 20) || eps_num > ((int64_t)1 << 30)) return RH_ERR_SHAPE;
     if (B == 0) return RH_OK;
     if (!seg_cost || !bottleneck || !cut) return RH_ERR_NULL;

@@ -196,3 +196,22 @@ def test_check_costs_counts_contract_violations():
     rh.rh_check_costs(x, bad)
     torch.cuda.synchronize()
     assert bad.item() == 3
+
+
+@pytest.mark.parametrize("Kp,B", [(16, 3), (128, 1)])
+def test_longest_chain_the_interface_allows(Kp, B):
+    N = 16384
+    rng = np.random.default_rng(Kp)
+    c = rng.integers(0, 1 << 20, size=(B, N, Kp)).astype(np.int64)
+    R = rng.integers(0, 1 << 20, size=(B, N - 1, Kp, Kp)).astype(np.int64)
+    check(c, R)
+    if Kp == 128:                                                     # and through the eight-workgroup kernel
+        dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+        ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp), dtype=torch.uint8, device=DEV)
+        total = torch.zeros(B, dtype=torch.int64, device=DEV)
+        last = torch.zeros(B, dtype=torch.int32, device=DEV)
+        arg = torch.zeros((B, N - 1, Kp), dtype=torch.int16, device=DEV)
+        rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, None, total, last, ws)
+        torch.cuda.synchronize()
+        o_arg, _, o_total, o_last = oracle.chain(c, R)
+        assert total.item() == o_total[0] and np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)

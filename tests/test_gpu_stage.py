@@ -67,3 +67,9 @@ def test_argument_errors():
     assert ok(ws=None) == -4 and ok(wsb=16) == -4
     assert rh.rh_workspace_size(rh.WS_STAGE_DP, 1, 64, 65) == 0
     torch.cuda.synchronize()
+
+
+def test_long_chain_of_segments():
+    # beyond one split's worth of i per workgroup and beyond 2^16 / 4 segments
+    cost = syn.segment_costs(3, 20000)[None]
+    check(cost, 6, s_query=6)
