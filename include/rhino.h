@@ -147,6 +147,29 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
                      size_t workspace_bytes, void* stream);
 
 /*
+ * rh_minplus_chain_specs -- the same dynamic program with the resharding times computed from
+ * the spec words per cell instead of read from tables: R_i[a][b] is exactly what
+ * rh_build_reshard would write for (out_spec[i][a], in_spec[i+1][b]) on problem p's mesh.  One
+ * operator graph, several logical meshes (mesh shapes are searched in parallel, Sec. 3 /
+ * Sec. 4): problem p is searched on meshes[p mod n_meshes].  Nothing of size Kp x Kp is ever
+ * stored, so it serves batches whose tables would not fit in memory.  Bound by the vector
+ * ALU, not by HBM.
+ *
+ *   B >= 0, 1 <= N <= RH_NMAX, Kp 64, 128 or 256, 1 <= n_meshes <= 64
+ *   meshes   host, [n_meshes], read during the call
+ *   c        [B][N][Kp] node costs per problem (they depend on the mesh), batch stride in elements
+ *   K, out_spec, in_spec, dims, elem_bytes   as for rh_build_reshard with n_edges = N-1, shared by
+ *            all problems
+ *   arg [B][N-1][Kp], vfinal [B][Kp] (may be NULL), total [B], last [B]   as for rh_minplus_chain
+ */
+int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes,
+                           const rh_mesh_t* meshes,
+                           const int64_t* c, int64_t c_batch_stride, const int32_t* K,
+                           const uint32_t* out_spec, const uint32_t* in_spec,
+                           const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg,
+                           int64_t* vfinal, int64_t* total, int32_t* last, void* stream);
+
+/*
  * rh_backtrack -- the plan X of Sec. 4.2 in index form:
  *     plan[N-1] = last;  plan[i] = arg_i[plan[i+1]],  i = N-2 .. 0.
  *   arg [B][N-1][Kp], last [B] (values in [0,Kp)), plan [B][N] out.

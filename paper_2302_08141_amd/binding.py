@@ -53,6 +53,9 @@ def lib():
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         L.rh_build_reshard.argtypes = [ctypes.POINTER(Mesh), i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.rh_minplus_chain.argtypes = [i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.rh_minplus_chain_specs.argtypes = [i32, i32, i32, i32, ctypes.POINTER(Mesh), vp, i64, vp, vp, vp, vp, vp, vp, vp,
+                                             vp, vp, vp]
+        L.rh_minplus_chain_specs.restype = ctypes.c_int
         L.rh_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp]
         L.rh_stage_dp.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_cone_merge.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -131,6 +134,24 @@ def rh_minplus_chain(B: int, N: int, Kp: int, c, c_batch_stride: int, R, R_batch
                                   _ptr(last, torch.int32, "last", b),
                                   ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None,
                                   workspace_bytes, _stream()), "rh_minplus_chain")
+
+
+def rh_minplus_chain_specs(B: int, N: int, Kp: int, meshes, c, c_batch_stride: int, K, out_spec, in_spec, dims,
+                           elem_bytes, arg, vfinal, total, last):
+    """meshes: list of at most 64 Mesh, problem p uses meshes[p % len(meshes)]; c int64[B][N][Kp]; K int32[N];
+    out_spec, in_spec int32-typed words [N][Kp]; dims int64[N-1][4]; elem_bytes int32[N-1]; outputs as for
+    rh_minplus_chain."""
+    marr = (Mesh * max(len(meshes), 1))(*meshes)
+    b, n, k = max(B, 0), max(N, 1), max(Kp, 0)
+    span = (b - 1) * c_batch_stride + n * k if b > 0 else 0
+    _check(lib().rh_minplus_chain_specs(B, N, Kp, len(meshes), marr, _ptr(c, torch.int64, "c", span), c_batch_stride,
+                                        _ptr(K, torch.int32, "K", n), _ptr(out_spec, torch.int32, "out_spec", n * k),
+                                        _ptr(in_spec, torch.int32, "in_spec", n * k),
+                                        _ptr(dims, torch.int64, "dims", 4 * (n - 1)),
+                                        _ptr(elem_bytes, torch.int32, "elem_bytes", n - 1),
+                                        _ptr(arg, torch.int16, "arg", b * (n - 1) * k),
+                                        _ptr(vfinal, torch.int64, "vfinal", b * k), _ptr(total, torch.int64, "total", b),
+                                        _ptr(last, torch.int32, "last", b), _stream()), "rh_minplus_chain_specs")
 
 
 def rh_backtrack(B: int, N: int, Kp: int, arg, last, plan):

@@ -25,6 +25,14 @@ hipError_t launch_chain_gang(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
                              const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
                              int64_t* total, int32_t* last, void* workspace, hipStream_t stream);
 
+// Chain DP with the resharding times computed from the spec words per cell; problem p uses mesh p % n_meshes
+// (n_meshes <= 64).
+hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                              const int64_t* c, int64_t c_bs,
+                              const int32_t* K, const uint32_t* out_spec, const uint32_t* in_spec,
+                              const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg, int64_t* vfinal,
+                              int64_t* total, int32_t* last, hipStream_t stream);
+
 hipError_t launch_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
                             const int32_t* last, int32_t* plan, hipStream_t stream);
 

@@ -11,6 +11,7 @@
 // The kernel is bound by the 8 bytes it writes per cell; rows are written as coalesced
 // 16-byte stores.
 #include "kernels.h"
+#include "reshard_common.h"
 
 namespace rh {
 namespace {
@@ -19,38 +20,6 @@ typedef long long ll2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kPanelRows = 16;   // rows of one edge table per workgroup
-
-enum : uint32_t { kNone = 0, kGather = 1, kAllToAll = 2, kAllReduce = 3, kImpossible = 4 };
-
-// Canonical form of a spec word for one edge: per axis the state and, for a split, dim and
-// lgdiv; bit 31 set = not a usable candidate.
-__device__ __forceinline__ uint32_t canonical(uint32_t w, int slot, int k_real, const int64_t* dm,
-                                              const Mesh& mesh) {
-    uint32_t out = 0;
-    bool ok = slot < k_real;
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-        if (x >= mesh.naxes) break;
-        const uint32_t byte = (w >> (8 * x)) & 0xFFu;
-        const uint32_t st = byte & 3u, d = (byte >> 2) & 7u, lg = (byte >> 5) & 7u;
-        if (st == 3u) ok = false;
-        if (st == 1u) {
-            if (d > 3u) {
-                ok = false;
-            } else {
-                const int64_t blocks = (int64_t)1 << (mesh.lgm[x] + (int)lg);
-                if ((dm[d] & (blocks - 1)) != 0) ok = false;
-            }
-            out |= byte << (8 * x);
-        } else {
-            out |= st << (8 * x);
-        }
-    }
-    if (mesh.naxes == 2 && (out & 3u) == 1u && ((out >> 8) & 3u) == 1u &&
-        ((out >> 2) & 7u) == ((out >> 10) & 7u))
-        ok = false;   // one dim on both axes
-    return ok ? out : (out | 0x80000000u);
-}
 
 __device__ __forceinline__ uint32_t transition(uint32_t pb, uint32_t qb) {
     const uint32_t ps = pb & 3u, qs = qb & 3u;
@@ -89,23 +58,7 @@ reshard_kernel(Mesh mesh, int32_t Kp, int32_t lgKp, const int32_t* __restrict__ 
 
     if (tid < 16) {
         const int x = tid >> 3, o = (tid >> 2) & 1, kind = tid & 3;
-        int64_t ns = 0;
-        if (kind != kNone && x < mesh.naxes) {
-            const uint64_t whole = (uint64_t)elem_bytes[e] * (uint64_t)dm[0] * (uint64_t)dm[1] *
-                                   (uint64_t)dm[2] * (uint64_t)dm[3];
-            const int lgo = (o && mesh.naxes == 2) ? mesh.lgm[1 - x] : 0;
-            const uint64_t T = whole >> lgo;
-            const int lg = mesh.lgm[x];
-            const uint64_t moved = T * (((uint64_t)1 << lg) - 1);
-            uint64_t V = kind == kAllToAll ? (moved >> (2 * lg)) : (moved >> lg);
-            if (kind == kAllReduce) V += V;
-            if (V > 0) {
-                const uint64_t t = V * 1000u / (uint64_t)mesh.bw_bytes_per_us[x] +
-                                   (uint64_t)mesh.alpha_ns[x];
-                ns = t < (uint64_t)kInf ? (int64_t)t : kInf;
-            }
-        }
-        tab[x][o][kind] = ns;
+        tab[x][o][kind] = axis_time(x, o, kind, mesh, dm, elem_bytes[e]);
     }
     if (tid >= 64 && tid < 64 + kPanelRows) {
         const int a = row0 + (tid - 64);

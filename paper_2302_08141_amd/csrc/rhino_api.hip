@@ -19,16 +19,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int from_hip(hipError_t e) { return e == hipSuccess ? RH_OK : RH_ERR_HIP; }
 
-}  // namespace
-
-extern "C" {
-
-int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp, const int32_t* K,
-                     const uint32_t* out_spec, const uint32_t* in_spec, const int64_t* dims,
-                     const int32_t* elem_bytes, int64_t* R, void* stream) {
-    if (mesh == nullptr) return RH_ERR_NULL;
-    if (n_edges < 0) return RH_ERR_SHAPE;
-    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+// Validates a caller's mesh and converts it to the kernels' form.
+int convert_mesh(const rh_mesh_t* mesh, rh::Mesh* out) {
     if (mesh->naxes < 1 || mesh->naxes > 2) return RH_ERR_SHAPE;
     rh::Mesh m{};
     m.naxes = mesh->naxes;
@@ -44,6 +36,22 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp, const i
         m.bw_bytes_per_us[x] = mesh->bw_bytes_per_us[x];
         m.alpha_ns[x] = mesh->alpha_ns[x];
     }
+    *out = m;
+    return RH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp, const int32_t* K,
+                     const uint32_t* out_spec, const uint32_t* in_spec, const int64_t* dims,
+                     const int32_t* elem_bytes, int64_t* R, void* stream) {
+    if (mesh == nullptr) return RH_ERR_NULL;
+    if (n_edges < 0) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    rh::Mesh m{};
+    if (const int rc = convert_mesh(mesh, &m)) return rc;
     if (n_edges == 0) return RH_OK;
     if (!K || !out_spec || !in_spec || !dims || !elem_bytes || !R) return RH_ERR_NULL;
     if (!aligned16(R) || (reinterpret_cast<uintptr_t>(in_spec) & 7u) != 0) return RH_ERR_SHAPE;
@@ -76,6 +84,24 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t
                                               total, last, workspace, static_cast<hipStream_t>(stream)));
     return from_hip(rh::launch_chain(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal, total,
                                      last, static_cast<hipStream_t>(stream)));
+}
+
+int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const rh_mesh_t* meshes, const int64_t* c,
+                           int64_t c_batch_stride, const int32_t* K, const uint32_t* out_spec,
+                           const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes,
+                           uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last, void* stream) {
+    if (B < 0 || N < 1 || N > RH_NMAX || n_meshes < 1 || n_meshes > 64) return RH_ERR_SHAPE;
+    if (Kp != 64 && Kp != 128 && Kp != 256) return RH_ERR_K_RANGE;
+    if (B == 0) return RH_OK;
+    if (!meshes || !c || !total || !last) return RH_ERR_NULL;
+    if (N > 1 && (!K || !out_spec || !in_spec || !dims || !elem_bytes || !arg)) return RH_ERR_NULL;
+    if (c_batch_stride < 0 || (B > 1 && c_batch_stride < (int64_t)N * Kp)) return RH_ERR_SHAPE;
+    rh::Mesh ms[64];
+    for (int p = 0; p < n_meshes; ++p)
+        if (const int rc = convert_mesh(meshes + p, ms + p)) return rc;
+    return from_hip(rh::launch_chain_fused(B, N, Kp, n_meshes, ms, c, c_batch_stride, K, out_spec, in_spec, dims,
+                                           elem_bytes, arg, vfinal, total, last,
+                                           static_cast<hipStream_t>(stream)));
 }
 
 int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg, const int32_t* last,

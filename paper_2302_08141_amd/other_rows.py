@@ -58,6 +58,30 @@ def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
             "shared_table_gbps": cells * 8 / (t * 1e-3) / 1e9}
 
 
+def _fused_rows(g, dev):
+    """The chain DP that computes resharding times per cell (no tables in memory): the graph on the 11
+    two-dimensional power-of-two shapes of its 1024-device mesh, once each and cycled to 256 problems."""
+    N, Kp = g["N"], g["Kp"]
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    K, osp, isp = to(g["K"]), to(g["out_spec"].view(np.int32)), to(g["in_spec"].view(np.int32))
+    dims, eb = to(g["dims"]), to(g["elem_bytes"])
+    n_dev = g["m"][0] * g["m"][1]
+    shapes = [(1 << k, n_dev >> k) for k in range(n_dev.bit_length())]
+    out = {"mesh_shapes": len(shapes)}
+    for B in (1, len(shapes), 256):
+        meshes = [rh.Mesh.make(shapes[(p + len(shapes) // 2) % len(shapes)], g["bw_bytes_per_us"], g["alpha_ns"])
+                  for p in range(min(B, len(shapes)))]
+        c = to(g["c"][None]).repeat(B, 1, 1).contiguous()     # node costs of the reference mesh for every problem
+        arg = torch.empty((B, N - 1, Kp), dtype=torch.int16, device=dev)
+        total = torch.empty(B, dtype=torch.int64, device=dev)
+        last = torch.empty(B, dtype=torch.int32, device=dev)
+        t = _best_ms(lambda: rh.rh_minplus_chain_specs(B, N, Kp, meshes, c, N * Kp, K, osp, isp, dims, eb, arg, None,
+                                                       total, last), reps=2)
+        cells = B * (N - 1) * Kp * Kp
+        out[f"B{B}"] = {"ms": t, "cells_per_s": cells / (t * 1e-3), "tables_not_stored_gb": cells * 8 / 1e9}
+    return out
+
+
 def _graph_rows(g, dev):
     N, Kp = g["N"], g["Kp"]
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -79,7 +103,7 @@ def _graph_rows(g, dev):
                                                    ws))
     t_back = _best_ms(lambda: rh.rh_backtrack(1, N, Kp, arg, last, plan))
     cells = (N - 1) * Kp * Kp
-    extra = {"memory_sweep": _memory_sweep_rows(g, R, dev)} if Kp == 256 else {}
+    extra = {"memory_sweep": _memory_sweep_rows(g, R, dev), "fused_no_tables": _fused_rows(g, dev)} if Kp == 256 else {}
     return {**extra, "N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
             "reshard_ms": t_build, "reshard_write_gbps": cells * 8 / (t_build * 1e-3) / 1e9,
             "plain_write_kernel_gbps": cells * 8 / (t_write * 1e-3) / 1e9,
