@@ -123,10 +123,8 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
 
         const int64_t* tab0 = &tab[0][0][0];
         const int64_t* tab1 = &tab[1][0][0];
-        for (int a = wave; a < KP; a += W) {
-            const uint32_t pw = __builtin_amdgcn_readfirstlane(prow[a]);
-            if (pw & 0x80000000u) continue;   // not a candidate: the whole row is infeasible
-            const int64_t va = vs[a];
+        auto relax_row = [&](int a, uint32_t pw, int64_t va) {
+            if (pw & 0x80000000u) return;     // not a candidate: the whole row is infeasible
             const uint32_t p0b = pw & 0xFFu, p1b = (pw >> 8) & 0xFFu;
             const uint32_t row0 = kind_row(p0b & 3u), row1 = kind_row(p1b & 3u);
             const uint32_t base0 = ((p1b & 3u) == 1u) ? 8u : 0u;   // axis 0 moves while axis 1 has the producer's state
@@ -140,6 +138,14 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
                 best[k] = lt ? key : best[k];
                 bidx[k] = lt ? a : bidx[k];
             }
+        };
+        // two rows per trip so that the second row's words are already on their way
+        static_assert((KP / W) % 2 == 0, "rows per wave must be even");
+        for (int a = wave; a < KP; a += 2 * W) {
+            const uint32_t pa = prow[a], pb = prow[a + W];
+            const int64_t va = vs[a], vb = vs[a + W];
+            relax_row(a, __builtin_amdgcn_readfirstlane(pa), va);
+            relax_row(a + W, __builtin_amdgcn_readfirstlane(pb), vb);
         }
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
