@@ -172,7 +172,7 @@ int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes,
 /*
  * rh_backtrack -- the plan X of Sec. 4.2 in index form:
  *     plan[N-1] = last;  plan[i] = arg_i[plan[i+1]],  i = N-2 .. 0.
- *   arg [B][N-1][Kp], last [B] (values in [0,Kp)), plan [B][N] out.
+ *   arg [B][N-1][Kp] (16-byte aligned), last [B] (values in [0,Kp)), plan [B][N] out.
  */
 int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
                  const int32_t* last, int32_t* plan, void* stream);

@@ -110,6 +110,7 @@ int rh_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg, const in
     if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
     if (B == 0) return RH_OK;
     if (!last || !plan || (N > 1 && !arg)) return RH_ERR_NULL;
+    if (arg && !aligned16(arg)) return RH_ERR_SHAPE;   // rows are fetched as 16-byte words
     return from_hip(rh::launch_backtrack(B, N, Kp, arg, last, plan, static_cast<hipStream_t>(stream)));
 }
 
