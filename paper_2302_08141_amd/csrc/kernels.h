@@ -56,6 +56,11 @@ hipError_t launch_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_c
                            int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds,
                            void* workspace, hipStream_t stream);
 
+// Exact search by bisection for chains short enough to live in LDS (one workgroup per problem).
+bool stage_fast_applies(int32_t L);
+hipError_t launch_stage_fast(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_t* bottleneck,
+                             int32_t* cut, int32_t s_query, int32_t* bounds, hipStream_t stream);
+
 size_t stage_window_workspace_bytes(int32_t B, int32_t L, int32_t S);
 hipError_t launch_stage_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, const int64_t* xfer,
                                int64_t eps_num, int64_t eps_den, int64_t* bottleneck, int32_t* cut,

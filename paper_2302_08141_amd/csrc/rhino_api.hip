@@ -157,6 +157,9 @@ int rh_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, int64_
     if (!workspace) return RH_ERR_WORKSPACE;
     if (workspace_bytes < rh::stage_workspace_bytes(B, L, S)) return RH_ERR_WORKSPACE;
     if (!aligned16(workspace)) return RH_ERR_WORKSPACE;
+    if (rh::stage_fast_applies(L))
+        return from_hip(rh::launch_stage_fast(B, L, S, seg_cost, bottleneck, cut, s_query, bounds,
+                                              static_cast<hipStream_t>(stream)));
     return from_hip(rh::launch_stage_dp(B, L, S, seg_cost, bottleneck, cut, s_query, bounds, workspace,
                                         static_cast<hipStream_t>(stream)));
 }

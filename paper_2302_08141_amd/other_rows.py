@@ -130,6 +130,14 @@ def _stage_rows(dev):
     cost = seg.reshape(1, L)
     t_dp = _best_ms(lambda: rh.rh_stage_dp(1, L, S, cost, bott, cut, S, bounds, ws))
     cells = sum((L - s + 1) * (L - s + 2) // 2 for s in range(2, S + 1))      # (i, j) pairs with s-1 <= i < j <= L
+    # 256 chains of segments at once (one per candidate mesh, say): costs of problem p are problem 0's rotated by p
+    Bm = 256
+    costs = torch.stack([torch.roll(seg, p) for p in range(Bm)])
+    bott_m = torch.empty((Bm, S), dtype=torch.int64, device=dev)
+    cut_m = torch.empty((Bm, S, L + 1), dtype=torch.int32, device=dev)
+    ws_m = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP, Bm, L, S), dtype=torch.uint8, device=dev)
+    t_dp_m = _best_ms(lambda: rh.rh_stage_dp(Bm, L, S, costs, bott_m, cut_m, 0, None, ws_m))
+    del costs, bott_m, cut_m, ws_m
     # the same partition for exactly S stages with boundary transfers and a tolerance of half a stage
     xfer = torch.from_numpy(syn.uniform_at(syn.stream_seed(syn.BASE_SEED, 0, 7), np.arange(L + 1, dtype=np.uint64),
                                            50000)[None]).to(dev)
@@ -138,6 +146,8 @@ def _stage_rows(dev):
     t_win = _best_ms(lambda: rh.rh_stage_dp_window(1, L, S, cost, xfer, 1, 2, wb, cut, bounds, ws2))
     return {"L": L, "S": S, "segment_chain": {"ops": M, "K": K}, "segment_chains_ms": t_seg,
             "stage_dp_ms": t_dp, "stage_dp_cells": cells, "stage_dp_cells_per_s": cells / (t_dp * 1e-3),
+            "stage_dp_256_problems_ms": t_dp_m, "stage_dp_256_problems_cells_per_s": Bm * cells / (t_dp_m * 1e-3),
+            "stage_dp_method": "bisection on the monotone crossing point (exact); cells = size of the full scan",
             "bottleneck_ns_at_S": int(bott[0, S - 1].item()),
             "window_eps_half_with_transfers_ms": t_win, "window_bottleneck_ns": int(wb.item())}
 

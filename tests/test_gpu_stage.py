@@ -69,6 +69,21 @@ def test_argument_errors():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("L,S,B", [(6143, 6, 1), (6144, 6, 1), (6209, 5, 2), (8191, 3, 1)])
+def test_both_sides_of_the_lds_limit(L, S, B):
+    # up to 6143 segments one workgroup bisects in LDS; longer chains scan every (i, j) cell
+    cost = np.stack([syn.segment_costs(p, L) for p in range(B)])
+    check(cost, S, s_query=S)
+
+
+def test_many_ties_on_long_chains():
+    rng = np.random.default_rng(5)
+    cost = rng.integers(0, 3, size=(2, 6300)).astype(np.int64)        # plateaus of zero-cost segments
+    check(cost, 7, s_query=7)
+    cost = (rng.integers(0, 2, size=(1, 6100)) * rng.integers(0, 4, size=(1, 6100))).astype(np.int64)
+    check(cost, 33, s_query=33)
+
+
 def test_long_chain_of_segments():
     # beyond one split's worth of i per workgroup and beyond 2^16 / 4 segments
     cost = syn.segment_costs(3, 20000)[None]
