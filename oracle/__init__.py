@@ -153,6 +153,36 @@ def stage_dp(cost: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
     return bott, cut, bounds
 
 
+def interval_costs(c: np.ndarray, R: np.ndarray, ldT: int = 0, nthreads: int = 1) -> np.ndarray:
+    """c[L][Kp], R[L-1][Kp][Kp] -> T int64[L][ldT] (ldT >= L+1, default L+1): T[i][j] = least plan cost of the
+    operators i..j-1 on their own, INF where j <= i; columns beyond L are left at -1."""
+    _chk(c, np.int64, "c"); _chk(R, np.int64, "R")
+    L, Kp = c.shape
+    assert R.shape == (max(L - 1, 0), Kp, Kp)
+    ldT = ldT or L + 1
+    T = np.full((L, ldT), -1, dtype=np.int64)
+    rc = lib().oracle_interval_costs(ctypes.c_int32(L), ctypes.c_int32(Kp), _p(c), _p(R), ctypes.c_int64(ldT),
+                                     _p(T), ctypes.c_int32(nthreads))
+    if rc != 0:
+        raise ValueError(f"oracle_interval_costs rc={rc}")
+    return T
+
+
+def stage_interval(T: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
+    """T[B][L][ldT] -> bottleneck[B][S], cut int32[B][S][L+1], bounds int32[B][s_query+1] or None."""
+    _chk(T, np.int64, "T")
+    B, L, ldT = T.shape
+    bott = np.zeros((B, S), dtype=np.int64)
+    cut = np.zeros((B, S, L + 1), dtype=np.int32)
+    bounds = np.zeros((B, s_query + 1), dtype=np.int32) if s_query > 0 else None
+    rc = lib().oracle_stage_interval(ctypes.c_int32(B), ctypes.c_int32(L), ctypes.c_int32(S), ctypes.c_int64(ldT),
+                                     _p(T), _p(bott), _p(cut), ctypes.c_int32(s_query),
+                                     _p(bounds) if bounds is not None else None, ctypes.c_int32(nthreads))
+    if rc != 0:
+        raise ValueError(f"oracle_stage_interval rc={rc}")
+    return bott, cut, bounds
+
+
 def stage_window(cost: np.ndarray, d: int, xfer=None, eps_num: int = -1, eps_den: int = 1):
     """cost[B][L], xfer[B][L+1] or None -> bottleneck[B], cut int32[B][d][L+1], bounds int32[B][d+1]."""
     _chk(cost, np.int64, "cost")

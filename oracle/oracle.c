@@ -29,7 +29,14 @@
  *            tensor units it needs but does not own; axis 0 converted first,
  *            then axis 1; time = floor(bytes*1000 / bytes_per_us) + alpha;
  *   stages:  dp[1][j] = P(j); dp[s][j] = min_{s-1<=i<j} max(dp[s-1][i],
- *            P(j)-P(i)), ties -> lowest i, no empty stage.
+ *            P(j)-P(i)), ties -> lowest i, no empty stage;
+ *   stage time from the intra-stage plan (Sec. 3: each stage's subgraph
+ *            gets its own SPMD plan; Sec. 5.1 balances the stages):
+ *            T[i][j] = min over plans of operators i..j-1 of the Sec. 4.2
+ *            objective on those operators and the edges between them
+ *            -> oracle_interval_costs; dp[1][j] = T[0][j], dp[s][j] =
+ *            min_{s-1<=i<j} max(dp[s-1][i], T[i][j]), ties -> lowest i
+ *            -> oracle_stage_interval.
  *
  * Parity pins (tests, CPU only): brute force over all K^N plans, layered
  * shortest path by a library routine, closed forms, invariances, hand-worked
@@ -302,6 +309,107 @@ int oracle_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t *cost,
                 bd[t - 1] = ct[(size_t)(t - 1) * (L + 1) + bd[t]];
         }
         free(P); free(prev); free(cur);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Stage time of every interval of one operator chain.                  */
+/* c[L][Kp], R[L-1][Kp][Kp]; T[i*ldT + j] for 0 <= i < L, 0 <= j <= L:   */
+/* the least objective over the plans of operators i..j-1 alone (their  */
+/* node costs and the edges between them), INF where j <= i.            */
+/* Written out start by start: a forward sweep from operator i, whose   */
+/* running minimum after operator j-1 is T[i][j].                       */
+int oracle_interval_costs(int32_t L, int32_t Kp, const int64_t *c,
+                          const int64_t *R, int64_t ldT, int64_t *T,
+                          int32_t nthreads)
+{
+    if (L < 1 || Kp < 1 || ldT < (int64_t)L + 1) return -1;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int i = 0; i < L; ++i) {
+        int64_t *row = T + (size_t)i * (size_t)ldT;
+        int64_t *v = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
+        int64_t *w = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
+        for (int j = 0; j <= i; ++j) row[j] = ORC_INF;
+        for (int b = 0; b < Kp; ++b) {
+            int64_t x = c[(size_t)i * Kp + b];
+            v[b] = x >= ORC_INF ? ORC_INF : x;
+        }
+        for (int l = i; l < L; ++l) {
+            /* v = cost vector of the chain i..l by the strategy of operator l */
+            int64_t best = v[0];
+            for (int b = 1; b < Kp; ++b) if (v[b] < best) best = v[b];
+            row[l + 1] = best;
+            if (l + 1 == L) break;
+            const int64_t *Rl = R + (size_t)l * Kp * Kp;
+            const int64_t *cn = c + (size_t)(l + 1) * Kp;
+            for (int b = 0; b < Kp; ++b) {
+                int64_t m = sat_add(v[0], Rl[b]);
+                for (int a = 1; a < Kp; ++a) {
+                    int64_t t = sat_add(v[a], Rl[(size_t)a * Kp + b]);
+                    if (t < m) m = t;
+                }
+                w[b] = sat_add(cn[b], m);
+            }
+            int64_t *t = v; v = w; w = t;
+        }
+        free(v); free(w);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Balanced stages when the time of stage [i, j) is a table entry        */
+/* T[i*ldT + j] (any values in [0, INF], INF = the stage cannot run).   */
+/* dp[1][j] = T[0][j]; dp[s][j] = min_{s-1<=i<j} max(dp[s-1][i], T[i][j]) */
+/* with the lowest minimising i; dp = INF, cut = -1 for j < s.          */
+/* T: [B][L][ldT]; outputs as oracle_stage_dp.                          */
+int oracle_stage_interval(int32_t B, int32_t L, int32_t S, int64_t ldT,
+                          const int64_t *T, int64_t *bottleneck, int32_t *cut,
+                          int32_t s_query, int32_t *bounds, int32_t nthreads)
+{
+    if (B < 0 || L < 1 || S < 1 || S > L || ldT < (int64_t)L + 1) return -1;
+    if (s_query < 0 || s_query > S) return -1;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int p = 0; p < B; ++p) {
+        const int64_t *Tp = T + (size_t)p * (size_t)L * (size_t)ldT;
+        int32_t *ct = cut + (size_t)p * S * (L + 1);
+        int64_t *prev = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        int64_t *cur = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        prev[0] = ORC_INF;
+        ct[0] = -1;
+        for (int j = 1; j <= L; ++j) {
+            prev[j] = Tp[j] >= ORC_INF ? ORC_INF : Tp[j];
+            ct[j] = 0;
+        }
+        bottleneck[(size_t)p * S] = prev[L];
+        for (int s = 2; s <= S; ++s) {
+            int32_t *cts = ct + (size_t)(s - 1) * (L + 1);
+            for (int j = 0; j <= L; ++j) {
+                if (j < s) { cur[j] = ORC_INF; cts[j] = -1; continue; }
+                int64_t best = 0;
+                int besti = -1;
+                for (int i = s - 1; i < j; ++i) {
+                    int64_t t = Tp[(size_t)i * (size_t)ldT + j];
+                    if (t > ORC_INF) t = ORC_INF;
+                    int64_t m = prev[i] > t ? prev[i] : t;
+                    if (besti < 0 || m < best) { best = m; besti = i; }
+                }
+                cur[j] = best;
+                cts[j] = besti;
+            }
+            bottleneck[(size_t)p * S + (s - 1)] = cur[L];
+            int64_t *t = prev; prev = cur; cur = t;
+        }
+        if (bounds && s_query > 0) {
+            int32_t *bd = bounds + (size_t)p * (s_query + 1);
+            bd[s_query] = L;
+            for (int t = s_query; t >= 1; --t)
+                bd[t - 1] = ct[(size_t)(t - 1) * (L + 1) + bd[t]];
+        }
+        free(prev); free(cur);
     }
     return 0;
 }
