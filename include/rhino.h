@@ -291,9 +291,55 @@ int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                        int64_t* bottleneck, int32_t* cut, int32_t* bounds,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * rh_interval_costs -- the time of every candidate pipeline stage of an operator chain.
+ * Sec. 3: each stage's subgraph gets its own SPMD plan; Sec. 5.1 balances the stages.  On a
+ * chain, stage [i, j) holds the operators i..j-1 and its time is the least value of Sec. 4.2's
+ * objective over the plans of these operators alone (their node costs and the edges between
+ * them; an edge that crosses a stage boundary belongs to neither stage):
+ *     T[i][j] = min over x_i..x_{j-1} of  sum_l c_l[x_l] + sum_{i <= l < j-1} R_l[x_l][x_{l+1}]
+ * with the saturation rule of rh_minplus_chain (anything >= RH_INF is RH_INF).
+ *
+ *   0 <= B <= 65535, 1 <= L <= RH_NMAX, Kp in {16, 32, 64, 128, 256}
+ *   c    [B][L][Kp], R [B][L-1][Kp][Kp] (dense; R may be NULL if L == 1); slots beyond an
+ *        operator's candidates carry RH_INF in c
+ *   ldT  row stride of T in elements, even, >= L + 1
+ *   T    [B][L][ldT] out: entry [i][j] for i < j <= L; RH_INF for j <= i; columns beyond L
+ *        are not written
+ * c, R and T must be 16-byte aligned.  The plan of a chosen stage is what rh_minplus_chain and
+ * rh_backtrack return for the sub-chain (pass c + i*Kp, R + i*Kp*Kp and N = j - i).
+ */
+int rh_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c,
+                      const int64_t* R, int64_t ldT, int64_t* T, void* stream);
+
+/*
+ * rh_stage_dp_interval -- balanced pipeline stages (Sec. 2.1, Sec. 5.1-5.2) when the time of
+ * stage [i, j) is a table entry, as rh_interval_costs produces (any table with entries in
+ * [0, RH_INF] will do; RH_INF = the stage cannot run):
+ *     dp[1][j] = T[0][j]
+ *     dp[s][j] = min_{s-1 <= i < j} max( dp[s-1][i], T[i][j] ),  j >= s
+ *     cut[s][j] = the minimising i, lowest on ties (also when every candidate is RH_INF)
+ * for every s = 1..S in one call.
+ *
+ *   0 <= B <= 65535, 1 <= S <= L <= RH_NMAX, S <= 1024; ldT even, >= L + 1
+ *   T           [B][L][ldT], 16-byte aligned
+ *   bottleneck  [B][S] out, entry s-1 = dp[s][L]
+ *   cut         [B][S][L+1] out, entry [s-1][j]; 0 for s = 1, -1 where j < s
+ *   s_query     0 (no bounds wanted) or 1..S
+ *   bounds      [B][s_query+1] out: stage t = operators [bounds[t-1], bounds[t]); may be
+ *               NULL if s_query == 0
+ *   workspace   rh_workspace_size(RH_WS_STAGE_DP_INTERVAL, B, L, S) bytes, 256-byte aligned;
+ *               contents undefined before and after the call
+ */
+int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT,
+                         const int64_t* T, int64_t* bottleneck, int32_t* cut,
+                         int32_t s_query, int32_t* bounds, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
 #define RH_WS_MINPLUS_CHAIN 0
 #define RH_WS_STAGE_DP 1
 #define RH_WS_STAGE_DP_WINDOW 2
+#define RH_WS_STAGE_DP_INTERVAL 3
 /* Bytes of workspace the call `which` needs for these sizes (0 if none or
  * if the sizes are invalid). */
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "librhino.so")
 
 INF = 1 << 52
 KMIN, KMAX, NMAX = 16, 1024, 16384
-WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW = 0, 1, 2
+WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW, WS_STAGE_DP_INTERVAL = 0, 1, 2, 3
 
 
 class RhinoError(RuntimeError):
@@ -65,6 +65,8 @@ def lib():
         L.rh_mask_replicated.restype = L.rh_plan_memory.restype = ctypes.c_int
         L.rh_stage_dp_window.argtypes = [i32, i32, i32, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
         L.rh_stage_dp_window.restype = ctypes.c_int
+        L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp]
+        L.rh_stage_dp_interval.argtypes = [i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
         L.rh_workspace_size.restype = sz
         L.rh_check_costs.argtypes = [vp, i64, vp, vp]
@@ -221,6 +223,27 @@ def rh_stage_dp_window(B: int, L: int, S: int, seg_cost, xfer, eps_num: int, eps
                                     _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)),
                                     _ptr(bounds, torch.int32, "bounds", b * (s_ + 1)), ws_ptr, ws_bytes, _stream()),
            "rh_stage_dp_window")
+
+
+def rh_interval_costs(B: int, L: int, Kp: int, c, R, ldT: int, T):
+    """c int64[B][L][Kp]; R int64[B][L-1][Kp][Kp] (None if L == 1); T int64[B][L][ldT] out, ldT even and > L."""
+    b, l, k = max(B, 0), max(L, 0), max(Kp, 0)
+    _check(lib().rh_interval_costs(B, L, Kp, _ptr(c, torch.int64, "c", b * l * k),
+                                   _ptr(R, torch.int64, "R", b * max(l - 1, 0) * k * k), ldT,
+                                   _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), _stream()), "rh_interval_costs")
+
+
+def rh_stage_dp_interval(B: int, L: int, S: int, ldT: int, T, bottleneck, cut, s_query: int, bounds, workspace):
+    """T int64[B][L][ldT]; bottleneck int64[B][S]; cut int32[B][S][L+1]; bounds int32[B][s_query+1] or None;
+    workspace: uint8 tensor of rh_workspace_size(WS_STAGE_DP_INTERVAL, B, L, S) bytes."""
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    b, l, s_ = max(B, 0), max(L, 0), max(S, 0)
+    _check(lib().rh_stage_dp_interval(B, L, S, ldT, _ptr(T, torch.int64, "T", b * l * max(ldT, 0)),
+                                      _ptr(bottleneck, torch.int64, "bottleneck", b * s_),
+                                      _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)), s_query,
+                                      _ptr(bounds, torch.int32, "bounds", b * (max(s_query, 0) + 1)), ws_ptr,
+                                      ws_bytes, _stream()), "rh_stage_dp_interval")
 
 
 def rh_check_costs(x, violations):

@@ -1,0 +1,221 @@
+// Balanced pipeline stages when the time of stage [i, j) comes from a table (Sec. 3: every
+// stage has its own plan, so its time is not a difference of prefix sums; Sec. 5.1 balances):
+//     dp[1][j] = T[0][j],  dp[s][j] = min_{s-1 <= i < j} max(dp[s-1][i], T[i][j]),  lowest i on ties.
+// Every stage count reads the upper triangle of T once, so the search is bound by the memory
+// system (the table of one problem, L^2 * 8 bytes, is re-read S-1 times and mostly stays in the
+// last-level cache): rows of T are read with coalesced 16-byte loads, two j per lane, eight rows
+// in flight per lane; dp[s-1][i] is uniform over a wave and comes through scalar loads.
+// A workgroup owns 128 consecutive j; its 4 waves take the rows i round-robin; with few problems
+// the i range is also split over several workgroups and a small kernel merges the parts.
+#include "kernels.h"
+
+namespace rh {
+namespace {
+
+typedef long long ll2 __attribute__((ext_vector_type(2)));
+
+constexpr int kSiWaves = 4;
+constexpr int kSiTile = 128;            // j per workgroup
+constexpr int kSiUnroll = 8;
+
+struct SiLayout {
+    size_t dp_off, pval_off, pidx_off, total;
+    int splits, tiles;
+};
+
+__host__ inline SiLayout si_layout(int32_t B, int32_t L) {
+    SiLayout s;
+    s.tiles = (L + 1 + kSiTile - 1) / kSiTile;
+    int splits = 1;
+    // aim at about a thousand workgroups per launch; a split should still hold 32 rows
+    while (splits < 32 && (int64_t)B * s.tiles * splits < 1024 && (L / (splits * 2)) >= 32) splits *= 2;
+    s.splits = splits;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t cols = (size_t)s.tiles * kSiTile;
+    s.dp_off = 0;
+    s.pval_off = up((size_t)B * 2 * cols * sizeof(int64_t));
+    s.pidx_off = s.pval_off + up((size_t)B * splits * cols * sizeof(int64_t));
+    s.total = s.pidx_off + up((size_t)B * splits * cols * sizeof(int32_t));
+    return s;
+}
+
+__global__ void __launch_bounds__(256)
+si_init_kernel(int32_t L, int32_t S, int64_t ldT, const int64_t* __restrict__ T, int64_t T_bs, int64_t cols,
+               int64_t* __restrict__ dp, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+    const int p = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j > L) return;
+    const int64_t* row0 = T + (int64_t)p * T_bs;
+    int64_t v = kInf;
+    if (j >= 1) {
+        v = row0[j];
+        v = v < kInf ? v : kInf;
+    }
+    dp[(int64_t)p * 2 * cols + j] = v;                      // buffer 0 = dp[1]
+    cut[(int64_t)p * S * (L + 1) + j] = j >= 1 ? 0 : -1;
+    if (j == L) bottleneck[(int64_t)p * S] = v;
+}
+
+// One stage count s for the tile blockIdx.x / splits of problem blockIdx.y, rows of split blockIdx.x % splits.
+__global__ void __launch_bounds__(kSiWaves * 64)
+si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t ldT, const int64_t* __restrict__ T,
+               int64_t T_bs, int64_t cols, const int64_t* __restrict__ prev_all, int64_t* __restrict__ cur_all,
+               int64_t* __restrict__ pval, int32_t* __restrict__ pidx, int64_t* __restrict__ bottleneck,
+               int32_t* __restrict__ cut) {
+    __shared__ int64_t sval[kSiWaves][kSiTile];
+    __shared__ int32_t sidx[kSiWaves][kSiTile];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int tile = blockIdx.x / splits, split = blockIdx.x % splits;
+    const int p = blockIdx.y;
+    const int64_t* Tp = T + (int64_t)p * T_bs;
+    const int64_t* prev = prev_all + (int64_t)p * 2 * cols;
+    const int j0 = tile * kSiTile + 2 * lane;               // this lane's j0 and j0 + 1
+    const bool in_range = j0 <= L;                          // then j0 + 1 < ldT (ldT is even and > L)
+
+    // rows that can matter to this tile: s-1 <= i < min(L, last j of the tile)
+    const int j_last = tile * kSiTile + kSiTile - 1 < L ? tile * kSiTile + kSiTile - 1 : L;
+    const int i_begin = s - 1, i_end = j_last;              // exclusive
+    const int n_rows = i_end > i_begin ? i_end - i_begin : 0;
+    const int per = (n_rows + splits - 1) / splits;
+    const int lo = i_begin + split * per;
+    const int hi = lo + per < i_end ? lo + per : i_end;
+
+    int64_t best0 = INT64_MAX, best1 = INT64_MAX;
+    int32_t idx0 = -1, idx1 = -1;
+    auto relax = [&](int i, ll2 t, int64_t a) {
+        // a = dp[s-1][i] (already <= 2^52); entries at or left of the diagonal do not take part
+        int64_t t0 = t.x < kInf ? t.x : kInf, t1 = t.y < kInf ? t.y : kInf;
+        int64_t m0 = a > t0 ? a : t0, m1 = a > t1 ? a : t1;
+        const bool ok0 = i < j0 && m0 < best0, ok1 = i < j0 + 1 && m1 < best1;
+        best0 = ok0 ? m0 : best0;
+        idx0 = ok0 ? i : idx0;
+        best1 = ok1 ? m1 : best1;
+        idx1 = ok1 ? i : idx1;
+    };
+    if (in_range) {
+        const int64_t* col = Tp + j0;
+        int i = lo + wave;
+        for (; i + (kSiUnroll - 1) * kSiWaves < hi; i += kSiUnroll * kSiWaves) {
+            ll2 t[kSiUnroll];
+            int64_t a[kSiUnroll];
+#pragma unroll
+            for (int u = 0; u < kSiUnroll; ++u) {
+                const int r = i + u * kSiWaves;
+                t[u] = *reinterpret_cast<const ll2*>(col + (int64_t)r * ldT);
+                a[u] = prev[r];
+            }
+#pragma unroll
+            for (int u = 0; u < kSiUnroll; ++u) relax(i + u * kSiWaves, t[u], a[u]);
+        }
+        for (; i < hi; i += kSiWaves) relax(i, *reinterpret_cast<const ll2*>(col + (int64_t)i * ldT), prev[i]);
+    }
+    sval[wave][2 * lane] = best0;
+    sval[wave][2 * lane + 1] = best1;
+    sidx[wave][2 * lane] = idx0;
+    sidx[wave][2 * lane + 1] = idx1;
+    __syncthreads();
+    if (tid < kSiTile) {
+        // the waves hold interleaved rows: equal values are decided by the row index
+        int64_t b = sval[0][tid];
+        int32_t bi = sidx[0][tid];
+#pragma unroll
+        for (int w = 1; w < kSiWaves; ++w) {
+            const int64_t v = sval[w][tid];
+            const int32_t vi = sidx[w][tid];
+            const bool take = vi >= 0 && (bi < 0 || v < b || (v == b && vi < bi));
+            b = take ? v : b;
+            bi = take ? vi : bi;
+        }
+        const int j = tile * kSiTile + tid;
+        if (splits > 1) {
+            const int64_t at = ((int64_t)p * splits + split) * cols + j;
+            pval[at] = b;
+            pidx[at] = bi;
+        } else if (j <= L) {
+            const int64_t v = bi >= 0 ? b : kInf;
+            cur_all[(int64_t)p * 2 * cols + j] = v;
+            cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
+            if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kSiTile)
+si_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t cols, int64_t* __restrict__ cur_all,
+                const int64_t* __restrict__ pval, const int32_t* __restrict__ pidx,
+                int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+    const int p = blockIdx.y;
+    const int j = blockIdx.x * kSiTile + threadIdx.x;
+    if (j > L) return;
+    int64_t b = INT64_MAX;
+    int32_t bi = -1;
+    for (int k = 0; k < splits; ++k) {          // splits hold ascending row ranges: the first strict minimum wins
+        const int64_t at = ((int64_t)p * splits + k) * cols + j;
+        const int64_t v = pval[at];
+        const int32_t vi = pidx[at];
+        const bool take = vi >= 0 && (bi < 0 || v < b);
+        b = take ? v : b;
+        bi = take ? vi : bi;
+    }
+    const int64_t v = bi >= 0 ? b : kInf;
+    cur_all[(int64_t)p * 2 * cols + j] = v;
+    cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
+    if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
+}
+
+__global__ void __launch_bounds__(64)
+si_bounds_kernel(int32_t B, int32_t L, int32_t S, int32_t s_query, const int32_t* __restrict__ cut,
+                 int32_t* __restrict__ bounds) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= B) return;
+    const int32_t* ct = cut + (int64_t)p * S * (L + 1);
+    int32_t* bd = bounds + (int64_t)p * (s_query + 1);
+    int32_t x = L;
+    bd[s_query] = x;
+    for (int t = s_query; t >= 1; --t) {
+        x = ct[(int64_t)(t - 1) * (L + 1) + x];
+        x = x < 0 ? 0 : (x > L ? L : x);
+        bd[t - 1] = x;
+    }
+}
+
+}  // namespace
+
+size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S) {
+    (void)S;
+    return si_layout(B, L).total;
+}
+
+hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int64_t* T, int64_t* bottleneck,
+                                 int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
+                                 hipStream_t stream) {
+    if (B == 0) return hipSuccess;
+    const SiLayout lay = si_layout(B, L);
+    const int64_t cols = (int64_t)lay.tiles * kSiTile;
+    const int64_t T_bs = (int64_t)L * ldT;
+    char* ws = static_cast<char*>(workspace);
+    int64_t* dp = reinterpret_cast<int64_t*>(ws + lay.dp_off);
+    int64_t* pval = reinterpret_cast<int64_t*>(ws + lay.pval_off);
+    int32_t* pidx = reinterpret_cast<int32_t*>(ws + lay.pidx_off);
+    hipLaunchKernelGGL(si_init_kernel, dim3((L + 256) / 256, B), dim3(256), 0, stream, L, S, ldT, T, T_bs, cols, dp,
+                       bottleneck, cut);
+    const dim3 grid((unsigned)(lay.tiles * lay.splits), (unsigned)B);
+    const dim3 merge_grid((unsigned)lay.tiles, (unsigned)B);
+    for (int s = 2; s <= S; ++s) {
+        // dp[s-1] sits in buffer (s-1) odd ? 0 : 1 of each problem
+        const int64_t* prev_all = dp + (size_t)(s & 1) * cols;
+        int64_t* cur_all = dp + (size_t)((s & 1) ^ 1) * cols;
+        hipLaunchKernelGGL(si_step_kernel, grid, dim3(kSiWaves * 64), 0, stream, L, S, s, lay.splits, ldT, T, T_bs,
+                           cols, prev_all, cur_all, pval, pidx, bottleneck, cut);
+        if (lay.splits > 1)
+            hipLaunchKernelGGL(si_merge_kernel, merge_grid, dim3(kSiTile), 0, stream, L, S, s, lay.splits, cols,
+                               cur_all, pval, pidx, bottleneck, cut);
+    }
+    if (s_query > 0 && bounds != nullptr)
+        hipLaunchKernelGGL(si_bounds_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, B, L, S, s_query, cut, bounds);
+    return hipGetLastError();
+}
+
+}  // namespace rh

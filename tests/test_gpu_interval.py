@@ -1,0 +1,179 @@
+"""GPU parity of the interval stage times and of the stage search over a table against the CPU oracle (bit-exact)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_08141_amd import binding as rh
+from paper_2302_08141_amd.workloads import synthetic as syn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+INF = 1 << 52
+
+
+def even_ld(L, extra=0):
+    ld = L + 1 + extra
+    return ld + (ld & 1)
+
+
+def gpu_table(c, R, ldT):
+    B, L, Kp = c.shape
+    d_c = torch.from_numpy(c).to(DEV)
+    d_R = torch.from_numpy(R).to(DEV) if L > 1 else None
+    T = torch.full((B, L, ldT), -7, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs(B, L, Kp, d_c, d_R, ldT, T)
+    torch.cuda.synchronize()
+    return T
+
+
+def check_table(c, R, extra=0):
+    B, L, Kp = c.shape
+    ldT = even_ld(L, extra)
+    T = gpu_table(c, R, ldT).cpu().numpy()
+    for p in range(B):
+        want = oracle.interval_costs(c[p], R[p], ldT=ldT, nthreads=4)
+        assert np.array_equal(T[p, :, :L + 1], want[:, :L + 1]), f"problem {p}"
+    assert (T[:, :, L + 1:] == -7).all()                  # columns beyond L are not written
+    return T
+
+
+@pytest.mark.parametrize("L,K,Kp,B", [(1, 3, 16, 1), (2, 16, 16, 2), (5, 4, 16, 2), (17, 30, 32, 2), (40, 64, 64, 2),
+                                      (100, 50, 64, 1), (33, 128, 128, 1), (35, 100, 128, 2), (20, 256, 256, 1),
+                                      (18, 200, 256, 2), (300, 64, 64, 1), (1000, 10, 16, 1)])
+def test_table_shapes(L, K, Kp, B):
+    c, R = syn.random_chain_batch(range(B), L, K, 1_000_000, 10_000_000, Kp=Kp)
+    check_table(c, R, extra=(L % 3) * 2)
+
+
+def test_largest_costs_stay_exact():
+    # node and edge costs up to 2^36 - 1: sums reach 2^43 and every bit counts
+    rng = np.random.default_rng(3)
+    L, K = 70, 64
+    c = rng.integers(0, 1 << 36, size=(1, L, K)).astype(np.int64)
+    R = rng.integers(0, 1 << 36, size=(1, L - 1, K, K)).astype(np.int64)
+    c[0, :, -1] = (1 << 36) - 1
+    R[0, :, :, 0] = (1 << 36) - 1
+    check_table(c, R)
+
+
+def test_infeasible_strategies_and_operators():
+    rng = np.random.default_rng(4)
+    L, K = 48, 32
+    c = rng.integers(0, 1000, size=(2, L, K)).astype(np.int64)
+    R = rng.integers(0, 1000, size=(2, L - 1, K, K)).astype(np.int64)
+    R[0][rng.random(R[0].shape) < 0.7] = INF              # most pairs cannot be resharded
+    c[1, 20, :] = INF                                     # an operator that cannot run: no stage may hold it
+    R[1, 30, :, :] = INF                                  # an edge nobody can cross: operators 30 and 31 never share a stage
+    c[1, 5, :3] = INF
+    T = check_table(c, R)
+    assert (T[1, :21, 21:L + 1] == INF).all() and (T[1, :31, 32:L + 1] == INF).all()
+    assert T[1, 21, 22] < INF and T[1, 31, 40] < INF
+
+
+def gpu_search(T, S, s_query):
+    B, L, ldT = T.shape
+    d_T = T if isinstance(T, torch.Tensor) else torch.from_numpy(T).to(DEV)
+    bott = torch.full((B, S), -7, dtype=torch.int64, device=DEV)
+    cut = torch.full((B, S, L + 1), -7, dtype=torch.int32, device=DEV)
+    bounds = torch.full((B, s_query + 1), -7, dtype=torch.int32, device=DEV) if s_query else None
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, B, L, S), dtype=torch.uint8, device=DEV)
+    rh.rh_stage_dp_interval(B, L, S, ldT, d_T, bott, cut, s_query, bounds, ws)
+    torch.cuda.synchronize()
+    return bott.cpu().numpy(), cut.cpu().numpy(), bounds.cpu().numpy() if s_query else None
+
+
+def check_search(T, S, s_query):
+    want = oracle.stage_interval(T, S, s_query=s_query, nthreads=4)
+    got = gpu_search(T, S, s_query)
+    for g, w, name in zip(got, want, ("bottleneck", "cut", "bounds")):
+        if w is not None:
+            assert np.array_equal(g, w), name
+
+
+@pytest.mark.parametrize("L,S,B", [(1, 1, 1), (5, 5, 3), (127, 9, 2), (128, 128, 1), (129, 16, 2), (300, 33, 3),
+                                   (1000, 64, 1), (2051, 7, 1)])
+def test_search_on_any_table(L, S, B):
+    rng = np.random.default_rng(L * 7 + S)
+    ldT = even_ld(L, 4 if L % 2 else 0)
+    T = rng.integers(0, 1000 if L % 2 else 6, size=(B, L, ldT)).astype(np.int64)   # not monotone; small range = ties
+    T[rng.random(T.shape) < 0.05] = INF
+    check_search(T, S, s_query=min(S, 6))
+
+
+def test_search_on_dead_tables():
+    T = np.full((2, 140, 142), INF, dtype=np.int64)
+    T[1, :, :] = 5                                                    # every split ties: lowest i everywhere
+    check_search(T, 20, s_query=20)
+
+
+def test_table_and_search_together_and_the_plan_of_a_stage():
+    L, K, S = 200, 64, 12
+    c, R = syn.random_chain_batch([7], L, K, 100_000, 100_000)
+    ldT = even_ld(L)
+    T = gpu_table(c, R, ldT)
+    h_T = T.cpu().numpy()
+    assert np.array_equal(h_T[0, :, :L + 1], oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=4)[:, :L + 1])
+    want = oracle.stage_interval(h_T, S, s_query=S, nthreads=4)
+    got = gpu_search(T, S, S)
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+    # the plan of the bottleneck stage: the chain calls on the sub-chain reach the table's entry
+    b = got[2][0]
+    t = int(np.argmax([h_T[0, b[k], b[k + 1]] for k in range(S)]))
+    i, j = int(b[t]), int(b[t + 1])
+    assert h_T[0, i, j] == got[0][0, S - 1]
+    n = j - i
+    d_c, d_R = torch.from_numpy(c[0, i:j].copy()).to(DEV), torch.from_numpy(R[0, i:j - 1].copy()).to(DEV)
+    arg = torch.empty((1, max(n - 1, 1), K), dtype=torch.int16, device=DEV)
+    total = torch.empty(1, dtype=torch.int64, device=DEV)
+    last = torch.empty(1, dtype=torch.int32, device=DEV)
+    plan = torch.empty((1, n), dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(1, n, K, d_c, n * K, d_R if n > 1 else None, (n - 1) * K * K, arg, None, total, last)
+    rh.rh_backtrack(1, n, K, arg, last, plan)
+    torch.cuda.synchronize()
+    assert int(total.item()) == h_T[0, i, j]
+    assert oracle.plan_cost(c[0, i:j].copy(), R[0, i:j - 1].copy(), plan.cpu().numpy()[0]) == h_T[0, i, j]
+
+
+def test_stage_partition_size_with_interval_times():
+    # the stage-partition workload's L and S, each segment an operator with 64 boundary strategies
+    w = syn.STAGE_PARTITION
+    L, S, K = w["L"], w["S"], w["seg_K"]
+    c, R = syn.random_chain_batch([11], L, K, 100_000, 200_000)
+    ldT = even_ld(L, 14)
+    T = gpu_table(c, R, ldT)
+    want_T = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=oracle.num_threads())
+    h_T = T.cpu().numpy()
+    assert np.array_equal(h_T[0, :, :L + 1], want_T[:, :L + 1])
+    del want_T
+    want = oracle.stage_interval(h_T, S, s_query=S, nthreads=oracle.num_threads())
+    got = gpu_search(T, S, S)
+    for g, x in zip(got, want):
+        assert np.array_equal(g, x)
+
+
+def test_argument_errors():
+    lib = rh.lib()
+    t = torch.zeros(1 << 16, dtype=torch.int64, device=DEV)
+    out = torch.zeros(1 << 10, dtype=torch.int64, device=DEV)
+    P = lambda x: ctypes.c_void_p(x.data_ptr())
+    ic = lambda **kw: lib.rh_interval_costs(kw.get("B", 1), kw.get("L", 8), kw.get("Kp", 16), kw.get("c", P(t)),
+                                            kw.get("R", P(t)), kw.get("ld", 10), kw.get("T", P(out)), None)
+    assert ic(L=0) == -2 and ic(B=-1) == -2 and ic(ld=9) == -2 and ic(ld=8) == -2 and ic(L=16385, ld=16386) == -2
+    assert ic(Kp=48) == -3 and ic(Kp=512) == -3
+    assert ic(c=None) == -1 and ic(R=None) == -1 and ic(T=None) == -1
+    assert ic(c=ctypes.c_void_p(t.data_ptr() + 8)) == -2
+    assert ic(B=0, c=None, R=None, T=None) == 0
+    assert ic(L=1, ld=2, R=None) == 0
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, 8, 4), dtype=torch.uint8, device=DEV)
+    sd = lambda **kw: lib.rh_stage_dp_interval(kw.get("B", 1), kw.get("L", 8), kw.get("S", 4), kw.get("ld", 10),
+                                               kw.get("T", P(t)), P(t), P(t), kw.get("sq", 0), None,
+                                               kw.get("ws", P(ws)), kw.get("wsb", ws.numel()), None)
+    assert sd(S=9) == -2 and sd(S=0) == -2 and sd(ld=9) == -2 and sd(sq=5) == -2
+    assert sd(T=None) == -1 and sd(sq=2) == -1
+    assert sd(ws=None) == -4 and sd(wsb=8) == -4
+    assert rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, 8, 9) == 0
+    torch.cuda.synchronize()
