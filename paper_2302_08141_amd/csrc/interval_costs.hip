@@ -5,16 +5,17 @@
 // operator i; all L starts share the edge tables, so one step of all sweeps is a min-plus
 // product of the matrix of live cost vectors (one row per start) with R_l.
 //
-// Arithmetic: values are integers in [0, 2^52] and every intermediate sum stays <= 2^53, so the
+// Arithmetic: values are integers in [0, 2^52] and every intermediate sum stays < 2^53, so the
 // sweep runs in fp64 (exactly) -- a cell is v_add_f64 + v_min_f64 instead of five 64-bit
-// integer operations.  Sums are clamped to 2^52 (infeasible) after the minimum, which gives the
-// same result as clamping every term because the clamp is monotone.
+// integer operations.  Sums are clamped to "infeasible" after the minimum, which gives the same
+// result as clamping every term because the clamp is monotone.  Inside the kernel infeasible
+// is 2^52 - 1 (so that the conversion from int64 is an OR and a subtraction); feasible sums stay
+// below 2^51 (at most 2^15 terms below 2^36), so the two thresholds cut at the same place.
 //
-// Mapping: a lane owns Kp/64 columns b; a wave keeps up to four rows (starts) in registers and
-// broadcasts V[row][a] with two v_readlane per (row, a), so the broadcast operand travels in
-// scalar registers and R_l[a][b] is read once from LDS for all four rows.  A workgroup (4 waves,
-// 16 rows) stages R_l through LDS in 32 KiB pieces, converted to fp64 on the way in, double
-// buffered.  Rows are dealt to workgroups round-robin (row i to workgroup i mod NW): every
+// Mapping: a lane owns Kp/64 columns b; a wave keeps one row (start) in registers and
+// broadcasts V[row][a] with two v_readlane per a, so the broadcast operand travels in scalar
+// registers.  A workgroup (16 waves, 16 rows) stages R_l through LDS in 32 KiB pieces, converted
+// to fp64 on the way in, double buffered.  Rows are dealt to workgroups round-robin (row i to workgroup i mod NW): every
 // workgroup has rows of all ages, so the triangular work is balanced and all workgroups walk
 // the edges in the same order, which lets one trip to HBM serve the chip.
 #include "kernels.h"
@@ -22,12 +23,12 @@
 namespace rh {
 namespace {
 
-constexpr int kIcThreads = 256;
-constexpr int kIcWaves = 4;
-constexpr int kIcSlots = 4;                  // rows per wave
+constexpr int kIcThreads = 1024;
+constexpr int kIcWaves = 16;
+constexpr int kIcSlots = 1;                  // rows per wave
 constexpr int kIcRows = kIcWaves * kIcSlots; // rows per workgroup
 constexpr int kPiece = 4096;                 // elements of R per LDS buffer
-constexpr double kInfD = 4503599627370496.0; // 2^52
+constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
 
 __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -35,12 +36,41 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-__device__ __forceinline__ double to_f64(int64_t x) { return (double)(x < kInf ? x : kInf); }
+// Exact for 0 <= x < 2^52 - 1 (two full-rate instructions: the integer becomes the mantissa of 2^52 + x);
+// anything from 2^52 - 1 up, which includes RH_INF, becomes the kernel's infeasible value.
+__device__ __forceinline__ double to_f64(int64_t x) {
+    uint32_t lo = (uint32_t)x, hi = (uint32_t)((uint64_t)x >> 32);
+    const bool big = hi >= 0x100000u;
+    lo = big ? 0xFFFFFFFFu : lo;
+    hi = big ? 0xFFFFFu : hi;
+    return __hiloint2double((int)(hi | 0x43300000u), (int)lo) - 4503599627370496.0;
+}
+
+// back to the interface's integers: infeasible is 2^52
+__device__ __forceinline__ int64_t to_i64(double m) { return m >= kInfD ? kInf : (int64_t)m; }
 
 __device__ __forceinline__ double bcast(double x, int lane) {
     const int lo = __builtin_amdgcn_readlane(__double2loint(x), lane);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(x), lane);
     return __hiloint2double(hi, lo);
+}
+
+// x of the lane that the DPP pattern CTRL pairs this lane with (patterns that stay inside a row of 16 lanes)
+template <int CTRL>
+__device__ __forceinline__ double dpp_peer(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(__double2loint(x), __double2loint(x), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(__double2hiint(x), __double2hiint(x), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// minimum over the wave, the same value in every lane: quads, half rows and rows through DPP
+// (lane^1, lane^2, 7-lane within a half row, 15-lane within a row), the four rows through scalar registers
+__device__ __forceinline__ double wave_min(double m) {
+    m = __builtin_fmin(m, dpp_peer<0xB1>(m));    // quad_perm [1,0,3,2]
+    m = __builtin_fmin(m, dpp_peer<0x4E>(m));    // quad_perm [2,3,0,1]
+    m = __builtin_fmin(m, dpp_peer<0x141>(m));   // row_half_mirror
+    m = __builtin_fmin(m, dpp_peer<0x140>(m));   // row_mirror
+    return __builtin_fmin(__builtin_fmin(bcast(m, 0), bcast(m, 16)), __builtin_fmin(bcast(m, 32), bcast(m, 48)));
 }
 
 template <int KP>
@@ -67,16 +97,36 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
 #pragma unroll
         for (int k = 1; k < G::CPT; ++k) src[q] = k_src == k ? V[q][k] : src[q];
     }
+    // eight rows a at a time: their R values are fetched while the eight before them are worked on
+    constexpr int AB = 8;
+    static_assert(G::CH % AB == 0, "piece height");
+    double r[2][AB][G::CPT];
 #pragma unroll
-    for (int a = 0; a < G::CH; ++a) {
-        double r[G::CPT];
+    for (int u = 0; u < AB; ++u)
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) r[k] = piece[a * KP + col + 64 * k];
+        for (int k = 0; k < G::CPT; ++k) r[0][u][k] = piece[u * KP + col + 64 * k];
 #pragma unroll
-        for (int q = 0; q < NA; ++q) {
-            const double s = bcast(src[q], lane0 + a);
+    for (int blk = 0; blk < G::CH / AB; ++blk) {
+        if (blk + 1 < G::CH / AB) {
 #pragma unroll
-            for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], r[k] + s);
+            for (int u = 0; u < AB; ++u)
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k)
+                    r[(blk + 1) & 1][u][k] = piece[((blk + 1) * AB + u) * KP + col + 64 * k];
+        }
+#pragma unroll
+        for (int u = 0; u < AB; ++u) {
+            double sv[NA], t[NA][G::CPT];
+#pragma unroll
+            for (int q = 0; q < NA; ++q) sv[q] = bcast(src[q], lane0 + blk * AB + u);
+#pragma unroll
+            for (int q = 0; q < NA; ++q)
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k) t[q][k] = r[blk & 1][u][k] + sv[q];
+#pragma unroll
+            for (int q = 0; q < NA; ++q)
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], t[q][k]);
         }
     }
 }
@@ -98,7 +148,7 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
     const bool live_lane = lane < KP;             // KP < 64: the upper lanes carry infeasible columns
     const int col = live_lane ? lane : 0;
 
-    // rows of this wave, ascending: slot q holds start w + NW * (4 q + wave)
+    // rows of this wave, ascending: slot q holds start w + NW * (kIcWaves q + wave)
     int row[kIcSlots];
 #pragma unroll
     for (int q = 0; q < kIcSlots; ++q) row[q] = w + NW * (kIcWaves * q + wave);
@@ -168,6 +218,10 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k) V[q][k] = kInfD;
 
+    double tcol[kIcSlots];                        // finished columns of T waiting for their store
+#pragma unroll
+    for (int q = 0; q < kIcSlots; ++q) tcol[q] = kInfD;
+
     int g = 0;
     for (int l = l0; l < L; ++l) {
         int n_act = 0;                            // rows started so far; they start in slot order
@@ -179,16 +233,21 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
             }
             n_act += row[q] <= l ? 1 : 0;
         }
-        // T[row][l+1] = cheapest strategy of operator l for the chain row..l
+        // T[row][l+1] = cheapest strategy of operator l for the chain row..l.  Lane j mod 64 keeps column
+        // j; a full block of 64 columns (or the last, partial one) leaves as one coalesced store.
+        const int j = l + 1;
 #pragma unroll
         for (int q = 0; q < kIcSlots; ++q) {
             if (q < n_act) {
                 double m = V[q][0];
 #pragma unroll
                 for (int k = 1; k < G::CPT; ++k) m = __builtin_fmin(m, V[q][k]);
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) m = __builtin_fmin(m, __shfl_xor(m, off, 64));
-                if (lane == 0) T[(int64_t)row[q] * ldT + l + 1] = (int64_t)m;
+                m = wave_min(m);
+                tcol[q] = lane == (j & 63) ? m : tcol[q];
+                if ((j & 63) == 63 || j == L) {
+                    // columns of this block at or left of the diagonal still hold 2^52, which is their value
+                    if (lane <= (j & 63)) T[(int64_t)row[q] * ldT + (j & ~63) + lane] = to_i64(tcol[q]);
+                }
             }
         }
         if (l == L - 1) break;
@@ -202,12 +261,10 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
             const bool more = g + 1 < n_pieces;
             if (more) fetch(g + 1);               // in flight during the arithmetic
             const double* piece = lds + (g & 1) * kPiece;
-            switch (n_act) {
-                case 1: relax_piece<KP, 1>(piece, col, ch, V, acc); break;
-                case 2: relax_piece<KP, 2>(piece, col, ch, V, acc); break;
-                case 3: relax_piece<KP, 3>(piece, col, ch, V, acc); break;
-                case 4: relax_piece<KP, 4>(piece, col, ch, V, acc); break;
-                default: break;
+            static_assert(kIcSlots <= 2, "one case per number of live rows");
+            if (n_act == 1) relax_piece<KP, 1>(piece, col, ch, V, acc);
+            if constexpr (kIcSlots == 2) {
+                if (n_act == 2) relax_piece<KP, 2>(piece, col, ch, V, acc);
             }
             if (more) stash(g + 1);
             lds_barrier();                        // piece g+1 is in LDS; piece g has been read for the last time

@@ -151,13 +151,23 @@ si_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t cols, i
     if (j > L) return;
     int64_t b = INT64_MAX;
     int32_t bi = -1;
-    for (int k = 0; k < splits; ++k) {          // splits hold ascending row ranges: the first strict minimum wins
-        const int64_t at = ((int64_t)p * splits + k) * cols + j;
-        const int64_t v = pval[at];
-        const int32_t vi = pidx[at];
-        const bool take = vi >= 0 && (bi < 0 || v < b);
-        b = take ? v : b;
-        bi = take ? vi : bi;
+    // splits hold ascending row ranges: the first strict minimum wins; eight parts are fetched at a time
+    for (int k0 = 0; k0 < splits; k0 += 8) {
+        int64_t v[8];
+        int32_t vi[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u < splits ? k0 + u : splits - 1;     // a repeated part changes nothing
+            const int64_t at = ((int64_t)p * splits + k) * cols + j;
+            v[u] = pval[at];
+            vi[u] = pidx[at];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool take = vi[u] >= 0 && (bi < 0 || v[u] < b);
+            b = take ? v[u] : b;
+            bi = take ? vi[u] : bi;
+        }
     }
     const int64_t v = bi >= 0 ? b : kInf;
     cur_all[(int64_t)p * 2 * cols + j] = v;

@@ -144,12 +144,37 @@ def _stage_rows(dev):
     wb = torch.empty(1, dtype=torch.int64, device=dev)
     ws2 = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_WINDOW, 1, L, S), dtype=torch.uint8, device=dev)
     t_win = _best_ms(lambda: rh.rh_stage_dp_window(1, L, S, cost, xfer, 1, 2, wb, cut, bounds, ws2))
+    interval = _interval_rows(dev, L, S, K)
     return {"L": L, "S": S, "segment_chain": {"ops": M, "K": K}, "segment_chains_ms": t_seg,
+            "interval_stage_times": interval,
             "stage_dp_ms": t_dp, "stage_dp_cells": cells, "stage_dp_cells_per_s": cells / (t_dp * 1e-3),
             "stage_dp_256_problems_ms": t_dp_m, "stage_dp_256_problems_cells_per_s": Bm * cells / (t_dp_m * 1e-3),
             "stage_dp_method": "bisection on the monotone crossing point (exact); cells = size of the full scan",
             "bottleneck_ns_at_S": int(bott[0, S - 1].item()),
             "window_eps_half_with_transfers_ms": t_win, "window_bottleneck_ns": int(wb.item())}
+
+
+def _interval_rows(dev, L, S, K):
+    """Stage time = the stage's own best plan: every segment an operator with K boundary strategies; the table of
+    all L(L+1)/2 candidate stages, then the stage search over it."""
+    c = torch.empty((1, L, K), dtype=torch.int64, device=dev)
+    R = torch.empty((1, L - 1, K, K), dtype=torch.int64, device=dev)
+    device_fill.fill_random_chain(c, R, 11, 100_000, 200_000)
+    ldT = L + 2 - (L & 1)
+    T = torch.empty((1, L, ldT), dtype=torch.int64, device=dev)
+    t_tab = _best_ms(lambda: rh.rh_interval_costs(1, L, K, c, R, ldT, T))
+    cells_tab = sum(L - 1 - i for i in range(L)) * K * K
+    bott = torch.empty((1, S), dtype=torch.int64, device=dev)
+    cut = torch.empty((1, S, L + 1), dtype=torch.int32, device=dev)
+    bounds = torch.empty((1, S + 1), dtype=torch.int32, device=dev)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, L, S), dtype=torch.uint8, device=dev)
+    t_dp = _best_ms(lambda: rh.rh_stage_dp_interval(1, L, S, ldT, T, bott, cut, S, bounds, ws))
+    cells_dp = sum((L - s + 1) * (L - s + 2) // 2 for s in range(2, S + 1))
+    return {"K": K, "table_ms": t_tab, "table_cells": cells_tab, "table_cells_per_s": cells_tab / (t_tab * 1e-3),
+            "table_f64_lane_ops_per_s": 2 * cells_tab / (t_tab * 1e-3),
+            "search_ms": t_dp, "search_cells": cells_dp, "search_cells_per_s": cells_dp / (t_dp * 1e-3),
+            "search_table_read_gbps": cells_dp * 8 / (t_dp * 1e-3) / 1e9,
+            "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
 
 
 def _cone_rows(dev, n_cones=1024, K=64):
