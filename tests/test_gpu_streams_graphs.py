@@ -75,6 +75,65 @@ def test_graph_capture_and_replay(B, N, Kp, with_ws):
         assert torch.equal(bott, want_b) and torch.equal(bounds, want_bounds), rep
 
 
+def test_graph_of_the_stage_searches():
+    # interval table + search over it, the windowed search, and the full-scan search of a chain beyond the LDS limit
+    L, K, S = 150, 32, 9
+    hc, hR = syn.random_chain_batch([3], L, K, 1000, 5000)
+    c, R = torch.from_numpy(hc).to(DEV), torch.from_numpy(hR).to(DEV)
+    ldT = L + 2 - (L & 1)
+    T = torch.zeros((1, L, ldT), dtype=torch.int64, device=DEV)
+    out = {"b1": torch.zeros((1, S), dtype=torch.int64, device=DEV),
+           "c1": torch.zeros((1, S, L + 1), dtype=torch.int32, device=DEV),
+           "d1": torch.zeros((1, S + 1), dtype=torch.int32, device=DEV),
+           "b2": torch.zeros(1, dtype=torch.int64, device=DEV),
+           "c2": torch.zeros((1, S, L + 1), dtype=torch.int32, device=DEV),
+           "d2": torch.zeros((1, S + 1), dtype=torch.int32, device=DEV)}
+    Lb = 6200
+    cost = torch.from_numpy(syn.segment_costs(1, L)[None]).to(DEV)
+    costb = torch.from_numpy(syn.segment_costs(2, Lb)[None]).to(DEV)
+    out["b3"] = torch.zeros((1, 4), dtype=torch.int64, device=DEV)
+    out["c3"] = torch.zeros((1, 4, Lb + 1), dtype=torch.int32, device=DEV)
+    w1 = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, L, S), dtype=torch.uint8, device=DEV)
+    w2 = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_WINDOW, 1, L, S), dtype=torch.uint8, device=DEV)
+    w3 = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP, 1, Lb, 4), dtype=torch.uint8, device=DEV)
+
+    def work():
+        rh.rh_interval_costs(1, L, K, c, R, ldT, T)
+        rh.rh_stage_dp_interval(1, L, S, ldT, T, out["b1"], out["c1"], S, out["d1"], w1)
+        rh.rh_stage_dp_window(1, L, S, cost, None, 1, 1, out["b2"], out["c2"], out["d2"], w2)
+        rh.rh_stage_dp(1, Lb, 4, costb, out["b3"], out["c3"], 0, None, w3)
+
+    work()
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in out.items()}
+    want_T = T.clone()
+    o_T = oracle.interval_costs(hc[0], hR[0], ldT=ldT)
+    assert np.array_equal(want_T.cpu().numpy()[0, :, :L + 1], o_T[:, :L + 1])
+    o_b, o_c, o_d = oracle.stage_interval(want_T.cpu().numpy(), S, s_query=S)
+    assert np.array_equal(want["b1"].cpu().numpy(), o_b) and np.array_equal(want["d1"].cpu().numpy(), o_d)
+    assert np.array_equal(want["b3"].cpu().numpy(), oracle.stage_dp(costb.cpu().numpy(), 4)[0])
+
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            work()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for v in out.values():
+            v.fill_(-1)
+        T.fill_(-1)
+        for w in (w1, w2, w3):
+            w.fill_(rep + 1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(T[0, :, :L + 1], want_T[0, :, :L + 1]), rep
+        for k in out:
+            assert torch.equal(out[k], want[k]), (rep, k)
+
+
 def test_calls_on_two_streams_overlap_safely():
     B, N, Kp = 64, 60, 128
     data = []
