@@ -155,6 +155,21 @@ def test_stage_partition_size_with_interval_times():
         assert np.array_equal(g, x)
 
 
+def test_longest_chain_the_interface_takes():
+    L, K, S = 16384, 16, 3
+    c, R = syn.random_chain_batch([5], L, K, 1 << 20, 1 << 22)
+    ldT = even_ld(L)
+    T = gpu_table(c, R, ldT)
+    want_T = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=oracle.num_threads())
+    h_T = T.cpu().numpy()
+    assert np.array_equal(h_T[0, :, :L + 1], want_T[:, :L + 1])
+    del want_T
+    want = oracle.stage_interval(h_T, S, s_query=S, nthreads=oracle.num_threads())
+    got = gpu_search(T, S, S)
+    for g, x in zip(got, want):
+        assert np.array_equal(g, x)
+
+
 def test_argument_errors():
     lib = rh.lib()
     t = torch.zeros(1 << 16, dtype=torch.int64, device=DEV)
