@@ -1,0 +1,414 @@
+// Min-plus chain DP of ONE long chain, parallel along the chain.
+//
+// The forward sweep v_{i+1}[b] = c_{i+1}[b] + min_a (v_i[a] + R_i[a][b]) (Sec. 4.2 objective on the
+// linear chain of Sec. 4.3.2) is a chain of N-1 dependent steps; a single workgroup needs about
+// 10 us per step at Kp = 256, eight cooperating workgroups about 6 us, however fast the memory is.
+// Min-plus products are associative, so the chain is cut into segments of SL edges:
+//   1. for every segment but the last, all at once: the matrix M_g[a][b] = cost of the best way
+//      through the segment that enters with strategy a and leaves with strategy b (one forward
+//      sweep per entering strategy, Kp sweeps sharing the segment's edge tables; entering
+//      strategies whose node cost is infeasible are skipped);
+//   2. the vectors at the segment boundaries, v_{g+1} = v_g (x) M_g, a short sequential pass;
+//   3. the ordinary vector sweep inside every segment, all segments at once as one batch that
+//      starts from the boundary vectors: it writes arg exactly as the sequential sweep would,
+//      because the boundary vectors are the sequential sweep's own values (saturation at
+//      "infeasible" is monotone, so it commutes with the regrouping).
+// Step 1 does Kp times the arithmetic of the plain sweep, in fp64 (exact for these integers, see
+// interval_costs.hip) at two lane-operations per cell, in exchange for removing the dependent chain.
+#include "kernels.h"
+
+namespace rh {
+namespace {
+
+typedef long long ll2 __attribute__((ext_vector_type(2)));
+
+#ifndef RH_SCAN_WAVES
+#define RH_SCAN_WAVES 16
+#endif
+constexpr int kScWaves = RH_SCAN_WAVES;      // waves per workgroup of the matrix kernel
+constexpr int kScRows = 2;                   // entering strategies (rows of M_g) per wave: R values are read once for both
+constexpr int kScThreads = kScWaves * 64;
+constexpr int kScBlock = kScWaves * kScRows; // rows of M_g per workgroup
+constexpr int kBdThreads = 1024;             // the boundary kernel
+constexpr int kBdWaves = 16;
+constexpr int kScPiece = 4096;               // elements of R per LDS buffer
+constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
+
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// exact for 0 <= x < 2^52 - 1; anything larger (RH_INF included) becomes the kernel's infeasible value
+__device__ __forceinline__ double to_f64(int64_t x) {
+    uint32_t lo = (uint32_t)x, hi = (uint32_t)((uint64_t)x >> 32);
+    const bool big = hi >= 0x100000u;
+    lo = big ? 0xFFFFFFFFu : lo;
+    hi = big ? 0xFFFFFu : hi;
+    return __hiloint2double((int)(hi | 0x43300000u), (int)lo) - 4503599627370496.0;
+}
+
+__device__ __forceinline__ int64_t to_i64(double m) { return m >= kInfD ? kInf : (int64_t)m; }
+
+__device__ __forceinline__ double bcast(double x, int lane) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), lane);
+    return __hiloint2double(hi, lo);
+}
+
+template <int KP>
+struct Shape {
+    static constexpr int CPT = KP / 64;                       // columns per lane: lane + 64 k
+    static constexpr int CH = kScPiece / KP;                  // rows a of R_l per piece
+    static constexpr int NCH = KP / CH;                       // pieces per edge
+    static constexpr int EPT = kScPiece / kScThreads;         // elements per thread per piece
+    static constexpr int AB = CPT >= 4 ? 4 : 8;               // rows a whose R values are in registers ahead
+};
+
+// acc[q][k] = min(acc[q][k], V[q][a] + R[a][lane + 64 k]) for the CH rows a of one piece, NR rows of M_g at once
+template <int KP, int NR>
+__device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int lane, int ch,
+                                            const double (&V)[kScRows][Shape<KP>::CPT],
+                                            double (&acc)[kScRows][Shape<KP>::CPT]) {
+    using G = Shape<KP>;
+    const int a0 = ch * G::CH;
+    const int k_src = a0 >> 6, lane0 = a0 & 63;   // V[q][a] sits in register k_src, lane a mod 64
+    double src[NR];
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+        src[q] = V[q][0];
+#pragma unroll
+        for (int k = 1; k < G::CPT; ++k) src[q] = k_src == k ? V[q][k] : src[q];
+    }
+    double r[2][G::AB][G::CPT];
+#pragma unroll
+    for (int u = 0; u < G::AB; ++u)
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) r[0][u][k] = piece[u * KP + lane + 64 * k];
+#pragma unroll
+    for (int blk = 0; blk < G::CH / G::AB; ++blk) {
+        if (blk + 1 < G::CH / G::AB) {
+#pragma unroll
+            for (int u = 0; u < G::AB; ++u)
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k)
+                    r[(blk + 1) & 1][u][k] = piece[((blk + 1) * G::AB + u) * KP + lane + 64 * k];
+        }
+#pragma unroll
+        for (int u = 0; u < G::AB; ++u) {
+            double sv[NR];
+#pragma unroll
+            for (int q = 0; q < NR; ++q) sv[q] = bcast(src[q], lane0 + blk * G::AB + u);
+#pragma unroll
+            for (int q = 0; q < NR; ++q)
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], r[blk & 1][u][k] + sv[q]);
+        }
+    }
+}
+
+// ---- step 1: segment matrices -------------------------------------------------------------------
+// Workgroup (rb, g): up to kScBlock feasible entering strategies of segment g, kScRows per wave.  blockIdx.x = rb *
+// nseg_pad + g with nseg_pad a multiple of 8, so the workgroups of one segment, which read the same tables at
+// the same time, share an XCD and its L2.
+template <int KP>
+__global__ void __launch_bounds__(kScThreads)
+scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __restrict__ c,
+                   const int64_t* __restrict__ R, int64_t* __restrict__ M) {
+    using G = Shape<KP>;
+    extern __shared__ double lds[];               // two pieces of kScPiece doubles
+    __shared__ int32_t live_rows[KP];
+    __shared__ int32_t wave_cnt[KP / 64];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int g = blockIdx.x % nseg_pad, rb = blockIdx.x / nseg_pad;
+    if (g >= nseg) return;
+    const int l0 = g * SL;                        // first operator and first edge of the segment
+    const int64_t* c0 = c + (int64_t)l0 * KP;
+    int64_t* Mg = M + (int64_t)g * KP * KP;
+
+    // entering strategies with a feasible node cost, in ascending order
+    bool live = false;
+    if (tid < KP) live = c0[tid] < kInf;
+    const uint64_t mask = __ballot(live);
+    if (tid < KP && lane == 0) wave_cnt[wave] = __popcll(mask);
+    __syncthreads();
+    int n_live = 0, before = 0;
+#pragma unroll
+    for (int w = 0; w < KP / 64; ++w) {
+        const int n = wave_cnt[w];
+        before += w < wave ? n : 0;
+        n_live += n;
+    }
+    if (live) live_rows[before + __popcll(mask & ((1ull << lane) - 1))] = tid;
+    __syncthreads();
+
+    // rows of M_g that nobody computes are infeasible: every workgroup fills its share of them
+    for (int a = kScBlock * rb + wave; a < KP && a < kScBlock * (rb + 1); a += kScWaves) {
+        if (c0[a] >= kInf) {
+#pragma unroll
+            for (int k = 0; k < G::CPT; ++k) Mg[(int64_t)a * KP + lane + 64 * k] = kInf;
+        }
+    }
+    if (kScBlock * rb >= n_live) return;          // whole workgroup, after its last __syncthreads
+    // slot q of this wave takes the feasible strategy of rank kScBlock rb + q kScWaves + wave: ranks fill slot 0 of
+    // every wave before any slot 1
+    int a_row[kScRows];
+    int n_rows = 0;                               // wave-uniform
+#pragma unroll
+    for (int q = 0; q < kScRows; ++q) {
+        const int rank = kScBlock * rb + q * kScWaves + wave;
+        a_row[q] = rank < n_live ? live_rows[rank] : -1;
+        n_rows += rank < n_live ? 1 : 0;
+    }
+
+    const int n_pieces = SL * G::NCH;
+    int64_t pre[G::EPT];
+    auto fetch = [&](int p) {
+        const int64_t* src = R + ((int64_t)l0 * KP * KP + (int64_t)p * kScPiece);
+#pragma unroll
+        for (int e = 0; e < G::EPT / 2; ++e) {
+            const ll2 v = *reinterpret_cast<const ll2*>(src + 2 * (e * kScThreads + tid));
+            pre[2 * e] = v.x;
+            pre[2 * e + 1] = v.y;
+        }
+    };
+    auto stash = [&](int p) {
+        double* dst = lds + (p & 1) * kScPiece;
+#pragma unroll
+        for (int e = 0; e < G::EPT / 2; ++e) {
+            const int at = 2 * (e * kScThreads + tid);
+            dst[at] = to_f64(pre[2 * e]);
+            dst[at + 1] = to_f64(pre[2 * e + 1]);
+        }
+    };
+    fetch(0);
+    stash(0);
+    lds_barrier();
+
+    // node costs of operator l+1 in this lane's columns, one operator ahead
+    double cB[G::CPT];
+    int64_t cC[G::CPT];
+#pragma unroll
+    for (int k = 0; k < G::CPT; ++k) {
+        cB[k] = to_f64(c0[KP + lane + 64 * k]);                        // operator l0 + 1 exists: SL >= 1
+        cC[k] = SL > 1 ? c0[2 * KP + lane + 64 * k] : kInf;
+    }
+
+    // entering with strategy a_row costs nothing extra: v = 0 at a_row, infeasible elsewhere
+    double V[kScRows][G::CPT];
+#pragma unroll
+    for (int q = 0; q < kScRows; ++q)
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) V[q][k] = (lane + 64 * k == a_row[q]) ? 0.0 : kInfD;
+
+    int p = 0;
+    for (int e = 0; e < SL; ++e) {
+        double acc[kScRows][G::CPT];
+#pragma unroll
+        for (int q = 0; q < kScRows; ++q)
+#pragma unroll
+            for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
+        for (int ch = 0; ch < G::NCH; ++ch, ++p) {
+            const bool more = p + 1 < n_pieces;
+            if (more) fetch(p + 1);               // in flight during the arithmetic
+            const double* piece = lds + (p & 1) * kScPiece;
+            static_assert(kScRows == 2, "one case per number of live rows");
+            if (n_rows == 1) relax_piece<KP, 1>(piece, lane, ch, V, acc);
+            if (n_rows == 2) relax_piece<KP, 2>(piece, lane, ch, V, acc);
+            if (more) stash(p + 1);
+            lds_barrier();                        // piece p+1 is in LDS; piece p has been read for the last time
+        }
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) {
+#pragma unroll
+            for (int q = 0; q < kScRows; ++q)
+                V[q][k] = __builtin_fmin(cB[k] + __builtin_fmin(acc[q][k], kInfD), kInfD);
+            cB[k] = to_f64(cC[k]);
+            cC[k] = e + 3 <= SL ? c0[(int64_t)(e + 3) * KP + lane + 64 * k] : kInf;   // operator l0 + e + 3
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kScRows; ++q) {
+        if (q < n_rows) {
+#pragma unroll
+            for (int k = 0; k < G::CPT; ++k) Mg[(int64_t)a_row[q] * KP + lane + 64 * k] = to_i64(V[q][k]);
+        }
+    }
+}
+
+// ---- step 2: boundary vectors ---------------------------------------------------------------------
+// One workgroup: v_0 = c_0 (saturated), v_{g+1}[b] = min_a (v_g[a] + M_g[a][b]).  Every v_g becomes row 0 of
+// segment g's node costs in c_seg ([n_seg_total][SL+1][KP]); rows whose v_g[a] is infeasible are not read.
+template <int KP>
+__global__ void __launch_bounds__(kBdThreads)
+scan_boundary_kernel(int32_t SL, int32_t nseg, const int64_t* __restrict__ c, const int64_t* __restrict__ M,
+                     int64_t* __restrict__ c_seg) {
+    constexpr int LPG = KP / 128 > 0 ? KP / 128 : 1;      // 16-byte loads per lane per row
+    constexpr int ROW_LANES = KP / 2 < 64 ? KP / 2 : 64;  // lanes that hold a row (KP = 64: half a wave)
+    __shared__ int64_t vs[KP];
+    __shared__ int64_t part[kBdWaves][KP];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int64_t seg_stride = (int64_t)(SL + 1) * KP;
+    if (tid < KP) {
+        int64_t x = c[tid];
+        x = x < kInf ? x : kInf;
+        vs[tid] = x;
+        c_seg[tid] = x;
+    }
+    __syncthreads();
+    for (int g = 0; g < nseg; ++g) {
+        const int64_t* Mg = M + (int64_t)g * KP * KP;
+        int64_t best[2 * LPG];
+#pragma unroll
+        for (int j = 0; j < 2 * LPG; ++j) best[j] = kInf;
+        for (int a = wave; a < KP; a += kBdWaves) {
+            const int64_t va = vs[a];
+            if (va >= kInf) continue;             // wave-uniform: the row cannot matter (and may be skipped)
+            if (lane < ROW_LANES) {
+#pragma unroll
+                for (int k = 0; k < LPG; ++k) {
+                    const ll2 m = *reinterpret_cast<const ll2*>(Mg + (int64_t)a * KP + 2 * lane + 128 * k);
+                    const int64_t x0 = va + m.x, x1 = va + m.y;
+                    best[2 * k] = x0 < best[2 * k] ? x0 : best[2 * k];
+                    best[2 * k + 1] = x1 < best[2 * k + 1] ? x1 : best[2 * k + 1];
+                }
+            }
+        }
+        if (lane < ROW_LANES) {
+#pragma unroll
+            for (int k = 0; k < LPG; ++k) {
+                part[wave][2 * lane + 128 * k] = best[2 * k];
+                part[wave][2 * lane + 128 * k + 1] = best[2 * k + 1];
+            }
+        }
+        __syncthreads();
+        if (tid < KP) {
+            int64_t m = part[0][tid];
+#pragma unroll
+            for (int w = 1; w < kBdWaves; ++w) m = part[w][tid] < m ? part[w][tid] : m;
+            m = m < kInf ? m : kInf;
+            vs[tid] = m;
+            c_seg[(int64_t)(g + 1) * seg_stride + tid] = m;
+        }
+        __syncthreads();
+    }
+}
+
+// rows 1.. of every segment's node costs: c_seg[g][r][:] = c[g * SL + r][:], r >= 1, while g * SL + r < N
+__global__ void __launch_bounds__(256)
+scan_copy_c_kernel(int32_t N, int32_t SL, int32_t Kp, int32_t n_seg_total, const int64_t* __restrict__ c,
+                   int64_t* __restrict__ c_seg) {
+    const int64_t per_seg = (int64_t)SL * Kp;     // elements of rows 1..SL
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)n_seg_total * per_seg) return;
+    const int g = (int)(t / per_seg);
+    const int64_t off = t - (int64_t)g * per_seg;             // (r - 1) * Kp + column
+    const int64_t src = ((int64_t)g * SL + 1) * Kp + off;
+    if (src < (int64_t)N * Kp) c_seg[(int64_t)g * (SL + 1) * Kp + Kp + off] = c[src];
+}
+
+struct ScanPlan {
+    int32_t SL, G, r;                             // G segments: G-1 of SL edges and a last one of r edges, 1 <= r <= SL
+    size_t m_off, cseg_off, tot_off, last_off, total;
+};
+
+// Segment length: near sqrt(edges) (the boundary pass costs per segment, the final sweep per edge of a segment),
+// but long enough that the matrix kernel's workgroups are resident all at once.  Its registers allow one
+// workgroup per compute unit, and a segment whose operators have up to 96 feasible strategies takes three
+// workgroups of 32 rows, so at most 256 / 3 segments get a matrix.  Among 16 lengths the one that leaves the
+// shortest last segment wins (that segment is swept after the batch).
+constexpr int kMaxMatrixSegments = 85;
+
+__host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
+    ScanPlan p{};
+    const int E = N - 1;
+    int s0 = 16;
+    while ((int64_t)(s0 + 1) * (s0 + 1) <= E) ++s0;
+    while ((E - 1) / s0 > kMaxMatrixSegments) ++s0;
+    int best_sl = s0, best_r = E;
+    for (int sl = s0; sl < s0 + 16; ++sl) {
+        const int r = (E - 1) % sl + 1;           // 1..sl
+        if (r < best_r) {
+            best_r = r;
+            best_sl = sl;
+        }
+    }
+    p.SL = best_sl;
+    p.r = best_r;
+    p.G = (E - best_r) / best_sl + 1;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    p.m_off = 0;
+    p.cseg_off = up((size_t)(p.G - 1) * Kp * Kp * sizeof(int64_t));
+    p.tot_off = p.cseg_off + up((size_t)p.G * (p.SL + 1) * Kp * sizeof(int64_t));
+    p.last_off = p.tot_off + up((size_t)p.G * sizeof(int64_t));
+    p.total = p.last_off + up((size_t)p.G * sizeof(int32_t));
+    return p;
+}
+
+}  // namespace
+
+size_t scan_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
+    // worth it for one or two long chains; more problems fill the chip better with a workgroup (or eight) each
+    if (B < 1 || B > 2 || N < 512 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
+    return (size_t)B * plan_scan(N, Kp).total;
+}
+
+hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
+                             int64_t R_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last,
+                             void* workspace, hipStream_t stream) {
+    const ScanPlan pl = plan_scan(N, Kp);
+    const int nseg = pl.G - 1;                    // segments that need a matrix: all but the last
+    const int nseg_pad = (nseg + 7) & ~7;
+    const size_t lds = 2 * kScPiece * sizeof(double);
+    for (int p = 0; p < B; ++p) {
+        char* ws = static_cast<char*>(workspace) + (size_t)p * pl.total;
+        int64_t* M = reinterpret_cast<int64_t*>(ws + pl.m_off);
+        int64_t* c_seg = reinterpret_cast<int64_t*>(ws + pl.cseg_off);
+        int64_t* seg_total = reinterpret_cast<int64_t*>(ws + pl.tot_off);
+        int32_t* seg_last = reinterpret_cast<int32_t*>(ws + pl.last_off);
+        const int64_t* cp = c + (int64_t)p * c_bs;
+        const int64_t* Rp = R + (int64_t)p * R_bs;
+        uint16_t* argp = arg + (int64_t)p * (N - 1) * Kp;
+
+        const dim3 grid((unsigned)(((Kp + kScBlock - 1) / kScBlock) * nseg_pad));
+#define RH_SCAN(KP)                                                                                                 \
+    do {                                                                                                            \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP>),                   \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
+        if (e != hipSuccess) return e;                                                                              \
+        hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, nseg, nseg_pad,    \
+                           cp, Rp, M);                                                                              \
+        const int64_t n_copy = (int64_t)pl.G * pl.SL * KP;                                                          \
+        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N,     \
+                           pl.SL, KP, pl.G, cp, c_seg);                                                             \
+        hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3(1), dim3(kBdThreads), 0, stream, pl.SL, nseg, cp, M,    \
+                           c_seg);                                                                                  \
+    } while (0)
+        switch (Kp) {
+            case 64: RH_SCAN(64); break;
+            case 128: RH_SCAN(128); break;
+            case 256: RH_SCAN(256); break;
+            default: return hipErrorInvalidValue;
+        }
+#undef RH_SCAN
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        // step 3: the sweep inside every segment.  Full segments as one batch (their totals are scratch), then
+        // the last segment, whose final vector, total and last are the chain's.
+        const int64_t seg_c = (int64_t)(pl.SL + 1) * Kp, seg_R = (int64_t)pl.SL * Kp * Kp;
+        e = launch_chain(nseg, pl.SL + 1, Kp, c_seg, seg_c, Rp, seg_R, argp, nullptr, seg_total, seg_last, stream);
+        if (e != hipSuccess) return e;
+        e = launch_chain(1, pl.r + 1, Kp, c_seg + (int64_t)nseg * seg_c, seg_c, Rp + (int64_t)nseg * seg_R, seg_R,
+                         argp + (int64_t)nseg * pl.SL * Kp, vfinal ? vfinal + (int64_t)p * Kp : nullptr, total + p,
+                         last + p, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace rh

@@ -98,7 +98,7 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
         for (int k = 1; k < G::CPT; ++k) src[q] = k_src == k ? V[q][k] : src[q];
     }
     // eight rows a at a time: their R values are fetched while the eight before them are worked on
-    constexpr int AB = 8;
+    constexpr int AB = G::CPT >= 4 ? 4 : 8;
     static_assert(G::CH % AB == 0, "piece height");
     double r[2][AB][G::CPT];
 #pragma unroll

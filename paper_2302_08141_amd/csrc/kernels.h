@@ -25,6 +25,13 @@ hipError_t launch_chain_gang(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
                              const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
                              int64_t* total, int32_t* last, void* workspace, hipStream_t stream);
 
+// One or two long chains, parallel along the chain: segment matrices, boundary vectors, then the plain sweep
+// inside all segments as one batch (needs a workspace).
+size_t scan_workspace_bytes(int32_t B, int32_t N, int32_t Kp);   // 0 = not applicable to these sizes
+hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
+                             int64_t R_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last,
+                             void* workspace, hipStream_t stream);
+
 // Chain DP with the resharding times computed from the spec words per cell; problem p uses mesh p % n_meshes
 // (n_meshes <= 64).
 hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,

@@ -107,7 +107,7 @@ def _graph_rows(g, dev):
     return {**extra, "N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
             "reshard_ms": t_build, "reshard_write_gbps": cells * 8 / (t_build * 1e-3) / 1e9,
             "plain_write_kernel_gbps": cells * 8 / (t_write * 1e-3) / 1e9,
-            "chain_workgroups_per_problem": 8 if ws_bytes else 1,
+            "chain_method": "segments: matrices, boundary vectors, batched sweep" if ws_bytes else "one workgroup",
             "chain_ms": t_chain, "chain_cells_per_s": cells / (t_chain * 1e-3),
             "chain_hbm_gbps": cells * 8 * (1 + 1.25 / Kp) / (t_chain * 1e-3) / 1e9,
             "backtrack_ms": t_back}

@@ -123,6 +123,60 @@ def test_few_long_chains_spread_over_several_workgroups(Kp, N, B):
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 63, Kp) == 0 and rh.rh_workspace_size(0, B, N, 64) == 0
 
 
+@pytest.mark.parametrize("Kp,N,B", [(64, 512, 1), (64, 1000, 2), (128, 777, 1), (256, 600, 2), (256, 1153, 1)])
+def test_one_long_chain_cut_into_segments(Kp, N, B):
+    # with a workspace, one or two long chains are solved segment by segment (matrices, boundary vectors, batch)
+    need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp)
+    assert need > 0
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 511, 64) == 0
+    rng = np.random.default_rng(Kp + N)
+    K = Kp - (Kp // 5 if N % 2 else 0)                                # some shapes with empty candidate slots
+    c, R = syn.random_chain_batch(range(60, 60 + B), N, K, 1_000_000, 10_000_000, Kp=Kp)
+    # infeasible strategies scattered over the operators (as in tables built from specs)
+    dead = rng.random((B, N, Kp)) < 0.3
+    dead[:, :, 0] = False
+    c[dead] = INF
+    if B > 1:
+        # problem 1: ties everywhere and infeasible pairs
+        c[1] = rng.integers(0, 3, size=c[1].shape)
+        R[1] = rng.integers(0, 3, size=R[1].shape)
+        R[1][rng.random(R[1].shape) < 0.4] = INF
+        c[1, N // 2, Kp // 3:] = INF
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R, nthreads=8)
+    dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    for use_ws in (True, False, True):
+        arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+        vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+        total = torch.zeros(B, dtype=torch.int64, device=DEV)
+        last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+        ws = torch.full((need,), 0xAB, dtype=torch.uint8, device=DEV) if use_ws else None   # stale contents
+        rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(total.cpu().numpy(), o_total), use_ws
+        assert np.array_equal(last.cpu().numpy(), o_last)
+        assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+        assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+
+
+def test_long_chain_that_dies_in_the_middle():
+    # nothing is feasible from one operator on: every later segment starts from an all-infeasible vector
+    Kp, N = 64, 700
+    c, R = syn.random_chain_batch([9], N, Kp, 1000, 5000)
+    c[0, 300, :] = INF
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R)
+    dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, N, Kp), dtype=torch.uint8, device=DEV)
+    arg = torch.full((1, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+    vfinal = torch.zeros((1, Kp), dtype=torch.int64, device=DEV)
+    total = torch.zeros(1, dtype=torch.int64, device=DEV)
+    last = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(1, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+    torch.cuda.synchronize()
+    assert total.item() == INF == o_total[0] and last.item() == o_last[0]
+    assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+
+
 @pytest.mark.parametrize("Kp", [16, 64, 128])
 def test_ties_ragged_and_infeasible(Kp):
     rng = np.random.default_rng(Kp)
@@ -205,7 +259,7 @@ def test_longest_chain_the_interface_allows(Kp, B):
     c = rng.integers(0, 1 << 20, size=(B, N, Kp)).astype(np.int64)
     R = rng.integers(0, 1 << 20, size=(B, N - 1, Kp, Kp)).astype(np.int64)
     check(c, R)
-    if Kp == 128:                                                     # and through the eight-workgroup kernel
+    if Kp == 128:                                                     # and cut into segments
         dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
         ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp), dtype=torch.uint8, device=DEV)
         total = torch.zeros(B, dtype=torch.int64, device=DEV)
