@@ -6,8 +6,8 @@
 // Min-plus products are associative, so the chain is cut into segments of SL edges:
 //   1. for every segment but the last, all at once: the matrix M_g[a][b] = cost of the best way
 //      through the segment that enters with strategy a and leaves with strategy b (one forward
-//      sweep per entering strategy, Kp sweeps sharing the segment's edge tables; entering
-//      strategies whose node cost is infeasible are skipped);
+//      sweep per entering strategy, Kp sweeps sharing the segment's edge tables; strategies whose
+//      node cost is infeasible are skipped, as entering strategies and as rows of every edge table);
 //   2. the vectors at the segment boundaries, v_{g+1} = v_g (x) M_g, a short sequential pass;
 //   3. the ordinary vector sweep inside every segment, all segments at once as one batch that
 //      starts from the boundary vectors: it writes arg exactly as the sequential sweep would,
@@ -26,7 +26,10 @@ typedef long long ll2 __attribute__((ext_vector_type(2)));
 #define RH_SCAN_WAVES 16
 #endif
 constexpr int kScWaves = RH_SCAN_WAVES;      // waves per workgroup of the matrix kernel
-constexpr int kScRows = 2;                   // entering strategies (rows of M_g) per wave: R values are read once for both
+#ifndef RH_SCAN_ROWS
+#define RH_SCAN_ROWS 2
+#endif
+constexpr int kScRows = RH_SCAN_ROWS;        // entering strategies (rows of M_g) per wave: R values are read once for all
 constexpr int kScThreads = kScWaves * 64;
 constexpr int kScBlock = kScWaves * kScRows; // rows of M_g per workgroup
 constexpr int kBdThreads = 1024;             // the boundary kernel
@@ -63,48 +66,75 @@ struct Shape {
     static constexpr int CH = kScPiece / KP;                  // rows a of R_l per piece
     static constexpr int NCH = KP / CH;                       // pieces per edge
     static constexpr int EPT = kScPiece / kScThreads;         // elements per thread per piece
-    static constexpr int AB = CPT >= 4 ? 4 : 8;               // rows a whose R values are in registers ahead
+    static constexpr int AB = CPT >= 4 ? 2 : (CPT == 2 ? 4 : 8);   // rows a whose R values are in registers ahead
 };
 
-// acc[q][k] = min(acc[q][k], V[q][a] + R[a][lane + 64 k]) for the CH rows a of one piece, NR rows of M_g at once
+// acc[q][k] = min(acc[q][k], V[q][a] + R[a][lane + 64 k]) over the rows a of one piece whose strategy is feasible
+// (bit a of amask; an infeasible a has V[q][a] = infeasible and cannot win), NR rows of M_g at once.  The R values
+// of the next feasible a are fetched from LDS while the current one is worked on.
 template <int KP, int NR>
 __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int lane, int ch,
+                                            const uint64_t (&amask)[Shape<KP>::CPT],
                                             const double (&V)[kScRows][Shape<KP>::CPT],
                                             double (&acc)[kScRows][Shape<KP>::CPT]) {
     using G = Shape<KP>;
     const int a0 = ch * G::CH;
     const int k_src = a0 >> 6, lane0 = a0 & 63;   // V[q][a] sits in register k_src, lane a mod 64
+    // The selects below must stay selects: folded into an indexed read of V they would move V to scratch memory
+    // (the empty asm statements keep the compiler from doing that).
     double src[NR];
+    uint64_t word = amask[0];
+#pragma unroll
+    for (int k = 1; k < G::CPT; ++k) {
+        word = k_src == k ? amask[k] : word;
+        asm volatile("" : "+s"(word));
+    }
 #pragma unroll
     for (int q = 0; q < NR; ++q) {
         src[q] = V[q][0];
 #pragma unroll
-        for (int k = 1; k < G::CPT; ++k) src[q] = k_src == k ? V[q][k] : src[q];
+        for (int k = 1; k < G::CPT; ++k) {
+            src[q] = k_src == k ? V[q][k] : src[q];
+            asm volatile("" : "+v"(src[q]));
+        }
     }
-    double r[2][G::AB][G::CPT];
+    uint64_t bits = word >> lane0;
+    if (G::CH < 64) bits &= (1ull << G::CH) - 1;
+    if (bits == 0) return;
+    int u = __builtin_ctzll(bits);
+    bits &= bits - 1;
+    double r[G::CPT];
 #pragma unroll
-    for (int u = 0; u < G::AB; ++u)
+    for (int k = 0; k < G::CPT; ++k) r[k] = piece[u * KP + lane + 64 * k];
+    for (;;) {
+        const bool more = bits != 0;
+        const int un = more ? __builtin_ctzll(bits) : u;
+        bits &= bits - 1;
+        double rn[G::CPT];
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) r[0][u][k] = piece[u * KP + lane + 64 * k];
+        for (int k = 0; k < G::CPT; ++k) rn[k] = piece[un * KP + lane + 64 * k];
 #pragma unroll
-    for (int blk = 0; blk < G::CH / G::AB; ++blk) {
-        if (blk + 1 < G::CH / G::AB) {
+        for (int q = 0; q < NR; ++q) {
+            const double sv = bcast(src[q], lane0 + u);
 #pragma unroll
-            for (int u = 0; u < G::AB; ++u)
-#pragma unroll
-                for (int k = 0; k < G::CPT; ++k)
-                    r[(blk + 1) & 1][u][k] = piece[((blk + 1) * G::AB + u) * KP + lane + 64 * k];
+            for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], r[k] + sv);
         }
+        if (!more) break;
+        u = un;
 #pragma unroll
-        for (int u = 0; u < G::AB; ++u) {
-            double sv[NR];
-#pragma unroll
-            for (int q = 0; q < NR; ++q) sv[q] = bcast(src[q], lane0 + blk * G::AB + u);
-#pragma unroll
-            for (int q = 0; q < NR; ++q)
-#pragma unroll
-                for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], r[blk & 1][u][k] + sv[q]);
-        }
+        for (int k = 0; k < G::CPT; ++k) r[k] = rn[k];
+    }
+}
+
+// the instance of relax_piece for the number of rows this wave holds
+template <int KP, int NR>
+__device__ __forceinline__ void relax_rows(int n_rows, const double* __restrict__ piece, int lane, int ch,
+                                           const uint64_t (&amask)[Shape<KP>::CPT],
+                                           const double (&V)[kScRows][Shape<KP>::CPT],
+                                           double (&acc)[kScRows][Shape<KP>::CPT]) {
+    if (n_rows == NR) relax_piece<KP, NR>(piece, lane, ch, amask, V, acc);
+    if constexpr (NR > 1) {
+        if (n_rows < NR) relax_rows<KP, NR - 1>(n_rows, piece, lane, ch, amask, V, acc);
     }
 }
 
@@ -164,28 +194,31 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
         n_rows += rank < n_live ? 1 : 0;
     }
 
+    // Pieces travel global memory -> registers -> LDS.  A piece is fetched two pieces before it is used (raw0
+    // holds the even pieces, raw1 the odd ones), converted and stored to LDS while its predecessor is being used.
     const int n_pieces = SL * G::NCH;
-    int64_t pre[G::EPT];
-    auto fetch = [&](int p) {
+    int64_t raw0[G::EPT], raw1[G::EPT];
+    auto fetch = [&](int p, int64_t (&raw)[G::EPT]) {
         const int64_t* src = R + ((int64_t)l0 * KP * KP + (int64_t)p * kScPiece);
 #pragma unroll
         for (int e = 0; e < G::EPT / 2; ++e) {
             const ll2 v = *reinterpret_cast<const ll2*>(src + 2 * (e * kScThreads + tid));
-            pre[2 * e] = v.x;
-            pre[2 * e + 1] = v.y;
+            raw[2 * e] = v.x;
+            raw[2 * e + 1] = v.y;
         }
     };
-    auto stash = [&](int p) {
+    auto stash = [&](int p, const int64_t (&raw)[G::EPT]) {
         double* dst = lds + (p & 1) * kScPiece;
 #pragma unroll
         for (int e = 0; e < G::EPT / 2; ++e) {
             const int at = 2 * (e * kScThreads + tid);
-            dst[at] = to_f64(pre[2 * e]);
-            dst[at + 1] = to_f64(pre[2 * e + 1]);
+            dst[at] = to_f64(raw[2 * e]);
+            dst[at + 1] = to_f64(raw[2 * e + 1]);
         }
     };
-    fetch(0);
-    stash(0);
+    fetch(0, raw0);
+    if (n_pieces > 1) fetch(1, raw1);
+    stash(0, raw0);
     lds_barrier();
 
     // node costs of operator l+1 in this lane's columns, one operator ahead
@@ -197,38 +230,48 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
         cC[k] = SL > 1 ? c0[2 * KP + lane + 64 * k] : kInf;
     }
 
+    // feasible strategies of the operator the next edge leaves from: bit j of amask[k] is strategy 64 k + j
+    uint64_t amask[G::CPT];
+#pragma unroll
+    for (int k = 0; k < G::CPT; ++k) amask[k] = __ballot(c0[lane + 64 * k] < kInf);
+
     // entering with strategy a_row costs nothing extra: v = 0 at a_row, infeasible elsewhere
-    double V[kScRows][G::CPT];
+    double V[kScRows][G::CPT], acc[kScRows][G::CPT];
 #pragma unroll
     for (int q = 0; q < kScRows; ++q)
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k) V[q][k] = (lane + 64 * k == a_row[q]) ? 0.0 : kInfD;
 
-    int p = 0;
-    for (int e = 0; e < SL; ++e) {
-        double acc[kScRows][G::CPT];
-#pragma unroll
-        for (int q = 0; q < kScRows; ++q)
-#pragma unroll
-            for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
-        for (int ch = 0; ch < G::NCH; ++ch, ++p) {
-            const bool more = p + 1 < n_pieces;
-            if (more) fetch(p + 1);               // in flight during the arithmetic
-            const double* piece = lds + (p & 1) * kScPiece;
-            static_assert(kScRows == 2, "one case per number of live rows");
-            if (n_rows == 1) relax_piece<KP, 1>(piece, lane, ch, V, acc);
-            if (n_rows == 2) relax_piece<KP, 2>(piece, lane, ch, V, acc);
-            if (more) stash(p + 1);
-            lds_barrier();                        // piece p+1 is in LDS; piece p has been read for the last time
-        }
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
+    // piece p = rows a of piece p % NCH of edge p / NCH
+    auto one_piece = [&](int p, int64_t (&mine)[G::EPT], const int64_t (&next)[G::EPT]) {
+        const int ch = p & (G::NCH - 1);
+        if (ch == 0) {
 #pragma unroll
             for (int q = 0; q < kScRows; ++q)
-                V[q][k] = __builtin_fmin(cB[k] + __builtin_fmin(acc[q][k], kInfD), kInfD);
-            cB[k] = to_f64(cC[k]);
-            cC[k] = e + 3 <= SL ? c0[(int64_t)(e + 3) * KP + lane + 64 * k] : kInf;   // operator l0 + e + 3
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
         }
+        if (p + 2 < n_pieces) fetch(p + 2, mine);         // the registers of piece p are free: it is in LDS
+        const double* piece = lds + (p & 1) * kScPiece;
+        relax_rows<KP, kScRows>(n_rows, piece, lane, ch, amask, V, acc);
+        if (p + 1 < n_pieces) stash(p + 1, next);
+        lds_barrier();                                    // piece p+1 is in LDS; piece p has been read for the last time
+        if (ch == G::NCH - 1) {
+            const int e = p / G::NCH;
+#pragma unroll
+            for (int k = 0; k < G::CPT; ++k) {
+#pragma unroll
+                for (int q = 0; q < kScRows; ++q)
+                    V[q][k] = __builtin_fmin(cB[k] + __builtin_fmin(acc[q][k], kInfD), kInfD);
+                amask[k] = __ballot(cB[k] < kInfD);   // the operator just reached is where the next edge leaves from
+                cB[k] = to_f64(cC[k]);
+                cC[k] = e + 3 <= SL ? c0[(int64_t)(e + 3) * KP + lane + 64 * k] : kInf;   // operator l0 + e + 3
+            }
+        }
+    };
+    for (int p = 0; p < n_pieces; p += 2) {
+        one_piece(p, raw0, raw1);
+        if (p + 1 < n_pieces) one_piece(p + 1, raw1, raw0);
     }
 #pragma unroll
     for (int q = 0; q < kScRows; ++q) {
