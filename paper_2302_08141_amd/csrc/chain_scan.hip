@@ -35,6 +35,7 @@ constexpr int kScBlock = kScWaves * kScRows; // rows of M_g per workgroup
 constexpr int kBdThreads = 1024;             // the boundary kernel
 constexpr int kBdWaves = 16;
 constexpr int kScPiece = 4096;               // elements of R per LDS buffer
+constexpr int kMaxSegLen = 255;              // edges per segment (the planner stays below)
 constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
 
 __device__ __forceinline__ void lds_barrier() {
@@ -70,8 +71,7 @@ struct Shape {
 };
 
 // acc[q][k] = min(acc[q][k], V[q][a] + R[a][lane + 64 k]) over the rows a of one piece whose strategy is feasible
-// (bit a of amask; an infeasible a has V[q][a] = infeasible and cannot win), NR rows of M_g at once.  The R values
-// of the next feasible a are fetched from LDS while the current one is worked on.
+// (bit a of amask; an infeasible a has V[q][a] = infeasible and cannot win), NR rows of M_g at once.
 template <int KP, int NR>
 __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int lane, int ch,
                                             const uint64_t (&amask)[Shape<KP>::CPT],
@@ -100,29 +100,18 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
     }
     uint64_t bits = word >> lane0;
     if (G::CH < 64) bits &= (1ull << G::CH) - 1;
-    if (bits == 0) return;
-    int u = __builtin_ctzll(bits);
-    bits &= bits - 1;
-    double r[G::CPT];
-#pragma unroll
-    for (int k = 0; k < G::CPT; ++k) r[k] = piece[u * KP + lane + 64 * k];
-    for (;;) {
-        const bool more = bits != 0;
-        const int un = more ? __builtin_ctzll(bits) : u;
+    while (bits != 0) {
+        const int u = __builtin_ctzll(bits);
         bits &= bits - 1;
-        double rn[G::CPT];
+        double r[G::CPT];
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) rn[k] = piece[un * KP + lane + 64 * k];
+        for (int k = 0; k < G::CPT; ++k) r[k] = piece[u * KP + lane + 64 * k];
 #pragma unroll
         for (int q = 0; q < NR; ++q) {
             const double sv = bcast(src[q], lane0 + u);
 #pragma unroll
             for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], r[k] + sv);
         }
-        if (!more) break;
-        u = un;
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) r[k] = rn[k];
     }
 }
 
@@ -150,6 +139,7 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
     extern __shared__ double lds[];               // two pieces of kScPiece doubles
     __shared__ int32_t live_rows[KP];
     __shared__ int32_t wave_cnt[KP / 64];
+    __shared__ uint64_t opmask[kMaxSegLen + 1][G::CPT];   // feasible strategies of every operator of the segment
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -194,11 +184,28 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
         n_rows += rank < n_live ? 1 : 0;
     }
 
-    // Pieces travel global memory -> registers -> LDS.  A piece is fetched two pieces before it is used (raw0
-    // holds the even pieces, raw1 the odd ones), converted and stored to LDS while its predecessor is being used.
+    // bit j of opmask[o][k]: strategy 64 k + j of operator l0 + o is feasible.  An infeasible strategy a makes
+    // row a of the edge table that leaves from its operator irrelevant (v[a] is infeasible): such rows are neither
+    // fetched nor used.
+    for (int o = wave; o <= SL; o += kScWaves) {
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) {
+            const uint64_t m = __ballot(c0[(int64_t)o * KP + lane + 64 * k] < kInf);
+            if (lane == 0) opmask[o][k] = m;
+        }
+    }
+    lds_barrier();
+    auto row_live = [&](int o, int a) -> bool { return (opmask[o][a >> 6] >> (a & 63)) & 1; };
+
+    // Pieces travel global memory -> registers -> LDS.  A piece is fetched four pieces before it is used (register
+    // set p mod 4 holds piece p), converted and stored to LDS while its predecessor is being used.
+    // Piece p = rows a in [CH (p % NCH), CH (p % NCH + 1)) of the table of edge p / NCH.
     const int n_pieces = SL * G::NCH;
-    int64_t raw0[G::EPT], raw1[G::EPT];
+    int64_t raw0[G::EPT], raw1[G::EPT], raw2[G::EPT], raw3[G::EPT];
+    // Every load of the main loop is unconditional and every piece issues the same number of them, so that the
+    // waits can count outstanding loads instead of draining them all (a fetch past the end repeats the last piece).
     auto fetch = [&](int p, int64_t (&raw)[G::EPT]) {
+        p = p < n_pieces ? p : n_pieces - 1;
         const int64_t* src = R + ((int64_t)l0 * KP * KP + (int64_t)p * kScPiece);
 #pragma unroll
         for (int e = 0; e < G::EPT / 2; ++e) {
@@ -209,31 +216,39 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
     };
     auto stash = [&](int p, const int64_t (&raw)[G::EPT]) {
         double* dst = lds + (p & 1) * kScPiece;
+        const int o = p / G::NCH, a0 = (p & (G::NCH - 1)) * G::CH;
 #pragma unroll
         for (int e = 0; e < G::EPT / 2; ++e) {
             const int at = 2 * (e * kScThreads + tid);
-            dst[at] = to_f64(raw[2 * e]);
-            dst[at + 1] = to_f64(raw[2 * e + 1]);
+            if (row_live(o, a0 + at / KP)) {
+                dst[at] = to_f64(raw[2 * e]);
+                dst[at + 1] = to_f64(raw[2 * e + 1]);
+            }
         }
     };
     fetch(0, raw0);
-    if (n_pieces > 1) fetch(1, raw1);
+    fetch(1, raw1);
+    fetch(2, raw2);
+    fetch(3, raw3);
     stash(0, raw0);
     lds_barrier();
 
-    // node costs of operator l+1 in this lane's columns, one operator ahead
+    // node costs of the operator the current edge arrives at, in this lane's columns
     double cB[G::CPT];
-    int64_t cC[G::CPT];
 #pragma unroll
-    for (int k = 0; k < G::CPT; ++k) {
-        cB[k] = to_f64(c0[KP + lane + 64 * k]);                        // operator l0 + 1 exists: SL >= 1
-        cC[k] = SL > 1 ? c0[2 * KP + lane + 64 * k] : kInf;
-    }
+    for (int k = 0; k < G::CPT; ++k) cB[k] = to_f64(c0[KP + lane + 64 * k]);   // operator l0 + 1 exists: SL >= 1
 
-    // feasible strategies of the operator the next edge leaves from: bit j of amask[k] is strategy 64 k + j
+    // feasible strategies of the operator the current edge leaves from (wave-uniform copies of the table's words)
     uint64_t amask[G::CPT];
+    auto load_amask = [&](int o) {
 #pragma unroll
-    for (int k = 0; k < G::CPT; ++k) amask[k] = __ballot(c0[lane + 64 * k] < kInf);
+        for (int k = 0; k < G::CPT; ++k) {
+            const uint64_t m = opmask[o][k];
+            amask[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(m >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
+        }
+    };
+    load_amask(0);
 
     // entering with strategy a_row costs nothing extra: v = 0 at a_row, infeasible elsewhere
     double V[kScRows][G::CPT], acc[kScRows][G::CPT];
@@ -251,27 +266,37 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
 #pragma unroll
                 for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
         }
-        if (p + 2 < n_pieces) fetch(p + 2, mine);         // the registers of piece p are free: it is in LDS
+        // node costs for the edge after this one (read again by every piece of an edge: a load that only the last
+        // piece issued would be a conditional one)
+        const int e = p / G::NCH;
+        const int o_next = e + 2 <= SL ? e + 2 : SL;
+        int64_t cC[G::CPT];
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k)
+            cC[k] = c0[(int64_t)o_next * KP + lane + 64 * k];
+        fetch(p + 4, mine);                               // the registers of piece p are free: it is in LDS
         const double* piece = lds + (p & 1) * kScPiece;
         relax_rows<KP, kScRows>(n_rows, piece, lane, ch, amask, V, acc);
         if (p + 1 < n_pieces) stash(p + 1, next);
         lds_barrier();                                    // piece p+1 is in LDS; piece p has been read for the last time
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) asm volatile("" ::"v"(cC[k]));   // keeps the load in every piece
         if (ch == G::NCH - 1) {
-            const int e = p / G::NCH;
 #pragma unroll
             for (int k = 0; k < G::CPT; ++k) {
 #pragma unroll
                 for (int q = 0; q < kScRows; ++q)
                     V[q][k] = __builtin_fmin(cB[k] + __builtin_fmin(acc[q][k], kInfD), kInfD);
-                amask[k] = __ballot(cB[k] < kInfD);   // the operator just reached is where the next edge leaves from
                 cB[k] = to_f64(cC[k]);
-                cC[k] = e + 3 <= SL ? c0[(int64_t)(e + 3) * KP + lane + 64 * k] : kInf;   // operator l0 + e + 3
             }
+            load_amask(e + 1);                            // the operator just reached is where the next edge leaves from
         }
     };
-    for (int p = 0; p < n_pieces; p += 2) {
+    for (int p = 0; p < n_pieces; p += 4) {               // n_pieces is a multiple of 4 (the planner sees to it)
         one_piece(p, raw0, raw1);
-        if (p + 1 < n_pieces) one_piece(p + 1, raw1, raw0);
+        one_piece(p + 1, raw1, raw2);
+        one_piece(p + 2, raw2, raw3);
+        one_piece(p + 3, raw3, raw0);
     }
 #pragma unroll
     for (int q = 0; q < kScRows; ++q) {
@@ -373,8 +398,11 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
     int s0 = 16;
     while ((int64_t)(s0 + 1) * (s0 + 1) <= E) ++s0;
     while ((E - 1) / s0 > kMaxMatrixSegments) ++s0;
+    // the matrix kernel works through pieces in groups of four: Kp = 64 has one piece per edge
+    const int step = Kp == 64 ? 4 : 1;
+    s0 = (s0 + step - 1) / step * step;
     int best_sl = s0, best_r = E;
-    for (int sl = s0; sl < s0 + 16; ++sl) {
+    for (int sl = s0; sl < s0 + 16; sl += step) {
         const int r = (E - 1) % sl + 1;           // 1..sl
         if (r < best_r) {
             best_r = r;
@@ -398,7 +426,9 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
 size_t scan_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
     // worth it for one or two long chains; more problems fill the chip better with a workgroup (or eight) each
     if (B < 1 || B > 2 || N < 512 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
-    return (size_t)B * plan_scan(N, Kp).total;
+    const ScanPlan pl = plan_scan(N, Kp);
+    if (pl.SL > kMaxSegLen) return 0;
+    return (size_t)B * pl.total;
 }
 
 hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
