@@ -9,8 +9,9 @@
 //      sweep per entering strategy, Kp sweeps sharing the segment's edge tables; strategies whose
 //      node cost is infeasible are skipped, as entering strategies and as rows of every edge table);
 //   2. the vectors at the segment boundaries, v_{g+1} = v_g (x) M_g, a short sequential pass;
-//   3. the ordinary vector sweep inside every segment, all segments at once as one batch that
-//      starts from the boundary vectors: it writes arg exactly as the sequential sweep would,
+//   3. the ordinary vector sweep inside every third of a segment (step 1 runs as one launch per
+//      third and keeps the matrices that reach one and two thirds of a segment, so those start
+//      vectors cost one product each), all at once as one batch: it writes arg exactly as the sequential sweep would,
 //      because the boundary vectors are the sequential sweep's own values (saturation at
 //      "infeasible" is monotone, so it commutes with the regrouping).
 // Step 1 does Kp times the arithmetic of the plain sweep, in fp64 (exact for these integers, see
@@ -32,7 +33,8 @@ constexpr int kScWaves = RH_SCAN_WAVES;      // waves per workgroup of the matri
 constexpr int kScRows = RH_SCAN_ROWS;        // entering strategies (rows of M_g) per wave: R values are read once for all
 constexpr int kScThreads = kScWaves * 64;
 constexpr int kScBlock = kScWaves * kScRows; // rows of M_g per workgroup
-constexpr int kBdThreads = 1024;             // the boundary kernel
+constexpr int kScSub = 3;                    // the final sweep starts at every kScSub-th part of a segment
+constexpr int kBdThreads = 1024;             // the boundary kernels
 constexpr int kBdWaves = 16;
 constexpr int kScPiece = 4096;               // elements of R per LDS buffer
 constexpr int kMaxSegLen = 255;              // edges per segment (the planner stays below)
@@ -133,8 +135,9 @@ __device__ __forceinline__ void relax_rows(int n_rows, const double* __restrict_
 // the same time, share an XCD and its L2.
 template <int KP>
 __global__ void __launch_bounds__(kScThreads)
-scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __restrict__ c,
-                   const int64_t* __restrict__ R, int64_t* __restrict__ M) {
+scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t nseg_pad,
+                   const int64_t* __restrict__ c, const int64_t* __restrict__ R, const int64_t* __restrict__ Vin,
+                   int64_t in_stride, int64_t* __restrict__ Vout, int64_t out_stride, int32_t fill_dead) {
     using G = Shape<KP>;
     extern __shared__ double lds[];               // two pieces of kScPiece doubles
     __shared__ int32_t live_rows[KP];
@@ -145,13 +148,16 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
     const int lane = tid & 63;
     const int g = blockIdx.x % nseg_pad, rb = blockIdx.x / nseg_pad;
     if (g >= nseg) return;
-    const int l0 = g * SL;                        // first operator and first edge of the segment
+    // One launch per part of the segments: this one takes the rows from the segment's first operator + part * SLq
+    // (unit vectors for part 0, else what the launch before left in Vin) over SLq edges and leaves them in Vout.
+    const int64_t* cseg = c + (int64_t)g * SL * KP;           // node costs of the segment's first operator
+    const int l0 = g * SL + part * SLq;                       // first operator and first edge of this part
     const int64_t* c0 = c + (int64_t)l0 * KP;
-    int64_t* Mg = M + (int64_t)g * KP * KP;
+    int64_t* Mg = Vout + (int64_t)g * out_stride;
 
-    // entering strategies with a feasible node cost, in ascending order
+    // entering strategies (of the segment) with a feasible node cost, in ascending order
     bool live = false;
-    if (tid < KP) live = c0[tid] < kInf;
+    if (tid < KP) live = cseg[tid] < kInf;
     const uint64_t mask = __ballot(live);
     if (tid < KP && lane == 0) wave_cnt[wave] = __popcll(mask);
     __syncthreads();
@@ -166,8 +172,8 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
     __syncthreads();
 
     // rows of M_g that nobody computes are infeasible: every workgroup fills its share of them
-    for (int a = kScBlock * rb + wave; a < KP && a < kScBlock * (rb + 1); a += kScWaves) {
-        if (c0[a] >= kInf) {
+    for (int a = kScBlock * rb + wave; fill_dead && a < KP && a < kScBlock * (rb + 1); a += kScWaves) {
+        if (cseg[a] >= kInf) {
 #pragma unroll
             for (int k = 0; k < G::CPT; ++k) Mg[(int64_t)a * KP + lane + 64 * k] = kInf;
         }
@@ -187,7 +193,7 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
     // bit j of opmask[o][k]: strategy 64 k + j of operator l0 + o is feasible.  An infeasible strategy a makes
     // row a of the edge table that leaves from its operator irrelevant (v[a] is infeasible): such rows are neither
     // fetched nor used.
-    for (int o = wave; o <= SL; o += kScWaves) {
+    for (int o = wave; o <= SLq; o += kScWaves) {
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k) {
             const uint64_t m = __ballot(c0[(int64_t)o * KP + lane + 64 * k] < kInf);
@@ -200,7 +206,7 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
     // Pieces travel global memory -> registers -> LDS.  A piece is fetched four pieces before it is used (register
     // set p mod 4 holds piece p), converted and stored to LDS while its predecessor is being used.
     // Piece p = rows a in [CH (p % NCH), CH (p % NCH + 1)) of the table of edge p / NCH.
-    const int n_pieces = SL * G::NCH;
+    const int n_pieces = SLq * G::NCH;
     int64_t raw0[G::EPT], raw1[G::EPT], raw2[G::EPT], raw3[G::EPT];
     // Every load of the main loop is unconditional and every piece issues the same number of them, so that the
     // waits can count outstanding loads instead of draining them all (a fetch past the end repeats the last piece).
@@ -255,7 +261,11 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
 #pragma unroll
     for (int q = 0; q < kScRows; ++q)
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) V[q][k] = (lane + 64 * k == a_row[q]) ? 0.0 : kInfD;
+        for (int k = 0; k < G::CPT; ++k) {
+            V[q][k] = (lane + 64 * k == a_row[q]) ? 0.0 : kInfD;
+            if (Vin != nullptr && q < n_rows)
+                V[q][k] = to_f64(Vin[(int64_t)g * in_stride + (int64_t)a_row[q] * KP + lane + 64 * k]);
+        }
 
     // piece p = rows a of piece p % NCH of edge p / NCH
     auto one_piece = [&](int p, int64_t (&mine)[G::EPT], const int64_t (&next)[G::EPT]) {
@@ -269,7 +279,7 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
         // node costs for the edge after this one (read again by every piece of an edge: a load that only the last
         // piece issued would be a conditional one)
         const int e = p / G::NCH;
-        const int o_next = e + 2 <= SL ? e + 2 : SL;
+        const int o_next = e + 2 <= SLq ? e + 2 : SLq;
         int64_t cC[G::CPT];
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k)
@@ -308,20 +318,59 @@ scan_matrix_kernel(int32_t SL, int32_t nseg, int32_t nseg_pad, const int64_t* __
 }
 
 // ---- step 2: boundary vectors ---------------------------------------------------------------------
-// One workgroup: v_0 = c_0 (saturated), v_{g+1}[b] = min_a (v_g[a] + M_g[a][b]).  Every v_g becomes row 0 of
-// segment g's node costs in c_seg ([n_seg_total][SL+1][KP]); rows whose v_g[a] is infeasible are not read.
+// vs[b] <- min_a (vs[a] + Mg[a][b]), saturated; the whole workgroup (kBdThreads) takes part.  Rows whose vs[a] is
+// infeasible are not read (rows of entering strategies nobody computed hold nothing).
 template <int KP>
-__global__ void __launch_bounds__(kBdThreads)
-scan_boundary_kernel(int32_t SL, int32_t nseg, const int64_t* __restrict__ c, const int64_t* __restrict__ M,
-                     int64_t* __restrict__ c_seg) {
+__device__ __forceinline__ void vector_times_matrix(int64_t (&vs)[KP], int64_t (&part)[kBdWaves][KP],
+                                                    const int64_t* __restrict__ Mg, int tid, int wave, int lane) {
     constexpr int LPG = KP / 128 > 0 ? KP / 128 : 1;      // 16-byte loads per lane per row
     constexpr int ROW_LANES = KP / 2 < 64 ? KP / 2 : 64;  // lanes that hold a row (KP = 64: half a wave)
+    int64_t best[2 * LPG];
+#pragma unroll
+    for (int j = 0; j < 2 * LPG; ++j) best[j] = kInf;
+    for (int a = wave; a < KP; a += kBdWaves) {
+        const int64_t va = vs[a];
+        if (va >= kInf) continue;                 // wave-uniform
+        if (lane < ROW_LANES) {
+#pragma unroll
+            for (int k = 0; k < LPG; ++k) {
+                const ll2 m = *reinterpret_cast<const ll2*>(Mg + (int64_t)a * KP + 2 * lane + 128 * k);
+                const int64_t x0 = va + m.x, x1 = va + m.y;
+                best[2 * k] = x0 < best[2 * k] ? x0 : best[2 * k];
+                best[2 * k + 1] = x1 < best[2 * k + 1] ? x1 : best[2 * k + 1];
+            }
+        }
+    }
+    if (lane < ROW_LANES) {
+#pragma unroll
+        for (int k = 0; k < LPG; ++k) {
+            part[wave][2 * lane + 128 * k] = best[2 * k];
+            part[wave][2 * lane + 128 * k + 1] = best[2 * k + 1];
+        }
+    }
+    __syncthreads();
+    if (tid < KP) {
+        int64_t m = part[0][tid];
+#pragma unroll
+        for (int w = 1; w < kBdWaves; ++w) m = part[w][tid] < m ? part[w][tid] : m;
+        vs[tid] = m < kInf ? m : kInf;
+    }
+    __syncthreads();
+}
+
+// One workgroup: v_0 = c_0 (saturated), v_{g+1} = v_g (x) M_g.  The final sweep runs on problems of SLq = SL / kScSub
+// edges; problem q's node costs are c_seg[q][SLq + 1][KP] with the start vector as row 0: v_g is row 0 of problem
+// kScSub * g.
+template <int KP>
+__global__ void __launch_bounds__(kBdThreads)
+scan_boundary_kernel(int32_t SLq, int32_t nseg, const int64_t* __restrict__ c, const int64_t* __restrict__ M,
+                     int64_t* __restrict__ c_seg) {
     __shared__ int64_t vs[KP];
     __shared__ int64_t part[kBdWaves][KP];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    const int64_t seg_stride = (int64_t)(SL + 1) * KP;
+    const int64_t seg_stride = (int64_t)kScSub * (SLq + 1) * KP;
     if (tid < KP) {
         int64_t x = c[tid];
         x = x < kInf ? x : kInf;
@@ -330,41 +379,26 @@ scan_boundary_kernel(int32_t SL, int32_t nseg, const int64_t* __restrict__ c, co
     }
     __syncthreads();
     for (int g = 0; g < nseg; ++g) {
-        const int64_t* Mg = M + (int64_t)g * KP * KP;
-        int64_t best[2 * LPG];
-#pragma unroll
-        for (int j = 0; j < 2 * LPG; ++j) best[j] = kInf;
-        for (int a = wave; a < KP; a += kBdWaves) {
-            const int64_t va = vs[a];
-            if (va >= kInf) continue;             // wave-uniform: the row cannot matter (and may be skipped)
-            if (lane < ROW_LANES) {
-#pragma unroll
-                for (int k = 0; k < LPG; ++k) {
-                    const ll2 m = *reinterpret_cast<const ll2*>(Mg + (int64_t)a * KP + 2 * lane + 128 * k);
-                    const int64_t x0 = va + m.x, x1 = va + m.y;
-                    best[2 * k] = x0 < best[2 * k] ? x0 : best[2 * k];
-                    best[2 * k + 1] = x1 < best[2 * k + 1] ? x1 : best[2 * k + 1];
-                }
-            }
-        }
-        if (lane < ROW_LANES) {
-#pragma unroll
-            for (int k = 0; k < LPG; ++k) {
-                part[wave][2 * lane + 128 * k] = best[2 * k];
-                part[wave][2 * lane + 128 * k + 1] = best[2 * k + 1];
-            }
-        }
-        __syncthreads();
-        if (tid < KP) {
-            int64_t m = part[0][tid];
-#pragma unroll
-            for (int w = 1; w < kBdWaves; ++w) m = part[w][tid] < m ? part[w][tid] : m;
-            m = m < kInf ? m : kInf;
-            vs[tid] = m;
-            c_seg[(int64_t)(g + 1) * seg_stride + tid] = m;
-        }
-        __syncthreads();
+        vector_times_matrix<KP>(vs, part, M + (int64_t)g * KP * KP, tid, wave, lane);
+        if (tid < KP) c_seg[(int64_t)(g + 1) * seg_stride + tid] = vs[tid];
     }
+}
+
+// Workgroup (j, g): start vector of part j + 1 of segment g = v_g (x) Msub[g][j], row 0 of problem kScSub * g + j + 1.
+template <int KP>
+__global__ void __launch_bounds__(kBdThreads)
+scan_part_vectors_kernel(int32_t SLq, const int64_t* __restrict__ Msub, int64_t* __restrict__ c_seg) {
+    __shared__ int64_t vs[KP];
+    __shared__ int64_t part[kBdWaves][KP];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int j = blockIdx.x, g = blockIdx.y;
+    const int64_t prob_stride = (int64_t)(SLq + 1) * KP;
+    if (tid < KP) vs[tid] = c_seg[(int64_t)kScSub * g * prob_stride + tid];
+    __syncthreads();
+    vector_times_matrix<KP>(vs, part, Msub + ((int64_t)g * (kScSub - 1) + j) * KP * KP, tid, wave, lane);
+    if (tid < KP) c_seg[((int64_t)kScSub * g + j + 1) * prob_stride + tid] = vs[tid];
 }
 
 // rows 1.. of every segment's node costs: c_seg[g][r][:] = c[g * SL + r][:], r >= 1, while g * SL + r < N
@@ -382,14 +416,15 @@ scan_copy_c_kernel(int32_t N, int32_t SL, int32_t Kp, int32_t n_seg_total, const
 
 struct ScanPlan {
     int32_t SL, G, r;                             // G segments: G-1 of SL edges and a last one of r edges, 1 <= r <= SL
-    size_t m_off, cseg_off, tot_off, last_off, total;
+    size_t m_off, msub_off, cseg_off, tot_off, last_off, total;
 };
 
-// Segment length: near sqrt(edges) (the boundary pass costs per segment, the final sweep per edge of a segment),
+// Segment length: near sqrt(edges) (the boundary pass costs per segment, the final sweep per edge of a part),
 // but long enough that the matrix kernel's workgroups are resident all at once.  Its registers allow one
 // workgroup per compute unit, and a segment whose operators have up to 96 feasible strategies takes three
-// workgroups of 32 rows, so at most 256 / 3 segments get a matrix.  Among 16 lengths the one that leaves the
-// shortest last segment wins (that segment is swept after the batch).
+// workgroups of 32 rows, so at most 256 / 3 segments get a matrix.  SL is a multiple of kScSub, and the pieces of
+// a part a multiple of 4 (Kp = 64 has one piece per edge).  Among the next few such lengths the one that leaves
+// the shortest last segment wins (that segment is swept after the batch).
 constexpr int kMaxMatrixSegments = 85;
 
 __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
@@ -398,11 +433,11 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
     int s0 = 16;
     while ((int64_t)(s0 + 1) * (s0 + 1) <= E) ++s0;
     while ((E - 1) / s0 > kMaxMatrixSegments) ++s0;
-    // the matrix kernel works through pieces in groups of four: Kp = 64 has one piece per edge
-    const int step = Kp == 64 ? 4 : 1;
+    const int step = Kp == 64 ? 4 * kScSub : kScSub;
     s0 = (s0 + step - 1) / step * step;
     int best_sl = s0, best_r = E;
-    for (int sl = s0; sl < s0 + 16; sl += step) {
+    const int candidates = Kp == 64 ? 5 : 16;
+    for (int sl = s0; sl < s0 + candidates * step; sl += step) {
         const int r = (E - 1) % sl + 1;           // 1..sl
         if (r < best_r) {
             best_r = r;
@@ -413,11 +448,14 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
     p.r = best_r;
     p.G = (E - best_r) / best_sl + 1;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t nseg = (size_t)p.G - 1, mat = (size_t)Kp * Kp * sizeof(int64_t);
+    const size_t n_prob = nseg * kScSub + 1;      // parts of the full segments, then the last segment
     p.m_off = 0;
-    p.cseg_off = up((size_t)(p.G - 1) * Kp * Kp * sizeof(int64_t));
-    p.tot_off = p.cseg_off + up((size_t)p.G * (p.SL + 1) * Kp * sizeof(int64_t));
-    p.last_off = p.tot_off + up((size_t)p.G * sizeof(int64_t));
-    p.total = p.last_off + up((size_t)p.G * sizeof(int32_t));
+    p.msub_off = up(nseg * mat);
+    p.cseg_off = p.msub_off + up(nseg * (kScSub - 1) * mat);
+    p.tot_off = p.cseg_off + up((nseg * kScSub * (p.SL / kScSub + 1) + (size_t)p.SL + 1) * Kp * sizeof(int64_t));
+    p.last_off = p.tot_off + up(n_prob * sizeof(int64_t));
+    p.total = p.last_off + up(n_prob * sizeof(int32_t));
     return p;
 }
 
@@ -441,26 +479,41 @@ hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
     for (int p = 0; p < B; ++p) {
         char* ws = static_cast<char*>(workspace) + (size_t)p * pl.total;
         int64_t* M = reinterpret_cast<int64_t*>(ws + pl.m_off);
+        int64_t* Msub = reinterpret_cast<int64_t*>(ws + pl.msub_off);
         int64_t* c_seg = reinterpret_cast<int64_t*>(ws + pl.cseg_off);
         int64_t* seg_total = reinterpret_cast<int64_t*>(ws + pl.tot_off);
         int32_t* seg_last = reinterpret_cast<int32_t*>(ws + pl.last_off);
         const int64_t* cp = c + (int64_t)p * c_bs;
         const int64_t* Rp = R + (int64_t)p * R_bs;
         uint16_t* argp = arg + (int64_t)p * (N - 1) * Kp;
+        const int SLq = pl.SL / kScSub, n_part = nseg * kScSub;
+        const int64_t prob_c = (int64_t)(SLq + 1) * Kp, prob_R = (int64_t)SLq * Kp * Kp;
+        int64_t* c_last = c_seg + (int64_t)n_part * prob_c;   // node costs of the last segment: r + 1 rows
+        const int l_last = nseg * pl.SL;                      // its first operator
 
         const dim3 grid((unsigned)(((Kp + kScBlock - 1) / kScBlock) * nseg_pad));
+        // rows 1.. of the node costs of every part and of the last segment
+        const int64_t n_copy = (int64_t)n_part * SLq * Kp, n_copy_last = (int64_t)pl.r * Kp;
+        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N, SLq, Kp,
+                           n_part, cp, c_seg);
+        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy_last + 255) / 256)), dim3(256), 0, stream,
+                           N - l_last, pl.r, Kp, 1, cp + (int64_t)l_last * Kp, c_last);
 #define RH_SCAN(KP)                                                                                                 \
     do {                                                                                                            \
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP>),                   \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
         if (e != hipSuccess) return e;                                                                              \
-        hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, nseg, nseg_pad,    \
-                           cp, Rp, M);                                                                              \
-        const int64_t n_copy = (int64_t)pl.G * pl.SL * KP;                                                          \
-        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N,     \
-                           pl.SL, KP, pl.G, cp, c_seg);                                                             \
-        hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3(1), dim3(kBdThreads), 0, stream, pl.SL, nseg, cp, M,    \
+        for (int j = 0; j < kScSub; ++j) {                                                                          \
+            const int64_t mat = (int64_t)KP * KP, sub = (kScSub - 1) * mat;                                         \
+            const bool fin = j + 1 == kScSub;                                                                       \
+            hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,  \
+                               nseg_pad, cp, Rp, j ? Msub + (j - 1) * mat : nullptr, sub, fin ? M : Msub + j * mat, \
+                               fin ? mat : sub, fin ? 1 : 0);                                                       \
+        }                                                                                                           \
+        hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3(1), dim3(kBdThreads), 0, stream, SLq, nseg, cp, M,      \
                            c_seg);                                                                                  \
+        hipLaunchKernelGGL((scan_part_vectors_kernel<KP>), dim3(kScSub - 1, nseg), dim3(kBdThreads), 0, stream,     \
+                           SLq, Msub, c_seg);                                                                       \
     } while (0)
         switch (Kp) {
             case 64: RH_SCAN(64); break;
@@ -471,14 +524,13 @@ hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
 #undef RH_SCAN
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        // step 3: the sweep inside every segment.  Full segments as one batch (their totals are scratch), then
-        // the last segment, whose final vector, total and last are the chain's.
-        const int64_t seg_c = (int64_t)(pl.SL + 1) * Kp, seg_R = (int64_t)pl.SL * Kp * Kp;
-        e = launch_chain(nseg, pl.SL + 1, Kp, c_seg, seg_c, Rp, seg_R, argp, nullptr, seg_total, seg_last, stream);
+        // step 3: the sweep inside every part as one batch (their totals are scratch), then the last segment,
+        // whose final vector, total and last are the chain's.
+        e = launch_chain(n_part, SLq + 1, Kp, c_seg, prob_c, Rp, prob_R, argp, nullptr, seg_total, seg_last, stream);
         if (e != hipSuccess) return e;
-        e = launch_chain(1, pl.r + 1, Kp, c_seg + (int64_t)nseg * seg_c, seg_c, Rp + (int64_t)nseg * seg_R, seg_R,
-                         argp + (int64_t)nseg * pl.SL * Kp, vfinal ? vfinal + (int64_t)p * Kp : nullptr, total + p,
-                         last + p, stream);
+        e = launch_chain(1, pl.r + 1, Kp, c_last, 0, Rp + (int64_t)n_part * prob_R, 0,
+                         argp + (int64_t)l_last * Kp, vfinal ? vfinal + (int64_t)p * Kp : nullptr, total + p, last + p,
+                         stream);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
