@@ -95,7 +95,11 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
     for (int q = 0; q < NA; ++q) {
         src[q] = V[q][0];
 #pragma unroll
-        for (int k = 1; k < G::CPT; ++k) src[q] = k_src == k ? V[q][k] : src[q];
+        for (int k = 1; k < G::CPT; ++k) {
+            // must stay a select: folded into an indexed read of V it would move V to scratch memory
+            src[q] = k_src == k ? V[q][k] : src[q];
+            asm volatile("" : "+v"(src[q]));
+        }
     }
     // eight rows a at a time: their R values are fetched while the eight before them are worked on
     constexpr int AB = G::CPT >= 4 ? 4 : 8;
@@ -252,6 +256,11 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
         }
         if (l == L - 1) break;
 
+        // node costs three operators ahead: asked for now, so that the arithmetic below covers the trip
+        int64_t cD[G::CPT];
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) cD[k] = load_c(l + 3, k);
+
         double acc[kIcSlots][G::CPT];
 #pragma unroll
         for (int q = 0; q < kIcSlots; ++q)
@@ -283,7 +292,7 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
         for (int k = 0; k < G::CPT; ++k) {
             cA[k] = cB[k];
             cB[k] = to_f64(cC[k]);
-            cC[k] = load_c(l + 3, k);
+            cC[k] = cD[k];
         }
     }
 }
