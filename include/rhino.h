@@ -130,14 +130,19 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
  *   arg     [B][N-1][Kp] out (dense)
  *   vfinal  [B][Kp] out, v_{N-1}; may be NULL
  *   total   [B] out;  last [B] out
- *   workspace  optional.  rh_workspace_size(RH_WS_MINPLUS_CHAIN, B, N, Kp) is nonzero for a
- *           few (B <= 32) long (N >= 64) chains of wide tables (Kp 128 or 256); given that many
- *           bytes (256-byte aligned, contents undefined before and after) one problem is
- *           spread over eight workgroups that meet once per edge through the workspace, which
- *           is about three times faster for a single chain.  Calls that share a workspace
- *           must not overlap.  The meeting is a bounded wait: if a workgroup ever gives up
- *           (never seen; it needs the eight workgroups of a problem to be resident together),
- *           that problem returns total = -1.  With NULL, 0 the call needs no workspace.
+ *   workspace  optional; rh_workspace_size(RH_WS_MINPLUS_CHAIN, B, N, Kp) says how many bytes
+ *           help for these sizes (0 = none).  Given that many bytes (256-byte aligned, contents
+ *           undefined before and after; calls that share a workspace must not overlap):
+ *           - one or two long chains (B <= 2, N >= 512, Kp 64, 128 or 256) are cut into
+ *             segments: the min-plus matrix of every segment (all at once), the vectors at
+ *             the segment boundaries, then the plain sweep inside all segments as one batch.
+ *             Same outputs bit for bit, about ten times faster for 8192 operators x 256;
+ *           - otherwise a few (B <= 32) long (N >= 64) chains of wide tables (Kp 128 or 256)
+ *             are spread over eight workgroups each, which meet once per edge through the
+ *             workspace.  That meeting is a bounded wait: if a workgroup ever gives up (never
+ *             seen; it needs the eight workgroups of a problem resident together), the
+ *             problem returns total = -1.
+ *           With NULL, 0 the call needs no workspace.
  * Base pointers and batch strides must keep every row 16-byte aligned.
  */
 int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
