@@ -158,6 +158,26 @@ def test_one_long_chain_cut_into_segments(Kp, N, B):
         assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
 
 
+@pytest.mark.parametrize("Kp,N,B", [(64, 273, 1), (64, 2000, 3), (128, 529, 16), (256, 1041, 2), (256, 8192, 1),
+                                    (1024, 16384, 1), (512, 5000, 2), (64, 272, 1), (128, 3000, 17)])
+def test_backtrack_of_long_chains(Kp, N, B):
+    # a few long chains are walked in blocks of rows (maps per block, composed, then every block walked); any
+    # table of row indices will do, also one that never came from a sweep
+    rng = np.random.default_rng(Kp * 7 + N)
+    arg = rng.integers(0, Kp, size=(B, N - 1, Kp)).astype(np.uint16)
+    if B > 1:
+        arg[1] = (np.arange(Kp, dtype=np.uint16) * 5 + 3) % Kp        # the same permutation in every row
+    last = rng.integers(0, Kp, size=B).astype(np.int32)
+    want = oracle.backtrack(arg, last)
+    d_arg = torch.from_numpy(arg.view(np.int16)).to(DEV)
+    d_last = torch.from_numpy(last).to(DEV)
+    for fill in (-1, 7):                                              # whatever the plan buffer held before
+        plan = torch.full((B, N), fill, dtype=torch.int32, device=DEV)
+        rh.rh_backtrack(B, N, Kp, d_arg, d_last, plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(plan.cpu().numpy(), want)
+
+
 def test_long_chain_that_dies_in_the_middle():
     # nothing is feasible from one operator on: every later segment starts from an all-infeasible vector
     Kp, N = 64, 700
