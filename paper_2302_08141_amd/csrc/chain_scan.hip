@@ -203,11 +203,11 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     lds_barrier();
     auto row_live = [&](int o, int a) -> bool { return (opmask[o][a >> 6] >> (a & 63)) & 1; };
 
-    // Pieces travel global memory -> registers -> LDS.  A piece is fetched four pieces before it is used (register
-    // set p mod 4 holds piece p), converted and stored to LDS while its predecessor is being used.
+    // Pieces travel global memory -> registers -> LDS.  A piece is fetched two pieces before it is used (raw0 holds
+    // the even pieces, raw1 the odd ones), converted and stored to LDS while its predecessor is being used.
     // Piece p = rows a in [CH (p % NCH), CH (p % NCH + 1)) of the table of edge p / NCH.
     const int n_pieces = SLq * G::NCH;
-    int64_t raw0[G::EPT], raw1[G::EPT], raw2[G::EPT], raw3[G::EPT];
+    int64_t raw0[G::EPT], raw1[G::EPT];
     // Every load of the main loop is unconditional and every piece issues the same number of them, so that the
     // waits can count outstanding loads instead of draining them all (a fetch past the end repeats the last piece).
     auto fetch = [&](int p, int64_t (&raw)[G::EPT]) {
@@ -234,8 +234,6 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     };
     fetch(0, raw0);
     fetch(1, raw1);
-    fetch(2, raw2);
-    fetch(3, raw3);
     stash(0, raw0);
     lds_barrier();
 
@@ -284,7 +282,7 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k)
             cC[k] = c0[(int64_t)o_next * KP + lane + 64 * k];
-        fetch(p + 4, mine);                               // the registers of piece p are free: it is in LDS
+        fetch(p + 2, mine);                               // the registers of piece p are free: it is in LDS
         const double* piece = lds + (p & 1) * kScPiece;
         relax_rows<KP, kScRows>(n_rows, piece, lane, ch, amask, V, acc);
         if (p + 1 < n_pieces) stash(p + 1, next);
@@ -304,9 +302,9 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     };
     for (int p = 0; p < n_pieces; p += 4) {               // n_pieces is a multiple of 4 (the planner sees to it)
         one_piece(p, raw0, raw1);
-        one_piece(p + 1, raw1, raw2);
-        one_piece(p + 2, raw2, raw3);
-        one_piece(p + 3, raw3, raw0);
+        one_piece(p + 1, raw1, raw0);
+        one_piece(p + 2, raw0, raw1);
+        one_piece(p + 3, raw1, raw0);
     }
 #pragma unroll
     for (int q = 0; q < kScRows; ++q) {
