@@ -133,7 +133,7 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
  *   workspace  optional; rh_workspace_size(RH_WS_MINPLUS_CHAIN, B, N, Kp) says how many bytes
  *           help for these sizes (0 = none).  Given that many bytes (256-byte aligned, contents
  *           undefined before and after; calls that share a workspace must not overlap):
- *           - one or two long chains (B <= 2, N >= 512, Kp 64, 128 or 256) are cut into
+ *           - one or two long chains (B <= 2, N >= 128, Kp 64, 128 or 256) are cut into
  *             segments: the min-plus matrix of every segment (all at once), the vectors at
  *             the segment boundaries, then the plain sweep inside all segments as one batch.
  *             Same outputs bit for bit, about ten times faster for 8192 operators x 256;

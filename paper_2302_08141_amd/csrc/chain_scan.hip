@@ -461,7 +461,7 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
 
 size_t scan_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
     // worth it for one or two long chains; more problems fill the chip better with a workgroup (or eight) each
-    if (B < 1 || B > 2 || N < 512 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
+    if (B < 1 || B > 2 || N < 128 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
     const ScanPlan pl = plan_scan(N, Kp);
     if (pl.SL > kMaxSegLen) return 0;
     return (size_t)B * pl.total;

@@ -123,12 +123,13 @@ def test_few_long_chains_spread_over_several_workgroups(Kp, N, B):
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 63, Kp) == 0 and rh.rh_workspace_size(0, B, N, 64) == 0
 
 
-@pytest.mark.parametrize("Kp,N,B", [(64, 512, 1), (64, 1000, 2), (128, 777, 1), (256, 600, 2), (256, 1153, 1)])
+@pytest.mark.parametrize("Kp,N,B", [(64, 512, 1), (64, 1000, 2), (128, 777, 1), (256, 600, 2), (256, 1153, 1),
+                                    (64, 128, 1), (64, 243, 2), (128, 200, 1), (256, 129, 2)])
 def test_one_long_chain_cut_into_segments(Kp, N, B):
     # with a workspace, one or two long chains are solved segment by segment (matrices, boundary vectors, batch)
     need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp)
     assert need > 0
-    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 511, 64) == 0
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 127, 64) == 0
     rng = np.random.default_rng(Kp + N)
     K = Kp - (Kp // 5 if N % 2 else 0)                                # some shapes with empty candidate slots
     c, R = syn.random_chain_batch(range(60, 60 + B), N, K, 1_000_000, 10_000_000, Kp=Kp)
