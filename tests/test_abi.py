@@ -27,6 +27,15 @@ def test_host_only_calls():
     assert rh.rh_version() >= 100
     assert rh.strerror(0) == "ok" and "NULL" in rh.strerror(-1)
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 4096, 512, 128) == 0
+    # one or two long chains: room for the segment matrices (two thirds + whole), at least a Kp x Kp table each
+    one = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 8192, 256)
+    assert one > 3 * 70 * 256 * 256 * 8 and rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 2, 8192, 256) == 2 * one
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 128, 64) > 0
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 127, 64) == 0          # too short to cut
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 127, 256) > 0          # eight workgroups instead
+    gang = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 3, 8192, 256)             # three chains: eight workgroups each
+    assert 0 < gang < one
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 8192, 512) == 0
     pairs = 2 * 4097 * 16                      # two buffers of 16-byte pairs per problem
     assert rh.rh_workspace_size(rh.WS_STAGE_DP, 2, 4096, 64) >= 2 * pairs
     assert rh.rh_workspace_size(rh.WS_STAGE_DP, 64, 4096, 64) == 64 * pairs     # many problems: no split tiles
@@ -36,6 +45,10 @@ def test_host_only_calls():
     assert L.rh_minplus_chain(1, 2, 100, None, 0, None, 0, None, None, None, None, None, 0, None) == -3
     assert L.rh_minplus_chain(1, 2, 128, None, 0, None, 0, None, None, None, None, None, 0, None) == -1
     assert L.rh_stage_dp(1, 10, 11, None, None, None, 0, None, None, 0, None) == -2
+    assert L.rh_interval_costs(1, 8, 48, None, None, 10, None, None) == -3
+    assert L.rh_interval_costs(1, 8, 64, None, None, 9, None, None) == -2      # odd row stride
+    assert L.rh_stage_dp_interval(1, 8, 9, 10, None, None, None, 0, None, None, 0, None) == -2
+    assert rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, 4096, 64) > 2 * 4097 * 8
     assert L.rh_backtrack(-1, 2, 128, None, None, None, None) == -2
     assert L.rh_build_reshard(None, 1, 128, None, None, None, None, None, None, None) == -1
     assert L.rh_check_costs(None, 5, None, None) == -1
