@@ -23,14 +23,8 @@ namespace {
 
 typedef long long ll2 __attribute__((ext_vector_type(2)));
 
-#ifndef RH_SCAN_WAVES
-#define RH_SCAN_WAVES 16
-#endif
-constexpr int kScWaves = RH_SCAN_WAVES;      // waves per workgroup of the matrix kernel
-#ifndef RH_SCAN_ROWS
-#define RH_SCAN_ROWS 2
-#endif
-constexpr int kScRows = RH_SCAN_ROWS;        // entering strategies (rows of M_g) per wave: R values are read once for all
+constexpr int kScWaves = 16;                 // waves per workgroup of the matrix kernel
+constexpr int kScRows = 2;                   // entering strategies (rows of M_g) per wave: R values are read once for both
 constexpr int kScThreads = kScWaves * 64;
 constexpr int kScBlock = kScWaves * kScRows; // rows of M_g per workgroup
 constexpr int kScSub = 3;                    // the final sweep starts at every kScSub-th part of a segment
@@ -69,7 +63,6 @@ struct Shape {
     static constexpr int CH = kScPiece / KP;                  // rows a of R_l per piece
     static constexpr int NCH = KP / CH;                       // pieces per edge
     static constexpr int EPT = kScPiece / kScThreads;         // elements per thread per piece
-    static constexpr int AB = CPT >= 4 ? 2 : (CPT == 2 ? 4 : 8);   // rows a whose R values are in registers ahead
 };
 
 // acc[q][k] = min(acc[q][k], V[q][a] + R[a][lane + 64 k]) over the rows a of one piece whose strategy is feasible
