@@ -8,11 +8,13 @@
 // per cell against 6 plus 8 streamed bytes): worth it when the tables of all problems would
 // not fit in memory, and faster than streaming once many problems fill the chip.
 //
-// One workgroup per problem.  Per edge: 16 threads compute the 20-entry time table
+// One workgroup per problem.  Per edge: 20 threads compute the time table
 // ([axis][other axis splits][none | gather | all-to-all | all-reduce | impossible]), Kp threads
-// the canonical producer words; a lane owns Kp/64 consumer columns, the waves take the rows
-// round-robin; a cell is two byte compares, two nibble extractions from the producer's row of
-// the 3x3 state matrix, two LDS table reads and the min update.  Per-wave minima meet in LDS.
+// the canonical producer and consumer words; the usable producer strategies (valid spec, feasible
+// v_i) and the valid consumer strategies are listed, a lane owns up to Kp/64 of the listed
+// consumer columns, the waves take the listed rows round-robin; a cell is two byte compares,
+// two nibble extractions from the producer's row of the 3x3 state matrix, two LDS table reads
+// and the min update.  Per-wave minima meet in LDS.
 #include "kernels.h"
 #include "reshard_common.h"
 
@@ -50,11 +52,15 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
                    const uint32_t* __restrict__ in_spec, const int64_t* __restrict__ dims,
                    const int32_t* __restrict__ elem_bytes, uint16_t* __restrict__ arg,
                    int64_t* __restrict__ vfinal, int64_t* __restrict__ total, int32_t* __restrict__ last) {
-    constexpr int CPL = KP / 64;                // columns per lane: lane + 64*k
+    constexpr int CPL = KP / 64;                // consumer columns per lane: ranks lane + 64*k of the valid ones
     constexpr int kThreads = W * 64;
-    constexpr int MP = (KP + kThreads - 1) / kThreads;   // columns finished per thread
+    static_assert(KP <= kThreads, "one thread per strategy slot");
     __shared__ int64_t vs[KP];
-    __shared__ uint32_t prow[KP];
+    __shared__ uint32_t prow[KP], qrow[KP];     // canonical producer / consumer words of the edge
+    __shared__ uint16_t lrows[KP], lcols[KP];   // usable producer strategies / valid consumer strategies, ascending
+    __shared__ int64_t cnx[KP];                 // node costs of the consumer operator
+    __shared__ int64_t dml[2][4];
+    __shared__ int32_t cnt[2][CPL];
     __shared__ int64_t tab[2][2][8];            // kinds 0..4 used
     __shared__ u64 pkey[W][KP];
 
@@ -72,46 +78,93 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
     }
     const int64_t* cp = c + (int64_t)p * c_bs;
 
-#pragma unroll
-    for (int m = 0; m < MP; ++m) {
-        const int col = tid + m * kThreads;
-        if (col < KP) {
-            const int64_t x = cp[col];
-            vs[col] = x < kInf ? x : kInf;
-        }
+    if (tid < KP) {
+        const int64_t x = cp[tid];
+        vs[tid] = x < kInf ? x : kInf;
     }
     lds_barrier();
 
+    // What edge i needs from memory is asked for during edge i-1: the spec words and node costs of slot tid, the
+    // tensor shape, element size and candidate counts.
+    struct EdgeIn {
+        uint32_t osp, isp;
+        int64_t cnext, dim;                          // dim: extent tid of the edge's tensor (threads 0..3)
+        int32_t k_out, k_in, eb;
+    };
+    auto load_edge = [&](int i) {
+        EdgeIn e;
+        i = i < N - 1 ? i : N - 2;                   // a load past the last edge repeats it
+        const int slot = tid < KP ? tid : 0;
+        e.osp = out_spec[(int64_t)i * KP + slot];
+        e.isp = in_spec[(int64_t)(i + 1) * KP + slot];
+        e.cnext = cp[(int64_t)(i + 1) * KP + slot];
+        e.dim = dims[(int64_t)i * 4 + (tid & 3)];
+        e.k_out = K[i];
+        e.k_in = K[i + 1];
+        e.eb = elem_bytes[i];
+        return e;
+    };
+    // the tensor shape is indexed by the spec's dim field, so it lives in LDS (two edges, alternating)
+    EdgeIn cur = load_edge(0);
+    if (tid < 4) dml[0][tid] = cur.dim;
+    lds_barrier();
     for (int i = 0; i < N - 1; ++i) {
-        const int64_t* dm = dims + (int64_t)i * 4;
+        const EdgeIn nxt = load_edge(i + 1);
+        const int64_t* dm = dml[i & 1];
         // per-edge tables
         if (tid < 20) {
             const int x = tid / 10, o = (tid / 5) & 1, kind = tid % 5;
-            tab[x][o][kind] = axis_time(x, o, (uint32_t)kind, mesh, dm, elem_bytes[i]);
+            tab[x][o][kind] = axis_time(x, o, (uint32_t)kind, mesh, dm, cur.eb);
         }
-        for (int a = tid; a < KP; a += kThreads)
-            prow[a] = canonical(out_spec[(int64_t)i * KP + a], a, K[i], dm, mesh);
-        // this lane's consumer columns
+        // Thread t owns strategy slot t of both operators of the edge.  A producer strategy is worth a row only if
+        // its spec is a valid layout and v_i is feasible there; a consumer strategy is worth a column only if its
+        // spec is valid.  Both sets are listed in ascending order and only they are visited (on graphs built from
+        // specs about a third of the slots are valid, so this is a ninth of the cells).
+        bool row_ok = false, col_ok = false;
+        if (tid < KP) {
+            const uint32_t pw = canonical(cur.osp, tid, cur.k_out, dm, mesh);
+            const uint32_t qw = canonical(cur.isp, tid, cur.k_in, dm, mesh);
+            prow[tid] = pw;
+            qrow[tid] = qw;
+            cnx[tid] = cur.cnext;
+            row_ok = !(pw & 0x80000000u) && vs[tid] < kInf;
+            col_ok = !(qw & 0x80000000u);
+        }
+        const u64 row_mask = __ballot(row_ok), col_mask = __ballot(col_ok);
+        if (tid < KP && lane == 0) {
+            cnt[0][wave] = __popcll(row_mask);
+            cnt[1][wave] = __popcll(col_mask);
+        }
+        lds_barrier();
+        int n_rows = 0, n_cols = 0, rows_before = 0, cols_before = 0;
+#pragma unroll
+        for (int w = 0; w < CPL; ++w) {
+            rows_before += w < wave ? cnt[0][w] : 0;
+            cols_before += w < wave ? cnt[1][w] : 0;
+            n_rows += cnt[0][w];
+            n_cols += cnt[1][w];
+        }
+        const u64 below = ((u64)1 << lane) - 1;
+        if (row_ok) lrows[rows_before + __popcll(row_mask & below)] = (uint16_t)tid;
+        if (col_ok) lcols[cols_before + __popcll(col_mask & below)] = (uint16_t)tid;
+        lds_barrier();   // tab, prow, qrow and the two lists are ready
+
+        // this lane's consumer columns: ranks lane + 64 k of the valid ones
+        const int cplc = (n_cols + 63) >> 6;           // groups of 64 columns in use (wave-uniform)
         uint32_t q0b[CPL], q1b[CPL], sh0[CPL], sh1[CPL], base1[CPL];
-        bool qbad[CPL];
-        const int k_next = K[i + 1];
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
-            const int col = lane + 64 * k;
-            const uint32_t q = canonical(in_spec[(int64_t)(i + 1) * KP + col], col, k_next, dm, mesh);
-            qbad[k] = (q & 0x80000000u) != 0;
+            const int rank = lane + 64 * k;
+            const uint32_t q = qrow[rank < n_cols ? lcols[rank] : 0];
             q0b[k] = q & 0xFFu;
             q1b[k] = (q >> 8) & 0xFFu;
             sh0[k] = 4u * (q0b[k] & 3u);
             sh1[k] = 4u * (q1b[k] & 3u);
             base1[k] = ((q0b[k] & 3u) == 1u) ? 8u : 0u;   // axis 1 moves after axis 0 has the consumer's state
         }
-        int64_t cn[MP];
-#pragma unroll
-        for (int m = 0; m < MP; ++m) {
-            const int col = tid + m * kThreads;
-            cn[m] = col < KP ? cp[(int64_t)(i + 1) * KP + col] : 0;
-        }
+        // thread t finishes the column of rank t
+        const int my_col = tid < n_cols ? lcols[tid] : 0;
+        const int64_t cn = cnx[my_col];
         int64_t best[CPL];
         int32_t bidx[CPL];
 #pragma unroll
@@ -119,61 +172,67 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
             best[k] = INT64_MAX;
             bidx[k] = 0;
         }
-        lds_barrier();   // tab and prow are ready
 
         const int64_t* tab0 = &tab[0][0][0];
         const int64_t* tab1 = &tab[1][0][0];
         auto relax_row = [&](int a, uint32_t pw, int64_t va) {
-            if (pw & 0x80000000u) return;     // not a candidate: the whole row is infeasible
             const uint32_t p0b = pw & 0xFFu, p1b = (pw >> 8) & 0xFFu;
             const uint32_t row0 = kind_row(p0b & 3u), row1 = kind_row(p1b & 3u);
             const uint32_t base0 = ((p1b & 3u) == 1u) ? 8u : 0u;   // axis 0 moves while axis 1 has the producer's state
 #pragma unroll
             for (int k = 0; k < CPL; ++k) {
-                const uint32_t k0 = q0b[k] == p0b ? 0u : ((row0 >> sh0[k]) & 7u);
-                const uint32_t k1 = q1b[k] == p1b ? 0u : ((row1 >> sh1[k]) & 7u);
-                const int64_t t = tab0[base0 + k0] + tab1[base1[k] + k1];
-                const int64_t key = va + t;          // <= 3 * 2^52: anything that reaches 2^52 counts as infeasible
-                const bool lt = key < best[k];
-                best[k] = lt ? key : best[k];
-                bidx[k] = lt ? a : bidx[k];
+                if (k < cplc) {
+                    const uint32_t k0 = q0b[k] == p0b ? 0u : ((row0 >> sh0[k]) & 7u);
+                    const uint32_t k1 = q1b[k] == p1b ? 0u : ((row1 >> sh1[k]) & 7u);
+                    const int64_t t = tab0[base0 + k0] + tab1[base1[k] + k1];
+                    const int64_t key = va + t;          // <= 3 * 2^52: anything that reaches 2^52 counts as infeasible
+                    const bool lt = key < best[k];
+                    best[k] = lt ? key : best[k];
+                    bidx[k] = lt ? a : bidx[k];
+                }
             }
         };
-        // two rows per trip so that the second row's words are already on their way
-        static_assert((KP / W) % 2 == 0, "rows per wave must be even");
-        for (int a = wave; a < KP; a += 2 * W) {
-            const uint32_t pa = prow[a], pb = prow[a + W];
-            const int64_t va = vs[a], vb = vs[a + W];
+        // The waves take the usable rows round-robin, in ascending order within a wave (so that a lane's first
+        // minimum is its lowest row); two rows per trip so that the second row's words are already on their way.
+        for (int r = wave; r < n_rows; r += 2 * W) {
+            const int a = __builtin_amdgcn_readfirstlane((int)lrows[r]);
+            const bool two = r + W < n_rows;
+            const int b = __builtin_amdgcn_readfirstlane((int)lrows[two ? r + W : r]);
+            const uint32_t pa = prow[a], pb = prow[b];
+            const int64_t va = vs[a], vb = vs[b];
             relax_row(a, __builtin_amdgcn_readfirstlane(pa), va);
-            relax_row(a + W, __builtin_amdgcn_readfirstlane(pb), vb);
+            if (two) relax_row(b, __builtin_amdgcn_readfirstlane(pb), vb);
         }
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
-            const int64_t v = (qbad[k] || best[k] >= kInf) ? kInf : best[k];
+            const int64_t v = best[k] >= kInf ? kInf : best[k];
             pkey[wave][lane + 64 * k] = ((u64)v << 10) | (u64)(v >= kInf ? 0 : bidx[k]);
         }
         lds_barrier();   // the waves' minima are in LDS; every read of v_i, tab, prow is done
+        if (tid < n_cols) {
+            u64 mk = pkey[0][tid];
 #pragma unroll
-        for (int m = 0; m < MP; ++m) {
-            const int col = tid + m * kThreads;
-            if (col < KP) {
-                u64 mk = pkey[0][col];
-#pragma unroll
-                for (int w = 1; w < W; ++w) {
-                    const u64 o = pkey[w][col];
-                    mk = o < mk ? o : mk;
-                }
-                const int64_t b = (int64_t)(mk >> 10);
-                const bool dead = b >= kInf;
-                int64_t nv = cn[m] + (dead ? kInf : b);
-                nv = nv < kInf ? nv : kInf;
-                vs[col] = nv;
-                arg[((int64_t)p * (N - 1) + i) * KP + col] = dead ? (uint16_t)0 : (uint16_t)(mk & 1023u);
+            for (int w = 1; w < W; ++w) {
+                const u64 o = pkey[w][tid];
+                mk = o < mk ? o : mk;
             }
+            const int64_t b = (int64_t)(mk >> 10);
+            const bool dead = b >= kInf;
+            int64_t nv = cn + (dead ? kInf : b);
+            nv = nv < kInf ? nv : kInf;
+            vs[my_col] = nv;
+            arg[((int64_t)p * (N - 1) + i) * KP + my_col] = dead ? (uint16_t)0 : (uint16_t)(mk & 1023u);
         }
+        if (tid < KP && !col_ok) {                     // a strategy without a valid consumer spec
+            vs[tid] = kInf;
+            arg[((int64_t)p * (N - 1) + i) * KP + tid] = 0;
+        }
+        if (tid < 4) dml[(i + 1) & 1][tid] = nxt.dim;
         lds_barrier();   // v_{i+1} visible
+        cur = nxt;
     }
 
+    constexpr int MP = 1;
 #pragma unroll
     for (int m = 0; m < MP; ++m) {
         const int col = tid + m * kThreads;
