@@ -179,6 +179,41 @@ def test_backtrack_of_long_chains(Kp, N, B):
         assert np.array_equal(plan.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("Kp,N", [(64, 900), (256, 700)])
+def test_segmented_chain_with_awkward_feasibility(Kp, N):
+    # feasible sets that change from operator to operator: alternating halves, single survivors, a first operator
+    # with one feasible strategy, and edge tables with whole infeasible blocks
+    rng = np.random.default_rng(Kp + 1)
+    B = 2
+    c = rng.integers(0, 1000, size=(B, N, Kp)).astype(np.int64)
+    R = rng.integers(0, 1000, size=(B, N - 1, Kp, Kp)).astype(np.int64)
+    half = np.arange(Kp) % 2
+    for i in range(N):
+        c[0, i, half == (i % 2)] = INF                                # even operators keep odd slots and vice versa
+    for i in range(0, N, 37):
+        keep = int(rng.integers(0, Kp // 2)) * 2 + (1 - i % 2)        # one survivor, of the right parity
+        c[0, i, :] = INF
+        c[0, i, keep] = int(rng.integers(0, 1000))
+    c[1, :, Kp // 4:] = INF                                           # a quarter of the slots in use
+    R[1, :, : Kp // 8, Kp // 8: Kp // 4] = INF                        # a block nobody can cross
+    R[1, 100:, Kp // 8: Kp // 4, : Kp // 8] = INF
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R, nthreads=8)
+    assert o_total[0] < INF and o_total[1] < INF
+    dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp)
+    assert need > 0
+    ws = torch.full((need,), 0x5A, dtype=torch.uint8, device=DEV)
+    arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+    vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+    total = torch.zeros(B, dtype=torch.int64, device=DEV)
+    last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(total.cpu().numpy(), o_total) and np.array_equal(last.cpu().numpy(), o_last)
+    assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+
+
 def test_long_chain_that_dies_in_the_middle():
     # nothing is feasible from one operator on: every later segment starts from an all-infeasible vector
     Kp, N = 64, 700
