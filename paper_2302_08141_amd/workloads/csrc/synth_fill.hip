@@ -71,10 +71,17 @@ write_kernel(ull2* __restrict__ dst, int64_t n16, unsigned long long value) {
 
 // The same read-only stream with the access shape of a tuned streaming kernel: a 1024-thread
 // workgroup owns contiguous 256 KiB chunks and keeps 16 loads per lane in flight.
+// slices = 0: chunk ch goes to workgroup ch mod gridDim.  slices = 1: every workgroup walks a contiguous
+// range of chunks front to back (the access shape of one workgroup per problem table).
 __global__ void __launch_bounds__(1024)
-read_wide_kernel(const ull2* __restrict__ src, int64_t n_chunks, unsigned long long* __restrict__ sink) {
+read_wide_kernel(const ull2* __restrict__ src, int64_t n_chunks, int32_t slices,
+                 unsigned long long* __restrict__ sink) {
     ull2 acc = {0ull, 0ull};
-    for (int64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+    const int64_t per = (n_chunks + gridDim.x - 1) / gridDim.x;
+    const int64_t first = slices ? blockIdx.x * per : blockIdx.x;
+    const int64_t end = slices ? (first + per < n_chunks ? first + per : n_chunks) : n_chunks;
+    const int64_t step = slices ? 1 : gridDim.x;
+    for (int64_t ch = first; ch < end; ch += step) {
         const ull2* p = src + ch * 16384 + threadIdx.x;
         ull2 v[16];
 #pragma unroll
@@ -87,12 +94,22 @@ read_wide_kernel(const ull2* __restrict__ src, int64_t n_chunks, unsigned long l
 
 }  // namespace
 
-extern "C" int synth_stream_read_wide(const void* src, int64_t bytes, void* sink8, int32_t blocks, void* stream) {
+static int launch_read_wide(const void* src, int64_t bytes, void* sink8, int32_t blocks, int32_t slices,
+                            void* stream) {
     if (!src || !sink8 || bytes < 0 || (bytes % 262144) || blocks < 1) return -1;
     if (bytes == 0) return 0;
     hipLaunchKernelGGL(read_wide_kernel, dim3((unsigned)blocks), dim3(1024), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const ull2*>(src), bytes / 262144, static_cast<unsigned long long*>(sink8));
+                       static_cast<const ull2*>(src), bytes / 262144, slices,
+                       static_cast<unsigned long long*>(sink8));
     return hipGetLastError() == hipSuccess ? 0 : -2;
+}
+
+extern "C" int synth_stream_read_wide(const void* src, int64_t bytes, void* sink8, int32_t blocks, void* stream) {
+    return launch_read_wide(src, bytes, sink8, blocks, 0, stream);
+}
+
+extern "C" int synth_stream_read_slices(const void* src, int64_t bytes, void* sink8, int32_t blocks, void* stream) {
+    return launch_read_wide(src, bytes, sink8, blocks, 1, stream);
 }
 
 extern "C" int synth_stream_write(void* dst, int64_t bytes, uint64_t value, int32_t blocks, void* stream) {

@@ -35,6 +35,8 @@ def lib():
                                          ctypes.c_void_p]
         L.synth_stream_write.restype = ctypes.c_int
         L.synth_stream_read_wide.argtypes = L.synth_stream_read.argtypes
+        L.synth_stream_read_slices.argtypes = L.synth_stream_read.argtypes
+        L.synth_stream_read_slices.restype = ctypes.c_int
         L.synth_stream_copy.restype = L.synth_stream_read.restype = L.synth_stream_read_wide.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -72,13 +74,15 @@ def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 8192) -> Non
         raise RuntimeError(f"synth_stream_copy rc={rc}")
 
 
-def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 8192, wide: bool = False) -> None:
+def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 8192, wide: bool = False,
+                slices: bool = False) -> None:
     """Plain read-only streaming kernel over src (yardstick for the achievable HBM read rate).
-    wide: 1024-thread workgroups on contiguous 256 KiB chunks with 16 loads per lane in flight."""
+    wide: 1024-thread workgroups on contiguous 256 KiB chunks with 16 loads per lane in flight, chunks dealt
+    round-robin; slices: the same workgroups, each walking its own contiguous range of chunks."""
     assert src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.dtype == torch.int64 and sink.numel() >= 1
     nbytes = src.numel() * src.element_size()
-    assert nbytes % (262144 if wide else 16) == 0
-    fn = lib().synth_stream_read_wide if wide else lib().synth_stream_read
+    assert nbytes % (262144 if (wide or slices) else 16) == 0
+    fn = lib().synth_stream_read_slices if slices else lib().synth_stream_read_wide if wide else lib().synth_stream_read
     rc = fn(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()), blocks,
             ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if rc != 0:
