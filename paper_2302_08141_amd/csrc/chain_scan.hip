@@ -32,6 +32,7 @@ constexpr int kBdThreads = 1024;             // the boundary kernels
 constexpr int kBdWaves = 16;
 constexpr int kScPiece = 4096;               // elements of R per LDS buffer
 constexpr int kMaxSegLen = 255;              // edges per segment (the planner stays below)
+constexpr int kMaxPartLen = kMaxSegLen / kScSub;   // edges per part of a segment
 constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
 
 __device__ __forceinline__ void lds_barrier() {
@@ -59,31 +60,41 @@ __device__ __forceinline__ double bcast(double x, int lane) {
 
 template <int KP>
 struct Shape {
-    static constexpr int CPT = KP / 64;                       // columns per lane: lane + 64 k
-    static constexpr int CH = kScPiece / KP;                  // rows a of R_l per piece
-    static constexpr int NCH = KP / CH;                       // pieces per edge
+    static constexpr int CPT = KP / 64;                       // columns per lane: rank lane + 64 k
     static constexpr int EPT = kScPiece / kScThreads;         // elements per thread per piece
+    static_assert(EPT == 4, "a thread stages four neighbouring columns of one row");
 };
 
-// acc[q][k] = min(acc[q][k], V[q][a] + R[a][lane + 64 k]) over the rows a of one piece whose strategy is feasible
-// (bit a of amask; an infeasible a has V[q][a] = infeasible and cannot win), NR rows of M_g at once.
-template <int KP, int NR>
-__device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int lane, int ch,
-                                            const uint64_t (&amask)[Shape<KP>::CPT],
+// Layout of the table of one edge in LDS.  Only the rows of strategies that are feasible where the edge leaves
+// from (na of them) and the columns of strategies feasible where it arrives (nb) are staged, in rank order: a
+// row of a piece has 64 << lgc columns (the power of two that holds nb), a piece 64 >> lgc rows.
+struct EdgeShape {
+    int na, nb, lgc, np;                          // np = pieces of the edge, at least one
+};
+
+__device__ __forceinline__ EdgeShape edge_shape(int na, int nb) {
+    EdgeShape s;
+    s.na = na;
+    s.nb = nb;
+    s.lgc = nb <= 64 ? 0 : nb <= 128 ? 1 : 2;
+    const int np = (na + (64 >> s.lgc) - 1) >> (6 - s.lgc);
+    s.np = np > 0 ? np : 1;
+    return s;
+}
+
+// acc[q][k] = min(acc[q][k], V[q][rank0 + r] + piece[r][lane + 64 k]) over the rows r < nr of one piece (nr a
+// multiple of 4: the piece's rows past the last feasible strategy hold "infeasible", and so does V there), NR
+// rows of M_g at once, CC groups of 64 columns.
+template <int KP, int NR, int CC>
+__device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int lane, int nr, int rank0,
                                             const double (&V)[kScRows][Shape<KP>::CPT],
                                             double (&acc)[kScRows][Shape<KP>::CPT]) {
     using G = Shape<KP>;
-    const int a0 = ch * G::CH;
-    const int k_src = a0 >> 6, lane0 = a0 & 63;   // V[q][a] sits in register k_src, lane a mod 64
+    constexpr int W = 64 * CC;
+    const int k_src = rank0 >> 6, lane0 = rank0 & 63;   // V[q][rank] sits in register rank / 64, lane rank mod 64
     // The selects below must stay selects: folded into an indexed read of V they would move V to scratch memory
     // (the empty asm statements keep the compiler from doing that).
     double src[NR];
-    uint64_t word = amask[0];
-#pragma unroll
-    for (int k = 1; k < G::CPT; ++k) {
-        word = k_src == k ? amask[k] : word;
-        asm volatile("" : "+s"(word));
-    }
 #pragma unroll
     for (int q = 0; q < NR; ++q) {
         src[q] = V[q][0];
@@ -93,32 +104,35 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
             asm volatile("" : "+v"(src[q]));
         }
     }
-    uint64_t bits = word >> lane0;
-    if (G::CH < 64) bits &= (1ull << G::CH) - 1;
-    while (bits != 0) {
-        const int u = __builtin_ctzll(bits);
-        bits &= bits - 1;
-        double r[G::CPT];
+    constexpr int UR = CC == 4 ? 2 : 4;           // rows per trip: eight LDS values in flight
+    for (int r = 0; r < nr; r += UR) {
+        double rv[UR][CC];
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) r[k] = piece[u * KP + lane + 64 * k];
+        for (int u = 0; u < UR; ++u)
 #pragma unroll
-        for (int q = 0; q < NR; ++q) {
-            const double sv = bcast(src[q], lane0 + u);
+            for (int k = 0; k < CC; ++k) rv[u][k] = piece[(r + u) * W + lane + 64 * k];
 #pragma unroll
-            for (int k = 0; k < G::CPT; ++k) acc[q][k] = __builtin_fmin(acc[q][k], r[k] + sv);
-        }
+        for (int u = 0; u < UR; ++u)
+#pragma unroll
+            for (int q = 0; q < NR; ++q) {
+                const double sv = bcast(src[q], lane0 + r + u);
+#pragma unroll
+                for (int k = 0; k < CC; ++k) acc[q][k] = __builtin_fmin(acc[q][k], rv[u][k] + sv);
+            }
     }
 }
 
-// the instance of relax_piece for the number of rows this wave holds
+// the instance of relax_piece for the number of rows this wave holds and the width of the piece
 template <int KP, int NR>
-__device__ __forceinline__ void relax_rows(int n_rows, const double* __restrict__ piece, int lane, int ch,
-                                           const uint64_t (&amask)[Shape<KP>::CPT],
-                                           const double (&V)[kScRows][Shape<KP>::CPT],
-                                           double (&acc)[kScRows][Shape<KP>::CPT]) {
-    if (n_rows == NR) relax_piece<KP, NR>(piece, lane, ch, amask, V, acc);
-    if constexpr (NR > 1) {
-        if (n_rows < NR) relax_rows<KP, NR - 1>(n_rows, piece, lane, ch, amask, V, acc);
+__device__ __forceinline__ void relax_width(int lgc, const double* __restrict__ piece, int lane, int nr, int rank0,
+                                            const double (&V)[kScRows][Shape<KP>::CPT],
+                                            double (&acc)[kScRows][Shape<KP>::CPT]) {
+    if (lgc == 0) relax_piece<KP, NR, 1>(piece, lane, nr, rank0, V, acc);
+    if constexpr (KP >= 128) {
+        if (lgc == 1) relax_piece<KP, NR, 2>(piece, lane, nr, rank0, V, acc);
+    }
+    if constexpr (KP >= 256) {
+        if (lgc == 2) relax_piece<KP, NR, 4>(piece, lane, nr, rank0, V, acc);
     }
 }
 
@@ -135,7 +149,10 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     extern __shared__ double lds[];               // two pieces of kScPiece doubles
     __shared__ int32_t live_rows[KP];
     __shared__ int32_t wave_cnt[KP / 64];
-    __shared__ uint64_t opmask[kMaxSegLen + 1][G::CPT];   // feasible strategies of every operator of the segment
+    // lidx[o][rank] = the rank-th feasible strategy of operator l0 + o (ranks past the last repeat it, so that a
+    // lookup is always a valid strategy); nl[o] = how many there are
+    __shared__ __align__(4) uint8_t lidx[kMaxPartLen + 1][KP];
+    __shared__ int32_t nl[kMaxPartLen + 1];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -183,85 +200,101 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         n_rows += rank < n_live ? 1 : 0;
     }
 
-    // bit j of opmask[o][k]: strategy 64 k + j of operator l0 + o is feasible.  An infeasible strategy a makes
-    // row a of the edge table that leaves from its operator irrelevant (v[a] is infeasible): such rows are neither
-    // fetched nor used.
+    // The feasible strategies of every operator of the part, ranked.  An infeasible strategy makes its row of the
+    // edge table that leaves from its operator and its column of the table that arrives there irrelevant (the
+    // vector is infeasible there whatever the table says): such rows and columns are neither fetched nor used.
     for (int o = wave; o <= SLq; o += kScWaves) {
+        int base = 0, last_live = 0;
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k) {
-            const uint64_t m = __ballot(c0[(int64_t)o * KP + lane + 64 * k] < kInf);
-            if (lane == 0) opmask[o][k] = m;
+            const bool ok = c0[(int64_t)o * KP + lane + 64 * k] < kInf;
+            const uint64_t m = __ballot(ok);
+            if (ok) lidx[o][base + __popcll(m & ((1ull << lane) - 1))] = (uint8_t)(lane + 64 * k);
+            if (m != 0) last_live = 64 * k + 63 - __builtin_clzll(m);
+            base += __popcll(m);
         }
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) {
+            if (lane + 64 * k >= base) lidx[o][lane + 64 * k] = (uint8_t)last_live;
+        }
+        if (lane == 0) nl[o] = base;
     }
     lds_barrier();
-    auto row_live = [&](int o, int a) -> bool { return (opmask[o][a >> 6] >> (a & 63)) & 1; };
+    auto count_at = [&](int o) -> int { return __builtin_amdgcn_readfirstlane(nl[o]); };
 
     // Pieces travel global memory -> registers -> LDS.  A piece is fetched two pieces before it is used (raw0 holds
-    // the even pieces, raw1 the odd ones), converted and stored to LDS while its predecessor is being used.
-    // Piece p = rows a in [CH (p % NCH), CH (p % NCH + 1)) of the table of edge p / NCH.
-    const int n_pieces = SLq * G::NCH;
-    int64_t raw0[G::EPT], raw1[G::EPT];
+    // the even pieces, raw1 the odd ones), converted and stored to LDS while its predecessor is being used.  The
+    // pieces of an edge follow each other, then the next edge's; a cursor names one.
+    struct Cursor {
+        int e, j;                                 // edge of the part, piece of the edge
+        EdgeShape s;
+        bool past;                                // ran off the end: stands on the last piece
+    };
+    auto cursor_at = [&](int e) -> Cursor { return Cursor{e, 0, edge_shape(count_at(e), count_at(e + 1)), false}; };
+    auto advance = [&](Cursor cur) -> Cursor {
+        if (cur.j + 1 < cur.s.np) {
+            ++cur.j;
+            return cur;
+        }
+        if (cur.e + 1 < SLq) return cursor_at(cur.e + 1);
+        cur.past = true;
+        return cur;
+    };
+    // A thread stages the four neighbouring columns 4 tid .. 4 tid + 3 (in rank order) of one row of the piece.
     // Every load of the main loop is unconditional and every piece issues the same number of them, so that the
-    // waits can count outstanding loads instead of draining them all (a fetch past the end repeats the last piece).
-    auto fetch = [&](int p, int64_t (&raw)[G::EPT]) {
-        p = p < n_pieces ? p : n_pieces - 1;
-        const int64_t* src = R + ((int64_t)l0 * KP * KP + (int64_t)p * kScPiece);
+    // waits can count outstanding loads instead of draining them all (a fetch past the end repeats the last piece,
+    // ranks past the last feasible strategy repeat that strategy).
+    int64_t raw0[G::EPT], raw1[G::EPT];
+    auto fetch = [&](const Cursor& cur, int64_t (&raw)[G::EPT]) {
+        const int lgw = 6 + cur.s.lgc;
+        const int r = (4 * tid) >> lgw, col = (4 * tid) & ((1 << lgw) - 1);
+        const int a = lidx[cur.e][(cur.j << (12 - lgw)) + r];
+        const uint32_t b4 = *reinterpret_cast<const uint32_t*>(&lidx[cur.e + 1][col]);
+        const int64_t* src = R + ((int64_t)(l0 + cur.e) * KP + a) * KP;
 #pragma unroll
-        for (int e = 0; e < G::EPT / 2; ++e) {
-            const ll2 v = *reinterpret_cast<const ll2*>(src + 2 * (e * kScThreads + tid));
-            raw[2 * e] = v.x;
-            raw[2 * e + 1] = v.y;
-        }
+        for (int i = 0; i < G::EPT; ++i) raw[i] = src[(b4 >> (8 * i)) & 255u];
     };
-    auto stash = [&](int p, const int64_t (&raw)[G::EPT]) {
-        double* dst = lds + (p & 1) * kScPiece;
-        const int o = p / G::NCH, a0 = (p & (G::NCH - 1)) * G::CH;
+    auto stash = [&](const Cursor& cur, const int64_t (&raw)[G::EPT], double* dst) {
+        const int lgw = 6 + cur.s.lgc;
+        const int r = (4 * tid) >> lgw, col = (4 * tid) & ((1 << lgw) - 1);
+        const bool row_ok = (cur.j << (12 - lgw)) + r < cur.s.na;
 #pragma unroll
-        for (int e = 0; e < G::EPT / 2; ++e) {
-            const int at = 2 * (e * kScThreads + tid);
-            if (row_live(o, a0 + at / KP)) {
-                dst[at] = to_f64(raw[2 * e]);
-                dst[at + 1] = to_f64(raw[2 * e + 1]);
-            }
-        }
+        for (int i = 0; i < G::EPT; ++i)
+            dst[4 * tid + i] = (row_ok && col + i < cur.s.nb) ? to_f64(raw[i]) : kInfD;
     };
-    fetch(0, raw0);
-    fetch(1, raw1);
-    stash(0, raw0);
+    Cursor cc = cursor_at(0);                     // the piece being used, the one after it, the one after that
+    Cursor cs = advance(cc);
+    Cursor cf = advance(cs);
+    fetch(cc, raw0);
+    fetch(cs, raw1);
+    stash(cc, raw0, lds);
     lds_barrier();
 
-    // node costs of the operator the current edge arrives at, in this lane's columns
+    // node costs of the operator the current edge arrives at, in this lane's columns (rank lane + 64 k)
+    auto c_at = [&](int o, int k) -> int64_t { return c0[(int64_t)o * KP + lidx[o][lane + 64 * k]]; };
     double cB[G::CPT];
 #pragma unroll
-    for (int k = 0; k < G::CPT; ++k) cB[k] = to_f64(c0[KP + lane + 64 * k]);   // operator l0 + 1 exists: SL >= 1
-
-    // feasible strategies of the operator the current edge leaves from (wave-uniform copies of the table's words)
-    uint64_t amask[G::CPT];
-    auto load_amask = [&](int o) {
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
-            const uint64_t m = opmask[o][k];
-            amask[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(m >> 32)) << 32) |
-                       (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
-        }
-    };
-    load_amask(0);
+    for (int k = 0; k < G::CPT; ++k) cB[k] = to_f64(c_at(1, k));   // operator l0 + 1 exists: SLq >= 1
 
     // entering with strategy a_row costs nothing extra: v = 0 at a_row, infeasible elsewhere
     double V[kScRows][G::CPT], acc[kScRows][G::CPT];
+    const int n0 = count_at(0);
 #pragma unroll
     for (int q = 0; q < kScRows; ++q)
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k) {
-            V[q][k] = (lane + 64 * k == a_row[q]) ? 0.0 : kInfD;
-            if (Vin != nullptr && q < n_rows)
-                V[q][k] = to_f64(Vin[(int64_t)g * in_stride + (int64_t)a_row[q] * KP + lane + 64 * k]);
+            const int b = lidx[0][lane + 64 * k];
+            const bool ranked = lane + 64 * k < n0;
+            V[q][k] = (ranked && b == a_row[q]) ? 0.0 : kInfD;
+            if (Vin != nullptr && q < n_rows) {
+                const double x = to_f64(Vin[(int64_t)g * in_stride + (int64_t)a_row[q] * KP + b]);
+                V[q][k] = ranked ? x : kInfD;
+            }
         }
 
-    // piece p = rows a of piece p % NCH of edge p / NCH
-    auto one_piece = [&](int p, int64_t (&mine)[G::EPT], const int64_t (&next)[G::EPT]) {
-        const int ch = p & (G::NCH - 1);
-        if (ch == 0) {
+    // one piece: parity = which LDS buffer and which registers hold it
+    auto one_piece = [&](int parity, int64_t (&mine)[G::EPT], const int64_t (&next)[G::EPT]) {
+        if (cc.j == 0) {
 #pragma unroll
             for (int q = 0; q < kScRows; ++q)
 #pragma unroll
@@ -269,20 +302,25 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         }
         // node costs for the edge after this one (read again by every piece of an edge: a load that only the last
         // piece issued would be a conditional one)
-        const int e = p / G::NCH;
-        const int o_next = e + 2 <= SLq ? e + 2 : SLq;
+        const int o_next = cc.e + 2 <= SLq ? cc.e + 2 : SLq;
         int64_t cC[G::CPT];
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k)
-            cC[k] = c0[(int64_t)o_next * KP + lane + 64 * k];
-        fetch(p + 2, mine);                               // the registers of piece p are free: it is in LDS
-        const double* piece = lds + (p & 1) * kScPiece;
-        relax_rows<KP, kScRows>(n_rows, piece, lane, ch, amask, V, acc);
-        if (p + 1 < n_pieces) stash(p + 1, next);
-        lds_barrier();                                    // piece p+1 is in LDS; piece p has been read for the last time
+        for (int k = 0; k < G::CPT; ++k) cC[k] = c_at(o_next, k);
+        fetch(cf, mine);                                  // the registers of this piece are free: it is in LDS
+        const double* piece = lds + parity * kScPiece;
+        const int rows_pp = 64 >> cc.s.lgc, rank0 = cc.j * rows_pp;
+        int nr = cc.s.na - rank0;
+        nr = nr < rows_pp ? nr : rows_pp;
+        nr = (nr + 3) & ~3;                               // a piece has a multiple of 4 rows
+        if (n_rows == 1) relax_width<KP, 1>(cc.s.lgc, piece, lane, nr, rank0, V, acc);
+        if constexpr (kScRows == 2) {
+            if (n_rows == 2) relax_width<KP, 2>(cc.s.lgc, piece, lane, nr, rank0, V, acc);
+        }
+        if (!cs.past) stash(cs, next, lds + (parity ^ 1) * kScPiece);
+        lds_barrier();                                    // the next piece is in LDS; this one has been read for the last time
 #pragma unroll
         for (int k = 0; k < G::CPT; ++k) asm volatile("" ::"v"(cC[k]));   // keeps the load in every piece
-        if (ch == G::NCH - 1) {
+        if (cc.j == cc.s.np - 1) {
 #pragma unroll
             for (int k = 0; k < G::CPT; ++k) {
 #pragma unroll
@@ -290,20 +328,35 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
                     V[q][k] = __builtin_fmin(cB[k] + __builtin_fmin(acc[q][k], kInfD), kInfD);
                 cB[k] = to_f64(cC[k]);
             }
-            load_amask(e + 1);                            // the operator just reached is where the next edge leaves from
         }
+        cc = cs;
+        cs = cf;
+        cf = advance(cf);
     };
-    for (int p = 0; p < n_pieces; p += 4) {               // n_pieces is a multiple of 4 (the planner sees to it)
-        one_piece(p, raw0, raw1);
-        one_piece(p + 1, raw1, raw0);
-        one_piece(p + 2, raw0, raw1);
-        one_piece(p + 3, raw1, raw0);
+    static_assert(kScRows <= 2, "one case per number of rows");
+    while (true) {
+        one_piece(0, raw0, raw1);
+        if (cc.past) break;
+        one_piece(1, raw1, raw0);
+        if (cc.past) break;
     }
+
+    // V is in rank order of the part's last operator; the rows of M_g are in strategy order, infeasible where the
+    // operator's strategy is.  Every wave turns its rows round in its own stretch of the (now idle) piece buffers.
+    double* turn = lds + wave * KP;
+    const int n_end = count_at(SLq);
 #pragma unroll
     for (int q = 0; q < kScRows; ++q) {
-        if (q < n_rows) {
 #pragma unroll
-            for (int k = 0; k < G::CPT; ++k) Mg[(int64_t)a_row[q] * KP + lane + 64 * k] = to_i64(V[q][k]);
+        for (int k = 0; k < G::CPT; ++k) turn[lane + 64 * k] = kInfD;
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) {
+            if (lane + 64 * k < n_end) turn[lidx[SLq][lane + 64 * k]] = V[q][k];
+        }
+#pragma unroll
+        for (int k = 0; k < G::CPT; ++k) {
+            const double x = turn[lane + 64 * k];
+            if (q < n_rows) Mg[(int64_t)a_row[q] * KP + lane + 64 * k] = to_i64(x);
         }
     }
 }
