@@ -144,7 +144,7 @@ template <int KP>
 __global__ void __launch_bounds__(kScThreads)
 scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t nseg_pad,
                    const int64_t* __restrict__ c, const int64_t* __restrict__ R, const int64_t* __restrict__ Vin,
-                   int64_t in_stride, int64_t* __restrict__ Vout, int64_t out_stride, int32_t fill_dead) {
+                   int64_t in_stride, int64_t* __restrict__ Vout, int64_t out_stride) {
     using G = Shape<KP>;
     extern __shared__ double lds[];               // two pieces of kScPiece doubles
     __shared__ int32_t live_rows[KP];
@@ -181,23 +181,16 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     if (live) live_rows[before + __popcll(mask & ((1ull << lane) - 1))] = tid;
     __syncthreads();
 
-    // rows of M_g that nobody computes are infeasible: every workgroup fills its share of them
-    for (int a = kScBlock * rb + wave; fill_dead && a < KP && a < kScBlock * (rb + 1); a += kScWaves) {
-        if (cseg[a] >= kInf) {
-#pragma unroll
-            for (int k = 0; k < G::CPT; ++k) Mg[(int64_t)a * KP + lane + 64 * k] = kInf;
-        }
-    }
     if (kScBlock * rb >= n_live) return;          // whole workgroup, after its last __syncthreads
     // slot q of this wave takes the feasible strategy of rank kScBlock rb + q kScWaves + wave: ranks fill slot 0 of
     // every wave before any slot 1
-    int a_row[kScRows];
+    int a_row[kScRows], a_rank[kScRows];
     int n_rows = 0;                               // wave-uniform
 #pragma unroll
     for (int q = 0; q < kScRows; ++q) {
-        const int rank = kScBlock * rb + q * kScWaves + wave;
-        a_row[q] = rank < n_live ? live_rows[rank] : -1;
-        n_rows += rank < n_live ? 1 : 0;
+        a_rank[q] = kScBlock * rb + q * kScWaves + wave;
+        a_row[q] = a_rank[q] < n_live ? live_rows[a_rank[q]] : -1;
+        n_rows += a_rank[q] < n_live ? 1 : 0;
     }
 
     // The feasible strategies of every operator of the part, ranked.  An infeasible strategy makes its row of the
@@ -287,7 +280,7 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
             const bool ranked = lane + 64 * k < n0;
             V[q][k] = (ranked && b == a_row[q]) ? 0.0 : kInfD;
             if (Vin != nullptr && q < n_rows) {
-                const double x = to_f64(Vin[(int64_t)g * in_stride + (int64_t)a_row[q] * KP + b]);
+                const double x = to_f64(Vin[(int64_t)g * in_stride + (int64_t)a_rank[q] * KP + lane + 64 * k]);
                 V[q][k] = ranked ? x : kInfD;
             }
         }
@@ -341,51 +334,78 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         if (cc.past) break;
     }
 
-    // V is in rank order of the part's last operator; the rows of M_g are in strategy order, infeasible where the
-    // operator's strategy is.  Every wave turns its rows round in its own stretch of the (now idle) piece buffers.
-    double* turn = lds + wave * KP;
-    const int n_end = count_at(SLq);
+    // row a_rank of the matrix, columns in rank order of the part's last operator (infeasible past the last rank)
 #pragma unroll
     for (int q = 0; q < kScRows; ++q) {
+        if (q < n_rows) {
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) turn[lane + 64 * k] = kInfD;
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
-            if (lane + 64 * k < n_end) turn[lidx[SLq][lane + 64 * k]] = V[q][k];
-        }
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
-            const double x = turn[lane + 64 * k];
-            if (q < n_rows) Mg[(int64_t)a_row[q] * KP + lane + 64 * k] = to_i64(x);
+            for (int k = 0; k < G::CPT; ++k) Mg[(int64_t)a_rank[q] * KP + lane + 64 * k] = to_i64(V[q][k]);
         }
     }
 }
 
 // ---- step 2: boundary vectors ---------------------------------------------------------------------
-// vs[b] <- min_a (vs[a] + Mg[a][b]), saturated; the whole workgroup (kBdThreads) takes part.  Rows whose vs[a] is
-// infeasible are not read (rows of entering strategies nobody computed hold nothing).
+// The matrices are in rank order (row = rank of the entering strategy among the feasible ones of the segment's
+// first operator, column = rank at the operator the matrix reaches), and so are the vectors these kernels
+// multiply; the node-cost rows they hand to the final sweep are in strategy order again.
+
+// Ranks the feasible strategies of one operator (node costs c_op[0..KP), already in x for thread tid < KP):
+// returns how many there are; live/rank describe strategy tid.  The whole workgroup calls it.
 template <int KP>
-__device__ __forceinline__ void vector_times_matrix(int64_t (&vs)[KP], int64_t (&part)[kBdWaves][KP],
-                                                    const int64_t* __restrict__ Mg, int tid, int wave, int lane) {
+__device__ __forceinline__ int rank_feasible(int64_t x, int tid, int wave, int lane, int32_t (&wave_cnt)[KP / 64],
+                                             bool& live, int& rank) {
+    live = tid < KP && x < kInf;
+    const uint64_t mask = __ballot(live);
+    __syncthreads();                              // the counts of the call before have been read
+    if (tid < KP && lane == 0) wave_cnt[wave] = __popcll(mask);
+    __syncthreads();
+    int n = 0, before = 0;
+#pragma unroll
+    for (int w = 0; w < KP / 64; ++w) {
+        const int cnt = wave_cnt[w];
+        before += w < wave ? cnt : 0;
+        n += cnt;
+    }
+    rank = before + __popcll(mask & ((1ull << lane) - 1));
+    return n;
+}
+
+// vout[b] <- min_a (vs[a] + Mg[a][b]) for a < n_a, b < n_b, saturated; the whole workgroup (kBdThreads) takes part.
+// A wave takes the rows a = wave, wave + 16, ..., eight at a time with all their loads in flight together.
+template <int KP>
+__device__ __forceinline__ void vector_times_matrix(const int64_t* __restrict__ vs, int n_a, int n_b,
+                                                    int64_t (&part)[kBdWaves][KP], const int64_t* __restrict__ Mg,
+                                                    int64_t* __restrict__ vout, int tid, int wave, int lane) {
     constexpr int LPG = KP / 128 > 0 ? KP / 128 : 1;      // 16-byte loads per lane per row
-    constexpr int ROW_LANES = KP / 2 < 64 ? KP / 2 : 64;  // lanes that hold a row (KP = 64: half a wave)
+    constexpr int U = 8;
     int64_t best[2 * LPG];
 #pragma unroll
     for (int j = 0; j < 2 * LPG; ++j) best[j] = kInf;
-    for (int a = wave; a < KP; a += kBdWaves) {
-        const int64_t va = vs[a];
-        if (va >= kInf) continue;                 // wave-uniform
-        if (lane < ROW_LANES) {
+    for (int r0 = wave; r0 < n_a; r0 += kBdWaves * U) {
+        ll2 m[U][LPG];
+        int64_t va[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = r0 + kBdWaves * u;
+            const int rr = row < n_a ? row : n_a - 1;     // a row past the end repeats the last one and cannot win
+            va[u] = row < n_a ? vs[rr] : kInf;
 #pragma unroll
             for (int k = 0; k < LPG; ++k) {
-                const ll2 m = *reinterpret_cast<const ll2*>(Mg + (int64_t)a * KP + 2 * lane + 128 * k);
-                const int64_t x0 = va + m.x, x1 = va + m.y;
+                const int col = (2 * lane + 128 * k) & (KP - 1);
+                m[u][k] = ll2{0, 0};
+                if (col < n_b) m[u][k] = *reinterpret_cast<const ll2*>(Mg + (int64_t)rr * KP + col);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < LPG; ++k) {
+                const int64_t x0 = va[u] + m[u][k].x, x1 = va[u] + m[u][k].y;
                 best[2 * k] = x0 < best[2 * k] ? x0 : best[2 * k];
                 best[2 * k + 1] = x1 < best[2 * k + 1] ? x1 : best[2 * k + 1];
             }
-        }
     }
-    if (lane < ROW_LANES) {
+    if (2 * lane < KP) {
 #pragma unroll
         for (int k = 0; k < LPG; ++k) {
             part[wave][2 * lane + 128 * k] = best[2 * k];
@@ -394,10 +414,10 @@ __device__ __forceinline__ void vector_times_matrix(int64_t (&vs)[KP], int64_t (
     }
     __syncthreads();
     if (tid < KP) {
-        int64_t m = part[0][tid];
+        int64_t x = part[0][tid];
 #pragma unroll
-        for (int w = 1; w < kBdWaves; ++w) m = part[w][tid] < m ? part[w][tid] : m;
-        vs[tid] = m < kInf ? m : kInf;
+        for (int w = 1; w < kBdWaves; ++w) x = part[w][tid] < x ? part[w][tid] : x;
+        vout[tid] = (tid < n_b && x < kInf) ? x : kInf;
     }
     __syncthreads();
 }
@@ -407,42 +427,61 @@ __device__ __forceinline__ void vector_times_matrix(int64_t (&vs)[KP], int64_t (
 // kScSub * g.
 template <int KP>
 __global__ void __launch_bounds__(kBdThreads)
-scan_boundary_kernel(int32_t SLq, int32_t nseg, const int64_t* __restrict__ c, const int64_t* __restrict__ M,
-                     int64_t* __restrict__ c_seg) {
-    __shared__ int64_t vs[KP];
+scan_boundary_kernel(int32_t SL, int32_t SLq, int32_t nseg, const int64_t* __restrict__ c,
+                     const int64_t* __restrict__ M, int64_t* __restrict__ c_seg) {
+    __shared__ int64_t vs[2][KP];
     __shared__ int64_t part[kBdWaves][KP];
+    __shared__ int32_t wave_cnt[KP / 64];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int64_t seg_stride = (int64_t)kScSub * (SLq + 1) * KP;
-    if (tid < KP) {
-        int64_t x = c[tid];
-        x = x < kInf ? x : kInf;
-        vs[tid] = x;
-        c_seg[tid] = x;
-    }
+    bool live;
+    int rank;
+    int64_t x = tid < KP ? c[tid] : kInf;
+    int n_a = rank_feasible<KP>(x, tid, wave, lane, wave_cnt, live, rank);
+    if (tid < KP) c_seg[tid] = x < kInf ? x : kInf;
+    if (live) vs[0][rank] = x;
+    // node costs of the operator the next matrix reaches: asked for one product ahead
+    int64_t c_reach = (tid < KP && nseg > 0) ? c[(int64_t)SL * KP + tid] : kInf;
     __syncthreads();
     for (int g = 0; g < nseg; ++g) {
-        vector_times_matrix<KP>(vs, part, M + (int64_t)g * KP * KP, tid, wave, lane);
-        if (tid < KP) c_seg[(int64_t)(g + 1) * seg_stride + tid] = vs[tid];
+        const int64_t c_now = c_reach;
+        const int g_ahead = g + 2 <= nseg ? g + 2 : nseg;     // operator g_ahead * SL exists: the last segment follows
+        c_reach = tid < KP ? c[(int64_t)g_ahead * SL * KP + tid] : kInf;
+        const int n_b = rank_feasible<KP>(c_now, tid, wave, lane, wave_cnt, live, rank);
+        int64_t* vnew = vs[(g + 1) & 1];
+        vector_times_matrix<KP>(vs[g & 1], n_a, n_b, part, M + (int64_t)g * KP * KP, vnew, tid, wave, lane);
+        if (tid < KP) c_seg[(int64_t)(g + 1) * seg_stride + tid] = live ? vnew[rank] : kInf;
+        n_a = n_b;
     }
 }
 
 // Workgroup (j, g): start vector of part j + 1 of segment g = v_g (x) Msub[g][j], row 0 of problem kScSub * g + j + 1.
 template <int KP>
 __global__ void __launch_bounds__(kBdThreads)
-scan_part_vectors_kernel(int32_t SLq, const int64_t* __restrict__ Msub, int64_t* __restrict__ c_seg) {
-    __shared__ int64_t vs[KP];
+scan_part_vectors_kernel(int32_t SL, int32_t SLq, const int64_t* __restrict__ c, const int64_t* __restrict__ Msub,
+                         int64_t* __restrict__ c_seg) {
+    __shared__ int64_t vs[2][KP];
     __shared__ int64_t part[kBdWaves][KP];
+    __shared__ int32_t wave_cnt[KP / 64];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int j = blockIdx.x, g = blockIdx.y;
     const int64_t prob_stride = (int64_t)(SLq + 1) * KP;
-    if (tid < KP) vs[tid] = c_seg[(int64_t)kScSub * g * prob_stride + tid];
-    __syncthreads();
-    vector_times_matrix<KP>(vs, part, Msub + ((int64_t)g * (kScSub - 1) + j) * KP * KP, tid, wave, lane);
-    if (tid < KP) c_seg[((int64_t)kScSub * g + j + 1) * prob_stride + tid] = vs[tid];
+    const int op_a = g * SL, op_b = op_a + (j + 1) * SLq;   // where the matrix starts and what it reaches
+    bool live;
+    int rank;
+    const int64_t ca = tid < KP ? c[(int64_t)op_a * KP + tid] : kInf;
+    const int64_t cb = tid < KP ? c[(int64_t)op_b * KP + tid] : kInf;
+    const int64_t v = tid < KP ? c_seg[(int64_t)kScSub * g * prob_stride + tid] : kInf;
+    const int n_a = rank_feasible<KP>(ca, tid, wave, lane, wave_cnt, live, rank);
+    if (live) vs[0][rank] = v;
+    const int n_b = rank_feasible<KP>(cb, tid, wave, lane, wave_cnt, live, rank);   // its barriers publish vs[0]
+    vector_times_matrix<KP>(vs[0], n_a, n_b, part, Msub + ((int64_t)g * (kScSub - 1) + j) * KP * KP, vs[1], tid,
+                            wave, lane);
+    if (tid < KP) c_seg[((int64_t)kScSub * g + j + 1) * prob_stride + tid] = live ? vs[1][rank] : kInf;
 }
 
 // rows 1.. of every segment's node costs: c_seg[g][r][:] = c[g * SL + r][:], r >= 1, while g * SL + r < N
@@ -552,12 +591,12 @@ hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
             const bool fin = j + 1 == kScSub;                                                                       \
             hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,  \
                                nseg_pad, cp, Rp, j ? Msub + (j - 1) * mat : nullptr, sub, fin ? M : Msub + j * mat, \
-                               fin ? mat : sub, fin ? 1 : 0);                                                       \
+                               fin ? mat : sub);                                                       \
         }                                                                                                           \
-        hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3(1), dim3(kBdThreads), 0, stream, SLq, nseg, cp, M,      \
-                           c_seg);                                                                                  \
+        hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3(1), dim3(kBdThreads), 0, stream, pl.SL, SLq, nseg, cp,  \
+                           M, c_seg);                                                                               \
         hipLaunchKernelGGL((scan_part_vectors_kernel<KP>), dim3(kScSub - 1, nseg), dim3(kBdThreads), 0, stream,     \
-                           SLq, Msub, c_seg);                                                                       \
+                           pl.SL, SLq, cp, Msub, c_seg);                                                            \
     } while (0)
         switch (Kp) {
             case 64: RH_SCAN(64); break;
