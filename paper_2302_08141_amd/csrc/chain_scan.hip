@@ -153,6 +153,7 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     // lookup is always a valid strategy); nl[o] = how many there are
     __shared__ __align__(4) uint8_t lidx[kMaxPartLen + 1][KP];
     __shared__ int32_t nl[kMaxPartLen + 1];
+    __shared__ double c_arrive[2][KP];            // node costs (rank order) of the operator each staged piece's edge arrives at
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -233,41 +234,47 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         cur.past = true;
         return cur;
     };
-    // A thread stages the four neighbouring columns 4 tid .. 4 tid + 3 (in rank order) of one row of the piece.
+    // A wave stages 64 neighbouring columns (in rank order) of one row at a time: thread tid takes the elements
+    // tid, tid + 1024, ... of the piece, and one node cost of the operator the piece's edge arrives at (that row
+    // travels with every piece of the edge, so that all pieces issue the same loads).
     // Every load of the main loop is unconditional and every piece issues the same number of them, so that the
     // waits can count outstanding loads instead of draining them all (a fetch past the end repeats the last piece,
     // ranks past the last feasible strategy repeat that strategy).
-    int64_t raw0[G::EPT], raw1[G::EPT];
-    auto fetch = [&](const Cursor& cur, int64_t (&raw)[G::EPT]) {
-        const int lgw = 6 + cur.s.lgc;
-        const int r = (4 * tid) >> lgw, col = (4 * tid) & ((1 << lgw) - 1);
-        const int a = lidx[cur.e][(cur.j << (12 - lgw)) + r];
-        const uint32_t b4 = *reinterpret_cast<const uint32_t*>(&lidx[cur.e + 1][col]);
-        const int64_t* src = R + ((int64_t)(l0 + cur.e) * KP + a) * KP;
-#pragma unroll
-        for (int i = 0; i < G::EPT; ++i) raw[i] = src[(b4 >> (8 * i)) & 255u];
+    struct Raw {
+        int64_t r[G::EPT], c;
     };
-    auto stash = [&](const Cursor& cur, const int64_t (&raw)[G::EPT], double* dst) {
+    Raw raw0, raw1;
+    auto fetch = [&](const Cursor& cur, Raw& raw) {
         const int lgw = 6 + cur.s.lgc;
-        const int r = (4 * tid) >> lgw, col = (4 * tid) & ((1 << lgw) - 1);
-        const bool row_ok = (cur.j << (12 - lgw)) + r < cur.s.na;
+        const int row = tid >> lgw, col = tid & ((1 << lgw) - 1);
+        const int b = lidx[cur.e + 1][col];
+        const int64_t* src = R + (int64_t)(l0 + cur.e) * KP * KP + b;
 #pragma unroll
-        for (int i = 0; i < G::EPT; ++i)
-            dst[4 * tid + i] = (row_ok && col + i < cur.s.nb) ? to_f64(raw[i]) : kInfD;
+        for (int i = 0; i < G::EPT; ++i) {
+            const int a = lidx[cur.e][(cur.j << (12 - lgw)) + (i << (10 - lgw)) + row];
+            raw.r[i] = src[a * KP];
+        }
+        raw.c = c0[(int64_t)(cur.e + 1) * KP + lidx[cur.e + 1][tid & (KP - 1)]];
+    };
+    auto stash = [&](const Cursor& cur, const Raw& raw, int parity) {
+        double* dst = lds + parity * kScPiece;
+        const int lgw = 6 + cur.s.lgc;
+        const int row = tid >> lgw, col = tid & ((1 << lgw) - 1);
+        const bool col_ok = col < cur.s.nb;
+#pragma unroll
+        for (int i = 0; i < G::EPT; ++i) {
+            const bool row_ok = (cur.j << (12 - lgw)) + (i << (10 - lgw)) + row < cur.s.na;
+            dst[i * kScThreads + tid] = (row_ok && col_ok) ? to_f64(raw.r[i]) : kInfD;
+        }
+        if (tid < KP) c_arrive[parity][tid] = to_f64(raw.c);
     };
     Cursor cc = cursor_at(0);                     // the piece being used, the one after it, the one after that
     Cursor cs = advance(cc);
     Cursor cf = advance(cs);
     fetch(cc, raw0);
     fetch(cs, raw1);
-    stash(cc, raw0, lds);
+    stash(cc, raw0, 0);
     lds_barrier();
-
-    // node costs of the operator the current edge arrives at, in this lane's columns (rank lane + 64 k)
-    auto c_at = [&](int o, int k) -> int64_t { return c0[(int64_t)o * KP + lidx[o][lane + 64 * k]]; };
-    double cB[G::CPT];
-#pragma unroll
-    for (int k = 0; k < G::CPT; ++k) cB[k] = to_f64(c_at(1, k));   // operator l0 + 1 exists: SLq >= 1
 
     // entering with strategy a_row costs nothing extra: v = 0 at a_row, infeasible elsewhere
     double V[kScRows][G::CPT], acc[kScRows][G::CPT];
@@ -286,19 +293,13 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         }
 
     // one piece: parity = which LDS buffer and which registers hold it
-    auto one_piece = [&](int parity, int64_t (&mine)[G::EPT], const int64_t (&next)[G::EPT]) {
+    auto one_piece = [&](int parity, Raw& mine, const Raw& next) {
         if (cc.j == 0) {
 #pragma unroll
             for (int q = 0; q < kScRows; ++q)
 #pragma unroll
                 for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
         }
-        // node costs for the edge after this one (read again by every piece of an edge: a load that only the last
-        // piece issued would be a conditional one)
-        const int o_next = cc.e + 2 <= SLq ? cc.e + 2 : SLq;
-        int64_t cC[G::CPT];
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) cC[k] = c_at(o_next, k);
         fetch(cf, mine);                                  // the registers of this piece are free: it is in LDS
         const double* piece = lds + parity * kScPiece;
         const int rows_pp = 64 >> cc.s.lgc, rank0 = cc.j * rows_pp;
@@ -309,19 +310,17 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         if constexpr (kScRows == 2) {
             if (n_rows == 2) relax_width<KP, 2>(cc.s.lgc, piece, lane, nr, rank0, V, acc);
         }
-        if (!cs.past) stash(cs, next, lds + (parity ^ 1) * kScPiece);
-        lds_barrier();                                    // the next piece is in LDS; this one has been read for the last time
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) asm volatile("" ::"v"(cC[k]));   // keeps the load in every piece
-        if (cc.j == cc.s.np - 1) {
+        if (cc.j == cc.s.np - 1) {                        // the edge is done: on to the operator it arrives at
 #pragma unroll
             for (int k = 0; k < G::CPT; ++k) {
+                const double cb = c_arrive[parity][lane + 64 * k];
 #pragma unroll
                 for (int q = 0; q < kScRows; ++q)
-                    V[q][k] = __builtin_fmin(cB[k] + __builtin_fmin(acc[q][k], kInfD), kInfD);
-                cB[k] = to_f64(cC[k]);
+                    V[q][k] = __builtin_fmin(cb + __builtin_fmin(acc[q][k], kInfD), kInfD);
             }
         }
+        if (!cs.past) stash(cs, next, parity ^ 1);
+        lds_barrier();                                    // the next piece is in LDS; this one has been read for the last time
         cc = cs;
         cs = cf;
         cf = advance(cf);
