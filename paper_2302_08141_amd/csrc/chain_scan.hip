@@ -83,7 +83,7 @@ __device__ __forceinline__ EdgeShape edge_shape(int na, int nb) {
 }
 
 // acc[q][k] = min(acc[q][k], V[q][rank0 + r] + piece[r][lane + 64 k]) over the rows r < nr of one piece (nr a
-// multiple of 4: the piece's rows past the last feasible strategy hold "infeasible", and so does V there), NR
+// multiple of 8: the piece's rows past the last feasible strategy hold "infeasible", and so does V there), NR
 // rows of M_g at once, CC groups of 64 columns.
 template <int KP, int NR, int CC>
 __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int lane, int nr, int rank0,
@@ -104,21 +104,45 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
             asm volatile("" : "+v"(src[q]));
         }
     }
-    constexpr int UR = CC == 4 ? 2 : 4;           // rows per trip: eight LDS values in flight
-    for (int r = 0; r < nr; r += UR) {
-        double rv[UR][CC];
+    // The rows of the piece go with lanes lane0, lane0 + 1, ... of src; turned round so that they go with lanes
+    // 0, 1, ..., every broadcast below names its lane by a constant (a lane number computed at run time makes
+    // the broadcast markedly slower).
+    const int from = ((lane + lane0) & 63) << 2;
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+        const int lo = __builtin_amdgcn_ds_bpermute(from, __double2loint(src[q]));
+        const int hi = __builtin_amdgcn_ds_bpermute(from, __double2hiint(src[q]));
+        src[q] = __hiloint2double(hi, lo);
+    }
+    // Four LDS values per lane and trip; the next trip's values are asked for before this trip's arithmetic.
+    constexpr int UR = 4 / CC;                    // rows per trip
+    constexpr int ROWS = kScPiece / W;            // rows a piece has room for
+    double ra[UR][CC], rb[UR][CC];
+    auto load = [&](double (&rv)[UR][CC], int r) {
+        r = r < ROWS - UR ? r : ROWS - UR;
 #pragma unroll
         for (int u = 0; u < UR; ++u)
 #pragma unroll
             for (int k = 0; k < CC; ++k) rv[u][k] = piece[(r + u) * W + lane + 64 * k];
+    };
+    auto relax = [&](const double (&rv)[UR][CC], int r) {
 #pragma unroll
         for (int u = 0; u < UR; ++u)
 #pragma unroll
             for (int q = 0; q < NR; ++q) {
-                const double sv = bcast(src[q], lane0 + r + u);
+                const double sv = bcast(src[q], r + u);
 #pragma unroll
                 for (int k = 0; k < CC; ++k) acc[q][k] = __builtin_fmin(acc[q][k], rv[u][k] + sv);
             }
+    };
+    load(ra, 0);
+#pragma unroll
+    for (int r = 0; r < ROWS; r += 2 * UR) {
+        if ((r & 7) == 0 && r >= nr) break;       // nr is a multiple of 8
+        load(rb, r + UR);
+        relax(ra, r);
+        load(ra, r + 2 * UR);
+        relax(rb, r + UR);
     }
 }
 
@@ -305,7 +329,7 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         const int rows_pp = 64 >> cc.s.lgc, rank0 = cc.j * rows_pp;
         int nr = cc.s.na - rank0;
         nr = nr < rows_pp ? nr : rows_pp;
-        nr = (nr + 3) & ~3;                               // a piece has a multiple of 4 rows
+        nr = (nr + 7) & ~7;                               // a piece has a multiple of 8 rows
         if (n_rows == 1) relax_width<KP, 1>(cc.s.lgc, piece, lane, nr, rank0, V, acc);
         if constexpr (kScRows == 2) {
             if (n_rows == 2) relax_width<KP, 2>(cc.s.lgc, piece, lane, nr, rank0, V, acc);
