@@ -101,6 +101,20 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
             asm volatile("" : "+v"(src[q]));
         }
     }
+    // The rows of the piece go with lanes lane0, lane0 + 1, ... of src.  With several pieces per edge lane0 is
+    // only known at run time, and a broadcast from a lane numbered at run time is markedly slower than one
+    // from a constant lane: turn src round so that the rows go with lanes 0, 1, ...
+    int first = lane0;
+    if constexpr (G::NCH > 1) {
+        const int from = ((col + lane0) & 63) << 2;
+#pragma unroll
+        for (int q = 0; q < NA; ++q) {
+            const int lo = __builtin_amdgcn_ds_bpermute(from, __double2loint(src[q]));
+            const int hi = __builtin_amdgcn_ds_bpermute(from, __double2hiint(src[q]));
+            src[q] = __hiloint2double(hi, lo);
+        }
+        first = 0;
+    }
     // eight rows a at a time: their R values are fetched while the eight before them are worked on
     constexpr int AB = G::CPT >= 4 ? 4 : 8;
     static_assert(G::CH % AB == 0, "piece height");
@@ -122,7 +136,7 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
         for (int u = 0; u < AB; ++u) {
             double sv[NA], t[NA][G::CPT];
 #pragma unroll
-            for (int q = 0; q < NA; ++q) sv[q] = bcast(src[q], lane0 + blk * AB + u);
+            for (int q = 0; q < NA; ++q) sv[q] = bcast(src[q], first + blk * AB + u);
 #pragma unroll
             for (int q = 0; q < NA; ++q)
 #pragma unroll
