@@ -160,6 +160,30 @@ __device__ __forceinline__ void relax_width(int lgc, const double* __restrict__ 
     }
 }
 
+// lidx[o][rank] = the rank-th feasible strategy (finite node cost) of operator o, o < n_ops, ascending; ranks past
+// the last one repeat it (strategy 0 if there is none), so that a lookup always names a strategy; nl[o] = how many
+// there are.  c0 = node costs of operator 0.  The waves of the workgroup share the operators out.
+template <int KP>
+__device__ __forceinline__ void rank_operators(const int64_t* __restrict__ c0, int n_ops, uint8_t (*lidx)[KP],
+                                               int32_t* nl, int wave, int lane) {
+    for (int o = wave; o < n_ops; o += kScWaves) {
+        int base = 0, last_live = 0;
+#pragma unroll
+        for (int k = 0; k < KP / 64; ++k) {
+            const bool ok = c0[(int64_t)o * KP + lane + 64 * k] < kInf;
+            const uint64_t m = __ballot(ok);
+            if (ok) lidx[o][base + __popcll(m & ((1ull << lane) - 1))] = (uint8_t)(lane + 64 * k);
+            if (m != 0) last_live = 64 * k + 63 - __builtin_clzll(m);
+            base += __popcll(m);
+        }
+#pragma unroll
+        for (int k = 0; k < KP / 64; ++k) {
+            if (lane + 64 * k >= base) lidx[o][lane + 64 * k] = (uint8_t)last_live;
+        }
+        if (lane == 0) nl[o] = base;
+    }
+}
+
 // ---- step 1: segment matrices -------------------------------------------------------------------
 // Workgroup (rb, g): up to kScBlock feasible entering strategies of segment g, kScRows per wave.  blockIdx.x = rb *
 // nseg_pad + g with nseg_pad a multiple of 8, so the workgroups of one segment, which read the same tables at
@@ -221,22 +245,7 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     // The feasible strategies of every operator of the part, ranked.  An infeasible strategy makes its row of the
     // edge table that leaves from its operator and its column of the table that arrives there irrelevant (the
     // vector is infeasible there whatever the table says): such rows and columns are neither fetched nor used.
-    for (int o = wave; o <= SLq; o += kScWaves) {
-        int base = 0, last_live = 0;
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
-            const bool ok = c0[(int64_t)o * KP + lane + 64 * k] < kInf;
-            const uint64_t m = __ballot(ok);
-            if (ok) lidx[o][base + __popcll(m & ((1ull << lane) - 1))] = (uint8_t)(lane + 64 * k);
-            if (m != 0) last_live = 64 * k + 63 - __builtin_clzll(m);
-            base += __popcll(m);
-        }
-#pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
-            if (lane + 64 * k >= base) lidx[o][lane + 64 * k] = (uint8_t)last_live;
-        }
-        if (lane == 0) nl[o] = base;
-    }
+    rank_operators<KP>(c0, SLq + 1, lidx, nl, wave, lane);
     lds_barrier();
     auto count_at = [&](int o) -> int { return __builtin_amdgcn_readfirstlane(nl[o]); };
 
@@ -507,6 +516,131 @@ scan_part_vectors_kernel(int32_t SL, int32_t SLq, const int64_t* __restrict__ c,
     if (tid < KP) c_seg[((int64_t)kScSub * g + j + 1) * prob_stride + tid] = live ? vs[1][rank] : kInf;
 }
 
+// ---- step 3: the sweep inside every part --------------------------------------------------------
+// One workgroup per part: the plain forward sweep from the part's start vector (row 0 of its problem in c_seg)
+// over its SLq edges, writing arg.  Rows of an edge table whose strategy has an infeasible node cost cannot
+// hold a minimum (their vector entry is infeasible) and are not read; the others are dealt to the 16 waves in
+// rank order, D rows per wave in flight (D * trips covers the fullest edge): a slot is refilled with the same wave's row of the next edge as soon as
+// it has been used, so the loads run ahead of the dependent chain of edges.
+template <int KP, int D>
+__device__ __forceinline__ void sweep_part(int SLq, int trips, const int64_t* __restrict__ c0,
+                                           const int64_t* __restrict__ R0, uint16_t* __restrict__ arg0,
+                                           int64_t* vs, const uint8_t (*lidx)[KP], const int32_t* nl,
+                                           int64_t (*part_v)[KP], uint16_t (*part_a)[KP], int tid, int wave,
+                                           int lane) {
+    constexpr int LPG = KP / 128;                 // 16-byte loads per lane per row
+    ll2 buf[D][LPG];                              // a wave takes D * trips rows of every edge
+    auto row_of = [&](int e, int t, bool& ok) -> int {
+        const int n = __builtin_amdgcn_readfirstlane(nl[e]);
+        const int rank = wave + kScWaves * t;
+        ok = rank < n;
+        return lidx[e][ok ? rank : (n > 0 ? n - 1 : 0)];
+    };
+    auto fetch = [&](int e, int t, ll2 (&dst)[LPG]) {
+        bool ok;
+        const int a = __builtin_amdgcn_readfirstlane(row_of(e, t, ok));
+        const int64_t* src = R0 + ((int64_t)e * KP + a) * KP + 2 * lane;
+#pragma unroll
+        for (int k = 0; k < LPG; ++k) dst[k] = __builtin_nontemporal_load(reinterpret_cast<const ll2*>(src + 128 * k));
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) fetch(0, d, buf[d]);
+    int64_t c_next = tid < KP ? c0[KP + tid] : kInf;         // node costs of the operator edge 0 arrives at
+    for (int e = 0; e < SLq; ++e) {
+        const int64_t c_here = c_next;
+        const int o_ahead = e + 2 <= SLq ? e + 2 : SLq;
+        c_next = tid < KP ? c0[(int64_t)o_ahead * KP + tid] : kInf;
+        int64_t best[2 * LPG];
+        int32_t bidx[2 * LPG];
+#pragma unroll
+        for (int j = 0; j < 2 * LPG; ++j) {
+            best[j] = INT64_MAX;
+            bidx[j] = 0;
+        }
+        const int e_ahead = e + 1 < SLq ? e + 1 : SLq - 1;   // past the end the last edge is read again
+#pragma unroll 1
+        for (int tb = 0; tb < trips; ++tb) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int t = tb * D + d;
+                bool ok;
+                const int a = __builtin_amdgcn_readfirstlane(row_of(e, t, ok));
+                const int64_t va = ok ? vs[a] : kInf;        // a row past the last rank cannot win
+#pragma unroll
+                for (int k = 0; k < LPG; ++k) {
+                    const int64_t x0 = va + buf[d][k].x, x1 = va + buf[d][k].y;
+                    const bool l0 = x0 < best[2 * k], l1 = x1 < best[2 * k + 1];   // a ascends within a wave
+                    best[2 * k] = l0 ? x0 : best[2 * k];
+                    bidx[2 * k] = l0 ? a : bidx[2 * k];
+                    best[2 * k + 1] = l1 ? x1 : best[2 * k + 1];
+                    bidx[2 * k + 1] = l1 ? a : bidx[2 * k + 1];
+                }
+                // the same slot of the next trip, or of the next edge's first trip
+                const bool wraps = tb + 1 == trips;
+                fetch(wraps ? e_ahead : e, wraps ? d : t + D, buf[d]);
+                __builtin_amdgcn_sched_barrier(0);   // use slot d, then refill slot d
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < LPG; ++k) {
+            *reinterpret_cast<ll2*>(&part_v[wave][2 * lane + 128 * k]) = ll2{best[2 * k], best[2 * k + 1]};
+            part_a[wave][2 * lane + 128 * k] = (uint16_t)bidx[2 * k];
+            part_a[wave][2 * lane + 128 * k + 1] = (uint16_t)bidx[2 * k + 1];
+        }
+        __syncthreads();
+        if (tid < KP) {
+            // the waves hold interleaved ranks: among equal values the lowest strategy wins
+            int64_t m = part_v[0][tid];
+            int32_t ma = part_a[0][tid];
+#pragma unroll 4
+            for (int w = 1; w < kScWaves; ++w) {   // (a few at a time: the rows in flight hold most registers)
+                const int64_t x = part_v[w][tid];
+                const int32_t xa = part_a[w][tid];
+                const bool less = x < m || (x == m && xa < ma);
+                m = less ? x : m;
+                ma = less ? xa : ma;
+            }
+            const bool dead = m >= kInf;          // no feasible way into this strategy: (infeasible, 0)
+            arg0[(int64_t)e * KP + tid] = (uint16_t)(dead ? 0 : ma);
+            const int64_t v = m + c_here;
+            vs[tid] = (dead || v >= kInf) ? kInf : v;
+        }
+        __syncthreads();
+    }
+}
+
+template <int KP>
+__global__ void __launch_bounds__(kScThreads)
+scan_sweep_kernel(int32_t SLq, const int64_t* __restrict__ c, const int64_t* __restrict__ R,
+                  const int64_t* __restrict__ c_seg, uint16_t* __restrict__ arg) {
+    __shared__ __align__(16) int64_t part_v[kScWaves][KP];
+    __shared__ uint16_t part_a[kScWaves][KP];
+    __shared__ int64_t vs[KP];
+    __shared__ __align__(4) uint8_t lidx[kMaxPartLen + 1][KP];
+    __shared__ int32_t nl[kMaxPartLen + 1];
+    __shared__ int32_t n_max;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int q = blockIdx.x;                     // part q starts at operator q * SLq
+    const int64_t* c0 = c + (int64_t)q * SLq * KP;
+    if (tid == 0) n_max = 0;
+    if (tid < KP) vs[tid] = c_seg[(int64_t)q * (SLq + 1) * KP + tid];
+    __syncthreads();
+    rank_operators<KP>(c0, SLq, lidx, nl, wave, lane);        // the operators edges leave from
+    lds_barrier();
+    if (tid < SLq) atomicMax(&n_max, nl[tid]);
+    __syncthreads();
+    const int t_max = (n_max + kScWaves - 1) / kScWaves;      // rows per wave of the fullest edge
+    const int64_t* R0 = R + (int64_t)q * SLq * KP * KP;
+    uint16_t* arg0 = arg + (int64_t)q * SLq * KP;
+    // (four rows in flight per wave are 128 KiB per compute unit at Kp = 256: enough to keep the memory busy)
+    if (t_max <= 2)
+        sweep_part<KP, 2>(SLq, 1, c0, R0, arg0, vs, lidx, nl, part_v, part_a, tid, wave, lane);
+    else
+        sweep_part<KP, 4>(SLq, (t_max + 3) / 4, c0, R0, arg0, vs, lidx, nl, part_v, part_a, tid, wave, lane);
+}
+
 // rows 1.. of every segment's node costs: c_seg[g][r][:] = c[g * SL + r][:], r >= 1, while g * SL + r < N
 __global__ void __launch_bounds__(256)
 scan_copy_c_kernel(int32_t N, int32_t SL, int32_t Kp, int32_t n_seg_total, const int64_t* __restrict__ c,
@@ -600,8 +734,10 @@ hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
         const dim3 grid((unsigned)(((Kp + kScBlock - 1) / kScBlock) * nseg_pad));
         // rows 1.. of the node costs of every part and of the last segment
         const int64_t n_copy = (int64_t)n_part * SLq * Kp, n_copy_last = (int64_t)pl.r * Kp;
-        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N, SLq, Kp,
-                           n_part, cp, c_seg);
+        const bool own_sweep = Kp >= 128;         // step 3 by scan_sweep_kernel, which reads the node costs in place
+        if (!own_sweep)
+            hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N, SLq,
+                               Kp, n_part, cp, c_seg);
         hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy_last + 255) / 256)), dim3(256), 0, stream,
                            N - l_last, pl.r, Kp, 1, cp + (int64_t)l_last * Kp, c_last);
 #define RH_SCAN(KP)                                                                                                 \
@@ -632,7 +768,16 @@ hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
         if (e != hipSuccess) return e;
         // step 3: the sweep inside every part as one batch (their totals are scratch), then the last segment,
         // whose final vector, total and last are the chain's.
-        e = launch_chain(n_part, SLq + 1, Kp, c_seg, prob_c, Rp, prob_R, argp, nullptr, seg_total, seg_last, stream);
+        if (Kp == 256)
+            hipLaunchKernelGGL((scan_sweep_kernel<256>), dim3((unsigned)n_part), dim3(kScThreads), 0, stream, SLq, cp, Rp,
+                               c_seg, argp);
+        else if (Kp == 128)
+            hipLaunchKernelGGL((scan_sweep_kernel<128>), dim3((unsigned)n_part), dim3(kScThreads), 0, stream, SLq, cp, Rp,
+                               c_seg, argp);
+        else
+            e = launch_chain(n_part, SLq + 1, Kp, c_seg, prob_c, Rp, prob_R, argp, nullptr, seg_total, seg_last, stream);
+        if (e != hipSuccess) return e;
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
         e = launch_chain(1, pl.r + 1, Kp, c_last, 0, Rp + (int64_t)n_part * prob_R, 0,
                          argp + (int64_t)l_last * Kp, vfinal ? vfinal + (int64_t)p * Kp : nullptr, total + p, last + p,
