@@ -214,6 +214,34 @@ def test_segmented_chain_with_awkward_feasibility(Kp, N):
     assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
 
 
+@pytest.mark.parametrize("Kp,N,live", [(128, 400, 20), (256, 500, 150), (256, 300, 33), (128, 700, 100)])
+def test_segmented_chain_by_number_of_feasible_strategies(Kp, N, live):
+    # the kernels of the segmented path size their loops by the number of feasible strategies (rows in flight per
+    # wave, width of the staged tables): few, just past a power of two, and most of them
+    rng = np.random.default_rng(Kp + live)
+    c = rng.integers(0, 1000, size=(1, N, Kp)).astype(np.int64)
+    R = rng.integers(0, 1000, size=(1, N - 1, Kp, Kp)).astype(np.int64)
+    for i in range(N):
+        n_i = live if i % 7 else max(1, live // 3)                    # every seventh operator is narrow
+        dead = rng.permutation(Kp)[n_i:]
+        c[0, i, dead] = INF
+    R[0][rng.random(size=(N - 1, Kp, Kp)) < 0.05] = INF               # and some pairs cannot be converted
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R, nthreads=8)
+    dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, N, Kp)
+    assert need > 0
+    ws = torch.full((need,), 0xA5, dtype=torch.uint8, device=DEV)
+    arg = torch.full((1, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+    vfinal = torch.zeros((1, Kp), dtype=torch.int64, device=DEV)
+    total = torch.zeros(1, dtype=torch.int64, device=DEV)
+    last = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(1, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(total.cpu().numpy(), o_total) and np.array_equal(last.cpu().numpy(), o_last)
+    assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+
+
 def test_long_chain_that_dies_in_the_middle():
     # nothing is feasible from one operator on: every later segment starts from an all-infeasible vector
     Kp, N = 64, 700
