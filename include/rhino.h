@@ -135,13 +135,21 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
  *           undefined before and after; calls that share a workspace must not overlap):
  *           - one or two long chains (B <= 2, N >= 128, Kp 64, 128 or 256) are cut into
  *             segments: the min-plus matrix of every segment (all at once), the vectors at
- *             the segment boundaries, then the plain sweep inside all segments as one batch.
- *             Same outputs bit for bit, about ten times faster for 8192 operators x 256;
+ *             the segment boundaries, then the plain sweep inside all segments at once.
+ *             Same outputs bit for bit; 8192 operators x 256 take a quarter of the time when
+ *             every strategy is feasible and a fortieth on tables from sharding specs, where a
+ *             third of the slots are valid layouts (infeasible strategies are skipped);
  *           - otherwise a few (B <= 32) long (N >= 64) chains of wide tables (Kp 128 or 256)
  *             are spread over eight workgroups each, which meet once per edge through the
  *             workspace.  That meeting is a bounded wait: if a workgroup ever gives up (never
  *             seen; it needs the eight workgroups of a problem resident together), the
- *             problem returns total = -1.
+ *             problem returns total = -1;
+ *           - given rh_workspace_size(RH_WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp) bytes instead
+ *             (B <= 32, N >= 128, Kp 64, 128 or 256; more bytes than the above), the problems
+ *             go through the segmented route one after the other.  Worth it when most
+ *             strategies are infeasible: then a problem takes a twenty-fifth of what the eight
+ *             workgroups need for up to 32 problems together; with every strategy feasible
+ *             it is the better choice only for B <= 2.
  *           With NULL, 0 the call needs no workspace.
  * Base pointers and batch strides must keep every row 16-byte aligned.
  */
@@ -345,6 +353,7 @@ int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT,
 #define RH_WS_STAGE_DP 1
 #define RH_WS_STAGE_DP_WINDOW 2
 #define RH_WS_STAGE_DP_INTERVAL 3
+#define RH_WS_MINPLUS_CHAIN_SEGMENTED 4
 /* Bytes of workspace the call `which` needs for these sizes (0 if none or
  * if the sizes are invalid). */
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,

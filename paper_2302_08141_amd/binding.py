@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "librhino.so")
 
 INF = 1 << 52
 KMIN, KMAX, NMAX = 16, 1024, 16384
-WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW, WS_STAGE_DP_INTERVAL = 0, 1, 2, 3
+WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW, WS_STAGE_DP_INTERVAL, WS_MINPLUS_CHAIN_SEGMENTED = 0, 1, 2, 3, 4
 
 
 class RhinoError(RuntimeError):

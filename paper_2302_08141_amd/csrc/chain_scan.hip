@@ -702,11 +702,11 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
 }  // namespace
 
 size_t scan_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
-    // worth it for one or two long chains; more problems fill the chip better with a workgroup (or eight) each
-    if (B < 1 || B > 2 || N < 128 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
+    // the problems of a call go one after the other through the same workspace
+    if (B < 1 || B > 32 || N < 128 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
     const ScanPlan pl = plan_scan(N, Kp);
     if (pl.SL > kMaxSegLen) return 0;
-    return (size_t)B * pl.total;
+    return pl.total;
 }
 
 hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
@@ -717,7 +717,7 @@ hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
     const int nseg_pad = (nseg + 7) & ~7;
     const size_t lds = 2 * kScPiece * sizeof(double);
     for (int p = 0; p < B; ++p) {
-        char* ws = static_cast<char*>(workspace) + (size_t)p * pl.total;
+        char* ws = static_cast<char*>(workspace);       // stream order keeps the problems apart
         int64_t* M = reinterpret_cast<int64_t*>(ws + pl.m_off);
         int64_t* Msub = reinterpret_cast<int64_t*>(ws + pl.msub_off);
         int64_t* c_seg = reinterpret_cast<int64_t*>(ws + pl.cseg_off);

@@ -78,11 +78,13 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t
         return RH_ERR_SHAPE;
     if (workspace != nullptr && (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
         return RH_ERR_WORKSPACE;
+    // One or two long chains are cut into segments; three and more take the segmented route only when the caller
+    // brings its (larger) workspace, which says that the tables are sparse enough for it to pay.
     const size_t scan = rh::scan_workspace_bytes(B, N, Kp);
-    if (scan != 0 && workspace != nullptr && workspace_bytes >= scan)
+    const size_t gang = rh::gang_workspace_bytes(B, N, Kp);
+    if (scan != 0 && workspace != nullptr && workspace_bytes >= scan && (B <= 2 || scan > gang))
         return from_hip(rh::launch_chain_scan(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal, total,
                                               last, workspace, static_cast<hipStream_t>(stream)));
-    const size_t gang = rh::gang_workspace_bytes(B, N, Kp);
     if (gang != 0 && workspace != nullptr && workspace_bytes >= gang)
         return from_hip(rh::launch_chain_gang(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal,
                                               total, last, workspace, static_cast<hipStream_t>(stream)));
@@ -211,9 +213,10 @@ int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int
 
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or_S) {
     if (which == RH_WS_MINPLUS_CHAIN) {
-        const size_t scan = rh::scan_workspace_bytes(B, N_or_L, Kp_or_S);
+        const size_t scan = B <= 2 ? rh::scan_workspace_bytes(B, N_or_L, Kp_or_S) : 0;
         return scan != 0 ? scan : rh::gang_workspace_bytes(B, N_or_L, Kp_or_S);
     }
+    if (which == RH_WS_MINPLUS_CHAIN_SEGMENTED) return rh::scan_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_STAGE_DP) {
         if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);

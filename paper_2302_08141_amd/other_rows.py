@@ -41,20 +41,27 @@ def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
     plan = torch.empty((n_k, N), dtype=torch.int32, device=dev)
     plan_mem = torch.empty(n_k, dtype=torch.int64, device=dev)
     first = torch.empty(1, dtype=torch.int32, device=dev)
-    ws_bytes = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, n_k, N, Kp)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
     limit = 64 << 30
+    times = {}
+    # the chain batch spread over eight workgroups per problem, and (these tables are sparse: a third of the slots
+    # are valid layouts) the problems one after the other through the segmented route
+    for name, kind in (("eight_workgroups_each", rh.WS_MINPLUS_CHAIN), ("segmented", rh.WS_MINPLUS_CHAIN_SEGMENTED)):
+        ws_bytes = rh.rh_workspace_size(kind, n_k, N, Kp)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
 
-    def run():
-        rh.rh_mask_replicated(N, Kp, n_k, k0, c, pb, repl, cm)
-        rh.rh_minplus_chain(n_k, N, Kp, cm, N * Kp, R, 0, arg, None, total, last, ws)
-        rh.rh_backtrack(n_k, N, Kp, arg, last, plan)
-        rh.rh_plan_memory(n_k, N, Kp, plan, mem, total, limit, plan_mem, first)
+        def run():
+            rh.rh_mask_replicated(N, Kp, n_k, k0, c, pb, repl, cm)
+            rh.rh_minplus_chain(n_k, N, Kp, cm, N * Kp, R, 0, arg, None, total, last, ws)
+            rh.rh_backtrack(n_k, N, Kp, arg, last, plan)
+            rh.rh_plan_memory(n_k, N, Kp, plan, mem, total, limit, plan_mem, first)
 
-    t = _best_ms(run, reps=2)
+        times[name] = _best_ms(run, reps=2)
+        del ws
+    t = times["segmented"]
     cells = n_k * (N - 1) * Kp * Kp
     return {"k_values": n_k, "k0": k0, "limit_bytes": limit, "first_feasible_offset": int(first.item()),
-            "sweep_ms": t, "cells_per_s": cells / (t * 1e-3),
+            "sweep_ms": t, "sweep_method": "segmented chains, one problem after the other",
+            "sweep_ms_eight_workgroups_each": times["eight_workgroups_each"], "cells_per_s": cells / (t * 1e-3),
             "shared_table_gbps": cells * 8 / (t * 1e-3) / 1e9}
 
 

@@ -242,6 +242,32 @@ def test_segmented_chain_by_number_of_feasible_strategies(Kp, N, live):
     assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
 
 
+def test_several_chains_through_the_segmented_route():
+    # more than two problems take the segmented route when the caller brings its workspace; R shared or not
+    rng = np.random.default_rng(77)
+    B, N, Kp = 5, 300, 128
+    c = rng.integers(0, 1000, size=(B, N, Kp)).astype(np.int64)
+    c[rng.random(size=c.shape) < 0.6] = INF
+    c[:, :, 0] = rng.integers(0, 1000, size=(B, N))                   # strategy 0 stays feasible everywhere
+    for shared in (False, True):
+        R = rng.integers(0, 1000, size=(1 if shared else B, N - 1, Kp, Kp)).astype(np.int64)
+        o_arg, o_vf, o_total, o_last = (oracle.chain(c, R[0], nthreads=8, shared_R=True) if shared
+                                        else oracle.chain(c, R, nthreads=8))
+        dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+        need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp)
+        assert need > rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp) > 0
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+        vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+        total = torch.zeros(B, dtype=torch.int64, device=DEV)
+        last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+        rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, 0 if shared else (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(total.cpu().numpy(), o_total) and np.array_equal(last.cpu().numpy(), o_last)
+        assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+        assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+
+
 def test_long_chain_that_dies_in_the_middle():
     # nothing is feasible from one operator on: every later segment starts from an all-infeasible vector
     Kp, N = 64, 700
