@@ -26,7 +26,7 @@ def run_chain(c, R, o, ws=None):
 
 
 @pytest.mark.parametrize("B,N,Kp,with_ws", [(9, 30, 128, False), (2, 80, 256, True), (2100, 3, 64, False),
-                                            (1, 700, 64, True)])   # the last: one long chain cut into segments
+                                            (1, 700, 64, True), (2, 300, 128, True)])   # the last two: long chains cut into segments
 def test_graph_capture_and_replay(B, N, Kp, with_ws):
     hc, hR = syn.random_chain_batch(range(B), N, Kp, 1000, 5000)
     c, R = torch.from_numpy(hc).to(DEV), torch.from_numpy(hR).to(DEV)
