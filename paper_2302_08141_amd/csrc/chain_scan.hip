@@ -454,13 +454,16 @@ __device__ __forceinline__ void vector_times_matrix(const int64_t* __restrict__ 
     __syncthreads();
 }
 
-// One workgroup: v_0 = c_0 (saturated), v_{g+1} = v_g (x) M_g.  The final sweep runs on problems of SLq = SL / kScSub
+// One workgroup per problem: v_0 = c_0 (saturated), v_{g+1} = v_g (x) M_g.  The final sweep runs on problems of SLq = SL / kScSub
 // edges; problem q's node costs are c_seg[q][SLq + 1][KP] with the start vector as row 0: v_g is row 0 of problem
 // kScSub * g.
 template <int KP>
 __global__ void __launch_bounds__(kBdThreads)
-scan_boundary_kernel(int32_t SL, int32_t SLq, int32_t nseg, const int64_t* __restrict__ c,
-                     const int64_t* __restrict__ M, int64_t* __restrict__ c_seg) {
+scan_boundary_kernel(int32_t SL, int32_t SLq, int32_t nseg, const int64_t* __restrict__ c, int64_t c_bs,
+                     const int64_t* __restrict__ M, int64_t* __restrict__ c_seg, int64_t ws_elems) {
+    c += (int64_t)blockIdx.x * c_bs;              // one workgroup per problem; a problem's workspace is ws_elems long
+    M += (int64_t)blockIdx.x * ws_elems;
+    c_seg += (int64_t)blockIdx.x * ws_elems;
     __shared__ int64_t vs[2][KP];
     __shared__ int64_t part[kBdWaves][KP];
     __shared__ int32_t wave_cnt[KP / 64];
@@ -489,11 +492,14 @@ scan_boundary_kernel(int32_t SL, int32_t SLq, int32_t nseg, const int64_t* __res
     }
 }
 
-// Workgroup (j, g): start vector of part j + 1 of segment g = v_g (x) Msub[g][j], row 0 of problem kScSub * g + j + 1.
+// Workgroup (j, g, problem): start vector of part j + 1 of segment g = v_g (x) Msub[g][j], row 0 of problem kScSub * g + j + 1.
 template <int KP>
 __global__ void __launch_bounds__(kBdThreads)
-scan_part_vectors_kernel(int32_t SL, int32_t SLq, const int64_t* __restrict__ c, const int64_t* __restrict__ Msub,
-                         int64_t* __restrict__ c_seg) {
+scan_part_vectors_kernel(int32_t SL, int32_t SLq, const int64_t* __restrict__ c, int64_t c_bs,
+                         const int64_t* __restrict__ Msub, int64_t* __restrict__ c_seg, int64_t ws_elems) {
+    c += (int64_t)blockIdx.z * c_bs;              // blockIdx.z = problem
+    Msub += (int64_t)blockIdx.z * ws_elems;
+    c_seg += (int64_t)blockIdx.z * ws_elems;
     __shared__ int64_t vs[2][KP];
     __shared__ int64_t part[kBdWaves][KP];
     __shared__ int32_t wave_cnt[KP / 64];
@@ -517,7 +523,7 @@ scan_part_vectors_kernel(int32_t SL, int32_t SLq, const int64_t* __restrict__ c,
 }
 
 // ---- step 3: the sweep inside every part --------------------------------------------------------
-// One workgroup per part: the plain forward sweep from the part's start vector (row 0 of its problem in c_seg)
+// One workgroup per part (and problem): the plain forward sweep from the part's start vector (row 0 of its problem in c_seg)
 // over its SLq edges, writing arg.  Rows of an edge table whose strategy has an infeasible node cost cannot
 // hold a minimum (their vector entry is infeasible) and are not read; the others are dealt to the 16 waves in
 // rank order, D rows per wave in flight (D * trips covers the fullest edge): a slot is refilled with the same wave's row of the next edge as soon as
@@ -611,8 +617,13 @@ __device__ __forceinline__ void sweep_part(int SLq, int trips, const int64_t* __
 
 template <int KP>
 __global__ void __launch_bounds__(kScThreads)
-scan_sweep_kernel(int32_t SLq, const int64_t* __restrict__ c, const int64_t* __restrict__ R,
-                  const int64_t* __restrict__ c_seg, uint16_t* __restrict__ arg) {
+scan_sweep_kernel(int32_t SLq, const int64_t* __restrict__ c, int64_t c_bs, const int64_t* __restrict__ R,
+                  int64_t R_bs, const int64_t* __restrict__ c_seg, int64_t ws_elems, uint16_t* __restrict__ arg,
+                  int64_t arg_bs) {
+    c += (int64_t)blockIdx.y * c_bs;              // blockIdx.y = problem
+    R += (int64_t)blockIdx.y * R_bs;
+    c_seg += (int64_t)blockIdx.y * ws_elems;
+    arg += (int64_t)blockIdx.y * arg_bs;
     __shared__ __align__(16) int64_t part_v[kScWaves][KP];
     __shared__ uint16_t part_a[kScWaves][KP];
     __shared__ int64_t vs[KP];
@@ -702,89 +713,101 @@ __host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
 }  // namespace
 
 size_t scan_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
-    // the problems of a call go one after the other through the same workspace
     if (B < 1 || B > 32 || N < 128 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
     const ScanPlan pl = plan_scan(N, Kp);
     if (pl.SL > kMaxSegLen) return 0;
-    return pl.total;
+    return (size_t)B * pl.total;
 }
+
+namespace {
+
+// The segment matrices problem by problem (each fills the chip); then the boundary vectors, the part vectors and
+// the sweep inside the parts for all problems together (the boundary pass is one workgroup per problem); the last
+// segments one by one.
+template <int KP>
+hipError_t run_scan(const ScanPlan& pl, int32_t B, int32_t N, const int64_t* c, int64_t c_bs, const int64_t* R,
+                    int64_t R_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last, void* workspace,
+                    hipStream_t stream) {
+    const int nseg = pl.G - 1;                    // segments that need a matrix: all but the last
+    const int nseg_pad = (nseg + 7) & ~7;
+    const size_t lds = 2 * kScPiece * sizeof(double);
+    const int SLq = pl.SL / kScSub, n_part = nseg * kScSub;
+    const int64_t prob_c = (int64_t)(SLq + 1) * KP, prob_R = (int64_t)SLq * KP * KP;
+    const int64_t mat = (int64_t)KP * KP, sub = (kScSub - 1) * mat;
+    const int64_t ws_elems = (int64_t)(pl.total / sizeof(int64_t));
+    const int64_t arg_bs = (int64_t)(N - 1) * KP;
+    const int l_last = nseg * pl.SL;              // first operator of the last segment
+    constexpr bool own_sweep = KP >= 128;         // step 3 by scan_sweep_kernel, which reads the node costs in place
+    char* ws0 = static_cast<char*>(workspace);
+    int64_t* M0 = reinterpret_cast<int64_t*>(ws0 + pl.m_off);
+    int64_t* Msub0 = reinterpret_cast<int64_t*>(ws0 + pl.msub_off);
+    int64_t* c_seg0 = reinterpret_cast<int64_t*>(ws0 + pl.cseg_off);
+
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)(((KP + kScBlock - 1) / kScBlock) * nseg_pad));
+    for (int p = 0; p < B; ++p) {
+        int64_t* M = M0 + p * ws_elems;
+        int64_t* Msub = Msub0 + p * ws_elems;
+        int64_t* c_seg = c_seg0 + p * ws_elems;
+        const int64_t* cp = c + (int64_t)p * c_bs;
+        const int64_t* Rp = R + (int64_t)p * R_bs;
+        // rows 1.. of the node costs of the last segment (and of every part, where chain_coop_kernel sweeps them)
+        const int64_t n_copy = (int64_t)n_part * SLq * KP, n_copy_last = (int64_t)pl.r * KP;
+        if (!own_sweep)
+            hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N, SLq,
+                               KP, n_part, cp, c_seg);
+        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy_last + 255) / 256)), dim3(256), 0, stream,
+                           N - l_last, pl.r, KP, 1, cp + (int64_t)l_last * KP, c_seg + (int64_t)n_part * prob_c);
+        for (int j = 0; j < kScSub; ++j) {
+            const bool fin = j + 1 == kScSub;
+            hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,
+                               nseg_pad, cp, Rp, j ? Msub + (j - 1) * mat : nullptr, sub, fin ? M : Msub + j * mat,
+                               fin ? mat : sub);
+        }
+    }
+    hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3((unsigned)B), dim3(kBdThreads), 0, stream, pl.SL, SLq, nseg, c,
+                       c_bs, M0, c_seg0, ws_elems);
+    hipLaunchKernelGGL((scan_part_vectors_kernel<KP>), dim3(kScSub - 1, nseg, (unsigned)B), dim3(kBdThreads), 0, stream,
+                       pl.SL, SLq, c, c_bs, Msub0, c_seg0, ws_elems);
+    if constexpr (own_sweep)
+        hipLaunchKernelGGL((scan_sweep_kernel<KP>), dim3((unsigned)n_part, (unsigned)B), dim3(kScThreads), 0, stream, SLq,
+                           c, c_bs, R, R_bs, c_seg0, ws_elems, arg, arg_bs);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    for (int p = 0; p < B; ++p) {
+        int64_t* c_seg = c_seg0 + p * ws_elems;
+        const int64_t* Rp = R + (int64_t)p * R_bs;
+        uint16_t* argp = arg + p * arg_bs;
+        if constexpr (!own_sweep) {
+            // the parts as one batch (their totals are scratch)
+            int64_t* seg_total = reinterpret_cast<int64_t*>(ws0 + pl.tot_off) + p * ws_elems;
+            int32_t* seg_last = reinterpret_cast<int32_t*>(ws0 + pl.last_off) + 2 * p * ws_elems;
+            e = launch_chain(n_part, SLq + 1, KP, c_seg, prob_c, Rp, prob_R, argp, nullptr, seg_total, seg_last, stream);
+            if (e != hipSuccess) return e;
+        }
+        // the last segment, whose final vector, total and last are the chain's
+        e = launch_chain(1, pl.r + 1, KP, c_seg + (int64_t)n_part * prob_c, 0, Rp + (int64_t)n_part * prob_R, 0,
+                         argp + (int64_t)l_last * KP, vfinal ? vfinal + (int64_t)p * KP : nullptr, total + p, last + p,
+                         stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
 
 hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
                              int64_t R_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last,
                              void* workspace, hipStream_t stream) {
     const ScanPlan pl = plan_scan(N, Kp);
-    const int nseg = pl.G - 1;                    // segments that need a matrix: all but the last
-    const int nseg_pad = (nseg + 7) & ~7;
-    const size_t lds = 2 * kScPiece * sizeof(double);
-    for (int p = 0; p < B; ++p) {
-        char* ws = static_cast<char*>(workspace);       // stream order keeps the problems apart
-        int64_t* M = reinterpret_cast<int64_t*>(ws + pl.m_off);
-        int64_t* Msub = reinterpret_cast<int64_t*>(ws + pl.msub_off);
-        int64_t* c_seg = reinterpret_cast<int64_t*>(ws + pl.cseg_off);
-        int64_t* seg_total = reinterpret_cast<int64_t*>(ws + pl.tot_off);
-        int32_t* seg_last = reinterpret_cast<int32_t*>(ws + pl.last_off);
-        const int64_t* cp = c + (int64_t)p * c_bs;
-        const int64_t* Rp = R + (int64_t)p * R_bs;
-        uint16_t* argp = arg + (int64_t)p * (N - 1) * Kp;
-        const int SLq = pl.SL / kScSub, n_part = nseg * kScSub;
-        const int64_t prob_c = (int64_t)(SLq + 1) * Kp, prob_R = (int64_t)SLq * Kp * Kp;
-        int64_t* c_last = c_seg + (int64_t)n_part * prob_c;   // node costs of the last segment: r + 1 rows
-        const int l_last = nseg * pl.SL;                      // its first operator
-
-        const dim3 grid((unsigned)(((Kp + kScBlock - 1) / kScBlock) * nseg_pad));
-        // rows 1.. of the node costs of every part and of the last segment
-        const int64_t n_copy = (int64_t)n_part * SLq * Kp, n_copy_last = (int64_t)pl.r * Kp;
-        const bool own_sweep = Kp >= 128;         // step 3 by scan_sweep_kernel, which reads the node costs in place
-        if (!own_sweep)
-            hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy + 255) / 256)), dim3(256), 0, stream, N, SLq,
-                               Kp, n_part, cp, c_seg);
-        hipLaunchKernelGGL(scan_copy_c_kernel, dim3((unsigned)((n_copy_last + 255) / 256)), dim3(256), 0, stream,
-                           N - l_last, pl.r, Kp, 1, cp + (int64_t)l_last * Kp, c_last);
-#define RH_SCAN(KP)                                                                                                 \
-    do {                                                                                                            \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP>),                   \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
-        if (e != hipSuccess) return e;                                                                              \
-        for (int j = 0; j < kScSub; ++j) {                                                                          \
-            const int64_t mat = (int64_t)KP * KP, sub = (kScSub - 1) * mat;                                         \
-            const bool fin = j + 1 == kScSub;                                                                       \
-            hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,  \
-                               nseg_pad, cp, Rp, j ? Msub + (j - 1) * mat : nullptr, sub, fin ? M : Msub + j * mat, \
-                               fin ? mat : sub);                                                       \
-        }                                                                                                           \
-        hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3(1), dim3(kBdThreads), 0, stream, pl.SL, SLq, nseg, cp,  \
-                           M, c_seg);                                                                               \
-        hipLaunchKernelGGL((scan_part_vectors_kernel<KP>), dim3(kScSub - 1, nseg), dim3(kBdThreads), 0, stream,     \
-                           pl.SL, SLq, cp, Msub, c_seg);                                                            \
-    } while (0)
-        switch (Kp) {
-            case 64: RH_SCAN(64); break;
-            case 128: RH_SCAN(128); break;
-            case 256: RH_SCAN(256); break;
-            default: return hipErrorInvalidValue;
-        }
-#undef RH_SCAN
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        // step 3: the sweep inside every part as one batch (their totals are scratch), then the last segment,
-        // whose final vector, total and last are the chain's.
-        if (Kp == 256)
-            hipLaunchKernelGGL((scan_sweep_kernel<256>), dim3((unsigned)n_part), dim3(kScThreads), 0, stream, SLq, cp, Rp,
-                               c_seg, argp);
-        else if (Kp == 128)
-            hipLaunchKernelGGL((scan_sweep_kernel<128>), dim3((unsigned)n_part), dim3(kScThreads), 0, stream, SLq, cp, Rp,
-                               c_seg, argp);
-        else
-            e = launch_chain(n_part, SLq + 1, Kp, c_seg, prob_c, Rp, prob_R, argp, nullptr, seg_total, seg_last, stream);
-        if (e != hipSuccess) return e;
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        e = launch_chain(1, pl.r + 1, Kp, c_last, 0, Rp + (int64_t)n_part * prob_R, 0,
-                         argp + (int64_t)l_last * Kp, vfinal ? vfinal + (int64_t)p * Kp : nullptr, total + p, last + p,
-                         stream);
-        if (e != hipSuccess) return e;
+    switch (Kp) {
+        case 64: return run_scan<64>(pl, B, N, c, c_bs, R, R_bs, arg, vfinal, total, last, workspace, stream);
+        case 128: return run_scan<128>(pl, B, N, c, c_bs, R, R_bs, arg, vfinal, total, last, workspace, stream);
+        case 256: return run_scan<256>(pl, B, N, c, c_bs, R, R_bs, arg, vfinal, total, last, workspace, stream);
+        default: return hipErrorInvalidValue;
     }
-    return hipSuccess;
 }
 
 }  // namespace rh

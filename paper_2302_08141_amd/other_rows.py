@@ -44,7 +44,7 @@ def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
     limit = 64 << 30
     times = {}
     # the chain batch spread over eight workgroups per problem, and (these tables are sparse: a third of the slots
-    # are valid layouts) the problems one after the other through the segmented route
+    # are valid layouts) all problems through the segmented route
     for name, kind in (("eight_workgroups_each", rh.WS_MINPLUS_CHAIN), ("segmented", rh.WS_MINPLUS_CHAIN_SEGMENTED)):
         ws_bytes = rh.rh_workspace_size(kind, n_k, N, Kp)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
@@ -60,7 +60,7 @@ def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
     t = times["segmented"]
     cells = n_k * (N - 1) * Kp * Kp
     return {"k_values": n_k, "k0": k0, "limit_bytes": limit, "first_feasible_offset": int(first.item()),
-            "sweep_ms": t, "sweep_method": "segmented chains, one problem after the other",
+            "sweep_ms": t, "sweep_method": "segmented chains",
             "sweep_ms_eight_workgroups_each": times["eight_workgroups_each"], "cells_per_s": cells / (t * 1e-3),
             "shared_table_gbps": cells * 8 / (t * 1e-3) / 1e9}
 

@@ -29,15 +29,15 @@ def test_host_only_calls():
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 4096, 512, 128) == 0
     # one or two long chains: room for the segment matrices (two thirds + whole), at least a Kp x Kp table each
     one = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 8192, 256)
-    assert one > 3 * 70 * 256 * 256 * 8 and rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 2, 8192, 256) == one
+    assert one > 3 * 70 * 256 * 256 * 8 and rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 2, 8192, 256) == 2 * one
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 128, 64) > 0
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 127, 64) == 0          # too short to cut
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 127, 256) > 0          # eight workgroups instead
     gang = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 3, 8192, 256)             # three chains: eight workgroups each
     assert 0 < gang < one
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 8192, 512) == 0
-    # the segmented route for more problems: one problem's room, shared by all
-    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, 16, 8192, 256) == one
+    # the segmented route for more problems
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, 16, 8192, 256) == 16 * one
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, 33, 8192, 256) == 0
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, 4, 127, 256) == 0
     pairs = 2 * 4097 * 16                      # two buffers of 16-byte pairs per problem
