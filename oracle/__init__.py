@@ -153,16 +153,21 @@ def stage_dp(cost: np.ndarray, S: int, s_query: int = 0, nthreads: int = 1):
     return bott, cut, bounds
 
 
-def interval_costs(c: np.ndarray, R: np.ndarray, ldT: int = 0, nthreads: int = 1) -> np.ndarray:
+def interval_costs(c: np.ndarray, R: np.ndarray, ldT: int = 0, nthreads: int = 1, max_len: int = 0) -> np.ndarray:
     """c[L][Kp], R[L-1][Kp][Kp] -> T int64[L][ldT] (ldT >= L+1, default L+1): T[i][j] = least plan cost of the
-    operators i..j-1 on their own, INF where j <= i; columns beyond L are left at -1."""
+    operators i..j-1 on their own, INF where j <= i; columns beyond L are left at -1.  max_len > 0: no stage
+    longer than max_len operators, T[i][j] = INF for j - i > max_len."""
     _chk(c, np.int64, "c"); _chk(R, np.int64, "R")
     L, Kp = c.shape
     assert R.shape == (max(L - 1, 0), Kp, Kp)
     ldT = ldT or L + 1
     T = np.full((L, ldT), -1, dtype=np.int64)
-    rc = lib().oracle_interval_costs(ctypes.c_int32(L), ctypes.c_int32(Kp), _p(c), _p(R), ctypes.c_int64(ldT),
-                                     _p(T), ctypes.c_int32(nthreads))
+    if max_len > 0:
+        rc = lib().oracle_interval_costs_banded(ctypes.c_int32(L), ctypes.c_int32(Kp), ctypes.c_int32(max_len),
+                                                _p(c), _p(R), ctypes.c_int64(ldT), _p(T), ctypes.c_int32(nthreads))
+    else:
+        rc = lib().oracle_interval_costs(ctypes.c_int32(L), ctypes.c_int32(Kp), _p(c), _p(R), ctypes.c_int64(ldT),
+                                         _p(T), ctypes.c_int32(nthreads))
     if rc != 0:
         raise ValueError(f"oracle_interval_costs rc={rc}")
     return T

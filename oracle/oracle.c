@@ -34,7 +34,10 @@
  *            gets its own SPMD plan; Sec. 5.1 balances the stages):
  *            T[i][j] = min over plans of operators i..j-1 of the Sec. 4.2
  *            objective on those operators and the edges between them
- *            -> oracle_interval_costs; dp[1][j] = T[0][j], dp[s][j] =
+ *            -> oracle_interval_costs (oracle_interval_costs_banded: no
+ *            stage longer than a given number of operators, a limit in
+ *            the spirit of the bound tightening of Sec. 5.2; longer
+ *            intervals are INF); dp[1][j] = T[0][j], dp[s][j] =
  *            min_{s-1<=i<j} max(dp[s-1][i], T[i][j]), ties -> lowest i
  *            -> oracle_stage_interval.
  *
@@ -320,23 +323,23 @@ int oracle_stage_dp(int32_t B, int32_t L, int32_t S, const int64_t *cost,
 /* node costs and the edges between them), INF where j <= i.            */
 /* Written out start by start: a forward sweep from operator i, whose   */
 /* running minimum after operator j-1 is T[i][j].                       */
-int oracle_interval_costs(int32_t L, int32_t Kp, const int64_t *c,
-                          const int64_t *R, int64_t ldT, int64_t *T,
-                          int32_t nthreads)
+static int interval_rows(int32_t L, int32_t Kp, int32_t max_len,
+                         const int64_t *c, const int64_t *R, int64_t ldT,
+                         int64_t *T, int32_t nthreads)
 {
-    if (L < 1 || Kp < 1 || ldT < (int64_t)L + 1) return -1;
+    if (L < 1 || Kp < 1 || max_len < 1 || ldT < (int64_t)L + 1) return -1;
     if (nthreads < 1) nthreads = 1;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
     for (int i = 0; i < L; ++i) {
         int64_t *row = T + (size_t)i * (size_t)ldT;
         int64_t *v = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
         int64_t *w = (int64_t *)malloc(sizeof(int64_t) * (size_t)Kp);
-        for (int j = 0; j <= i; ++j) row[j] = ORC_INF;
+        for (int j = 0; j <= L; ++j) row[j] = ORC_INF;
         for (int b = 0; b < Kp; ++b) {
             int64_t x = c[(size_t)i * Kp + b];
             v[b] = x >= ORC_INF ? ORC_INF : x;
         }
-        for (int l = i; l < L; ++l) {
+        for (int l = i; l < L && l - i < max_len; ++l) {
             /* v = cost vector of the chain i..l by the strategy of operator l */
             int64_t best = v[0];
             for (int b = 1; b < Kp; ++b) if (v[b] < best) best = v[b];
@@ -357,6 +360,25 @@ int oracle_interval_costs(int32_t L, int32_t Kp, const int64_t *c,
         free(v); free(w);
     }
     return 0;
+}
+
+int oracle_interval_costs(int32_t L, int32_t Kp, const int64_t *c,
+                          const int64_t *R, int64_t ldT, int64_t *T,
+                          int32_t nthreads)
+{
+    return interval_rows(L, Kp, L, c, R, ldT, T, nthreads);
+}
+
+/* The same table when no stage may hold more than max_len operators    */
+/* (Sec. 5.2 keeps every operator within a tolerance of the stage that   */
+/* perfect balance gives it, so a stage cannot stretch over arbitrarily  */
+/* many operators; here the caller states the limit): T[i][j] = INF for  */
+/* j - i > max_len, the entries with j - i <= max_len as above.          */
+int oracle_interval_costs_banded(int32_t L, int32_t Kp, int32_t max_len,
+                                 const int64_t *c, const int64_t *R,
+                                 int64_t ldT, int64_t *T, int32_t nthreads)
+{
+    return interval_rows(L, Kp, max_len, c, R, ldT, T, nthreads);
 }
 
 /* ------------------------------------------------------------------ */

@@ -162,3 +162,39 @@ def test_stages_found_on_a_table_of_chain_optima_are_consistent():
     # the additive search on per-operator minima ignores the edges: it can only be lower
     lower, _, _ = oracle.stage_dp(c.min(axis=1)[None].copy(), S)
     assert (lower[0] <= bott[0]).all()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_banded_table_against_all_plans_and_limited_cut_sets(seed):
+    # No stage longer than max_len operators (Sec. 5.2 keeps operators near their balanced stage): inside the band
+    # the table is the definition, outside it is infeasible, and the search over it is the best cut set among
+    # those whose stages all respect the limit, stage times by enumeration of plans.
+    rng = np.random.default_rng(200 + seed)
+    L, K = int(rng.integers(3, 8)), int(rng.integers(1, 4))
+    max_len = int(rng.integers(1, L + 2))                 # from single-operator stages to no limit at all
+    c, R = random_chain(rng, L, K, 6 if seed % 2 else 50, 6 if seed % 2 else 80)
+    T = oracle.interval_costs(c, R, max_len=max_len)
+    for i in range(L):
+        for j in range(L + 1):
+            want = all_plans(c, R, i, j) if i < j <= i + max_len else INF
+            assert T[i, j] == want, (i, j, max_len)
+    full = oracle.interval_costs(c, R)
+    if max_len >= L:
+        assert np.array_equal(T, full)
+    S = L
+    bott, _, _ = oracle.stage_interval(T[None], S)
+    for s in range(1, S + 1):
+        best = INF
+        for cuts in itertools.combinations(range(1, L), s - 1):
+            b = (0,) + cuts + (L,)
+            if all(b[t + 1] - b[t] <= max_len for t in range(s)):
+                best = min(best, max(all_plans(c, R, b[t], b[t + 1]) for t in range(s)))
+        assert bott[0, s - 1] == best, (s, max_len)
+
+
+def test_banded_table_of_single_operator_stages():
+    rng = np.random.default_rng(210)
+    c, R = random_chain(rng, 9, 3)
+    T = oracle.interval_costs(c, R, max_len=1)
+    for i in range(9):
+        assert T[i, i + 1] == c[i].min() and (np.delete(T[i, :10], i + 1) == INF).all()
