@@ -349,6 +349,28 @@ int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT,
                          int32_t s_query, int32_t* bounds, void* workspace,
                          size_t workspace_bytes, void* stream);
 
+/*
+ * rh_interval_costs_banded, rh_stage_dp_interval_banded -- the same two calls when no stage may
+ * hold more than max_len operators.  Sec. 5.2 keeps every operator within a tolerance of the stage
+ * that perfect balance gives it, so useful stages are short compared with the chain; the caller
+ * states the limit.  The sweep that starts at operator i then stops after max_len operators, and
+ * the search looks at the max_len rows above the diagonal only:
+ *     T[i][j]  as rh_interval_costs for 0 < j - i <= max_len, RH_INF for j - i > max_len
+ *     dp[s][j] = min over max(s-1, j - max_len) <= i < j of max( dp[s-1][i], T[i][j] ),
+ *     cut as rh_stage_dp_interval: where no candidate is feasible, dp = RH_INF and cut = s-1
+ * i.e. exactly what the unlimited calls return on a table whose entries with j - i > max_len are
+ * RH_INF (the search ignores whatever T holds there).  max_len >= 1; max_len >= L is no limit.
+ * With max_len <= L/2 the table costs about (max_len + 15) / (L/2) of the full one.
+ * All other arguments as rh_interval_costs / rh_stage_dp_interval.
+ */
+int rh_interval_costs_banded(int32_t B, int32_t L, int32_t Kp, int32_t max_len,
+                             const int64_t* c, const int64_t* R, int64_t ldT,
+                             int64_t* T, void* stream);
+int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len,
+                                int64_t ldT, const int64_t* T, int64_t* bottleneck,
+                                int32_t* cut, int32_t s_query, int32_t* bounds,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 #define RH_WS_MINPLUS_CHAIN 0
 #define RH_WS_STAGE_DP 1
 #define RH_WS_STAGE_DP_WINDOW 2

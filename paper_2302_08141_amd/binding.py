@@ -67,6 +67,9 @@ def lib():
         L.rh_stage_dp_window.restype = ctypes.c_int
         L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp]
         L.rh_stage_dp_interval.argtypes = [i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.rh_interval_costs_banded.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp, vp]
+        L.rh_stage_dp_interval_banded.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.rh_interval_costs_banded.restype = L.rh_stage_dp_interval_banded.restype = ctypes.c_int
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
         L.rh_workspace_size.restype = sz
         L.rh_check_costs.argtypes = [vp, i64, vp, vp]
@@ -244,6 +247,28 @@ def rh_stage_dp_interval(B: int, L: int, S: int, ldT: int, T, bottleneck, cut, s
                                       _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)), s_query,
                                       _ptr(bounds, torch.int32, "bounds", b * (max(s_query, 0) + 1)), ws_ptr,
                                       ws_bytes, _stream()), "rh_stage_dp_interval")
+
+
+def rh_interval_costs_banded(B: int, L: int, Kp: int, max_len: int, c, R, ldT: int, T):
+    """rh_interval_costs with no stage longer than max_len operators: T[i][j] = RH_INF for j - i > max_len."""
+    b, l, k = max(B, 0), max(L, 0), max(Kp, 0)
+    _check(lib().rh_interval_costs_banded(B, L, Kp, max_len, _ptr(c, torch.int64, "c", b * l * k),
+                                          _ptr(R, torch.int64, "R", b * max(l - 1, 0) * k * k), ldT,
+                                          _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), _stream()),
+           "rh_interval_costs_banded")
+
+
+def rh_stage_dp_interval_banded(B: int, L: int, S: int, max_len: int, ldT: int, T, bottleneck, cut, s_query: int,
+                                bounds, workspace):
+    """rh_stage_dp_interval over stages of at most max_len operators (same buffers and workspace)."""
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    b, l, s_ = max(B, 0), max(L, 0), max(S, 0)
+    _check(lib().rh_stage_dp_interval_banded(B, L, S, max_len, ldT, _ptr(T, torch.int64, "T", b * l * max(ldT, 0)),
+                                             _ptr(bottleneck, torch.int64, "bottleneck", b * s_),
+                                             _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)), s_query,
+                                             _ptr(bounds, torch.int32, "bounds", b * (max(s_query, 0) + 1)), ws_ptr,
+                                             ws_bytes, _stream()), "rh_stage_dp_interval_banded")
 
 
 def rh_check_costs(x, violations):

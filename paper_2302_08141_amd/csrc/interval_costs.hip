@@ -15,9 +15,13 @@
 // Mapping: a lane owns Kp/64 columns b; a wave keeps one row (start) in registers and
 // broadcasts V[row][a] with two v_readlane per a, so the broadcast operand travels in scalar
 // registers.  A workgroup (16 waves, 16 rows) stages R_l through LDS in 32 KiB pieces, converted
-// to fp64 on the way in, double buffered.  Rows are dealt to workgroups round-robin (row i to workgroup i mod NW): every
-// workgroup has rows of all ages, so the triangular work is balanced and all workgroups walk
-// the edges in the same order, which lets one trip to HBM serve the chip.
+// to fp64 on the way in, double buffered.  Without a limit on the stage length the rows are dealt to
+// the workgroups round-robin (row i to workgroup i mod NW): every workgroup has rows of all ages, so
+// the triangular work is balanced and all workgroups walk the edges in the same order, which lets
+// one trip to HBM serve the chip.  With a limit of at most half the chain (no stage longer than
+// max_len operators: the sweep of row i stops after max_len operators and the rest of the row is
+// infeasible) a workgroup takes 16 neighbouring rows instead and walks only the max_len + 15 edges
+// they need, all its waves busy at the same time.
 #include "kernels.h"
 
 namespace rh {
@@ -151,9 +155,9 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
 
 template <int KP>
 __global__ void __launch_bounds__(kIcThreads)
-interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int64_t c_bs,
-                      const int64_t* __restrict__ R, int64_t R_bs, int64_t ldT, int64_t* __restrict__ T,
-                      int64_t T_bs) {
+interval_costs_kernel(int32_t L, int32_t max_len, int32_t wg_step, int32_t wave_step,
+                      const int64_t* __restrict__ c, int64_t c_bs, const int64_t* __restrict__ R, int64_t R_bs,
+                      int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
     using G = Shape<KP>;
     extern __shared__ double lds[];               // two pieces of kPiece doubles
     const int tid = threadIdx.x;
@@ -166,20 +170,26 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
     const bool live_lane = lane < KP;             // KP < 64: the upper lanes carry infeasible columns
     const int col = live_lane ? lane : 0;
 
-    // rows of this wave, ascending: slot q holds start w + NW * (kIcWaves q + wave)
+    // rows of this wave, ascending: slot q holds start w wg_step + wave_step (kIcWaves q + wave)
+    // (round-robin: wg_step 1, wave_step = number of workgroups; neighbouring rows: wg_step 16, wave_step 1)
     int row[kIcSlots];
 #pragma unroll
-    for (int q = 0; q < kIcSlots; ++q) row[q] = w + NW * (kIcWaves * q + wave);
+    for (int q = 0; q < kIcSlots; ++q) row[q] = w * wg_step + wave_step * (kIcWaves * q + wave);
 
-    // entries at and left of the diagonal
+    // entries at and left of the diagonal, and those of stages longer than max_len operators
 #pragma unroll
     for (int q = 0; q < kIcSlots; ++q) {
         if (row[q] < L)
-            for (int j = lane; j <= row[q]; j += 64) T[(int64_t)row[q] * ldT + j] = kInf;
+            for (int j = lane; j <= L; j += 64)
+                if (j <= row[q] || j - row[q] > max_len) T[(int64_t)row[q] * ldT + j] = kInf;
     }
 
-    const int l0 = w;                             // the first row of this workgroup starts at operator w
-    const int n_edges = L - 1 - l0;               // edges l0 .. L-2
+    const int l0 = w * wg_step;                   // the first row of this workgroup starts at operator l0
+    // the last operator any row of this workgroup reaches: its highest row, max_len operators on, or the chain's end
+    int row_hi = l0 + wave_step * (kIcRows - 1);
+    while (row_hi >= L) row_hi -= wave_step;
+    const int l_last = row_hi + max_len - 1 < L - 1 ? row_hi + max_len - 1 : L - 1;
+    const int n_edges = l_last - l0;              // edges l0 .. l_last - 1
     const int n_pieces = n_edges * G::NCH;
 
     // piece g = (edge l0 + g / NCH, rows a of piece g % NCH); the pieces of one edge are contiguous in R
@@ -241,15 +251,16 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
     for (int q = 0; q < kIcSlots; ++q) tcol[q] = kInfD;
 
     int g = 0;
-    for (int l = l0; l < L; ++l) {
-        int n_act = 0;                            // rows started so far; they start in slot order
+    for (int l = l0; l <= l_last; ++l) {
+        int n_act = 0;                            // rows under way: started (they start in slot order), not yet max_len long
+        static_assert(kIcSlots == 1, "a finished row in slot 0 beside a running one in slot 1 has no case below");
 #pragma unroll
         for (int q = 0; q < kIcSlots; ++q) {
             if (row[q] == l) {
 #pragma unroll
                 for (int k = 0; k < G::CPT; ++k) V[q][k] = cA[k];
             }
-            n_act += row[q] <= l ? 1 : 0;
+            n_act += (row[q] <= l && l - row[q] < max_len) ? 1 : 0;
         }
         // T[row][l+1] = cheapest strategy of operator l for the chain row..l.  Lane j mod 64 keeps column
         // j; a full block of 64 columns (or the last, partial one) leaves as one coalesced store.
@@ -262,13 +273,13 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
                 for (int k = 1; k < G::CPT; ++k) m = __builtin_fmin(m, V[q][k]);
                 m = wave_min(m);
                 tcol[q] = lane == (j & 63) ? m : tcol[q];
-                if ((j & 63) == 63 || j == L) {
+                if ((j & 63) == 63 || j == L || j - row[q] == max_len) {
                     // columns of this block at or left of the diagonal still hold 2^52, which is their value
                     if (lane <= (j & 63)) T[(int64_t)row[q] * ldT + (j & ~63) + lane] = to_i64(tcol[q]);
                 }
             }
         }
-        if (l == L - 1) break;
+        if (l == l_last) break;
 
         // node costs three operators ahead: asked for now, so that the arithmetic below covers the trip
         int64_t cD[G::CPT];
@@ -313,10 +324,15 @@ interval_costs_kernel(int32_t L, int32_t NW, const int64_t* __restrict__ c, int6
 
 }  // namespace
 
-hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
-                                 int64_t R_bs, int64_t ldT, int64_t* T, int64_t T_bs, hipStream_t stream) {
+hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, int64_t c_bs,
+                                 const int64_t* R, int64_t R_bs, int64_t ldT, int64_t* T, int64_t T_bs,
+                                 hipStream_t stream) {
     if (B == 0) return hipSuccess;
+    if (max_len > L) max_len = L;
     const int NW = (L + kIcRows - 1) / kIcRows;
+    // short stages only: neighbouring rows per workgroup (each walks max_len + 15 edges); else round-robin rows
+    const bool neighbours = max_len <= L / 2;
+    const int wg_step = neighbours ? kIcRows : 1, wave_step = neighbours ? 1 : NW;
     const size_t lds = 2 * kPiece * sizeof(double);
     const dim3 grid((unsigned)NW, (unsigned)B);
 #define RH_IC(KP)                                                                                                  \
@@ -324,8 +340,8 @@ hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(interval_costs_kernel<KP>),               \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                  \
         if (e != hipSuccess) return e;                                                                             \
-        hipLaunchKernelGGL((interval_costs_kernel<KP>), grid, dim3(kIcThreads), lds, stream, L, NW, c, c_bs, R,    \
-                           R_bs, ldT, T, T_bs);                                                                    \
+        hipLaunchKernelGGL((interval_costs_kernel<KP>), grid, dim3(kIcThreads), lds, stream, L, max_len, wg_step,  \
+                           wave_step, c, c_bs, R, R_bs, ldT, T, T_bs);                                             \
     } while (0)
     switch (Kp) {
         case 16: RH_IC(16); break;

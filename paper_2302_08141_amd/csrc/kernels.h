@@ -74,12 +74,12 @@ hipError_t launch_stage_window(int32_t B, int32_t L, int32_t S, const int64_t* s
                                int32_t* bounds, void* workspace, hipStream_t stream);
 
 // Stage times of all intervals of B operator chains: T[p][i][j] for 0 <= i < L, 0 <= j <= L (row stride ldT).
-hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
+hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, int64_t c_bs, const int64_t* R,
                                  int64_t R_bs, int64_t ldT, int64_t* T, int64_t T_bs, hipStream_t stream);
 
 // Stage search over a table of interval times.
 size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S);
-hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int64_t* T, int64_t* bottleneck,
+hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* T, int64_t* bottleneck,
                                  int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                                  hipStream_t stream);
 

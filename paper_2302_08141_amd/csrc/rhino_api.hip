@@ -183,22 +183,27 @@ int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                                             workspace, static_cast<hipStream_t>(stream)));
 }
 
-int rh_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c, const int64_t* R, int64_t ldT, int64_t* T,
-                      void* stream) {
-    if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX) return RH_ERR_SHAPE;
+int rh_interval_costs_banded(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, const int64_t* R,
+                             int64_t ldT, int64_t* T, void* stream) {
+    if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX || max_len < 1) return RH_ERR_SHAPE;
     if (Kp != 16 && Kp != 32 && Kp != 64 && Kp != 128 && Kp != 256) return RH_ERR_K_RANGE;
     if (ldT < (int64_t)L + 1 || (ldT & 1)) return RH_ERR_SHAPE;
     if (B == 0) return RH_OK;
     if (!c || !T || (L > 1 && !R)) return RH_ERR_NULL;
     if (!aligned16(c) || !aligned16(T) || (R && !aligned16(R))) return RH_ERR_SHAPE;
-    return from_hip(rh::launch_interval_costs(B, L, Kp, c, (int64_t)L * Kp, R, (int64_t)(L - 1) * Kp * Kp, ldT, T,
-                                              (int64_t)L * ldT, static_cast<hipStream_t>(stream)));
+    return from_hip(rh::launch_interval_costs(B, L, Kp, max_len, c, (int64_t)L * Kp, R, (int64_t)(L - 1) * Kp * Kp,
+                                              ldT, T, (int64_t)L * ldT, static_cast<hipStream_t>(stream)));
 }
 
-int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int64_t* T, int64_t* bottleneck,
-                         int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace, size_t workspace_bytes,
-                         void* stream) {
-    if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+int rh_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c, const int64_t* R, int64_t ldT, int64_t* T,
+                      void* stream) {
+    return rh_interval_costs_banded(B, L, Kp, L > 0 ? L : 1, c, R, ldT, T, stream);
+}
+
+int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* T,
+                                int64_t* bottleneck, int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX || S < 1 || S > L || S > 1024 || max_len < 1) return RH_ERR_SHAPE;
     if (ldT < (int64_t)L + 1 || (ldT & 1)) return RH_ERR_SHAPE;
     if (s_query < 0 || s_query > S) return RH_ERR_SHAPE;
     if (B == 0) return RH_OK;
@@ -207,8 +212,15 @@ int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int
     if (!aligned16(T)) return RH_ERR_SHAPE;
     if (!workspace || !aligned16(workspace)) return RH_ERR_WORKSPACE;
     if (workspace_bytes < rh::stage_interval_workspace_bytes(B, L, S)) return RH_ERR_WORKSPACE;
-    return from_hip(rh::launch_stage_interval(B, L, S, ldT, T, bottleneck, cut, s_query, bounds, workspace,
+    return from_hip(rh::launch_stage_interval(B, L, S, max_len, ldT, T, bottleneck, cut, s_query, bounds, workspace,
                                               static_cast<hipStream_t>(stream)));
+}
+
+int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int64_t* T, int64_t* bottleneck,
+                         int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+    return rh_stage_dp_interval_banded(B, L, S, L > 0 ? L : 1, ldT, T, bottleneck, cut, s_query, bounds, workspace,
+                                       workspace_bytes, stream);
 }
 
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or_S) {

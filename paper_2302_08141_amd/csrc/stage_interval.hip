@@ -40,14 +40,14 @@ __host__ inline SiLayout si_layout(int32_t B, int32_t L) {
 }
 
 __global__ void __launch_bounds__(256)
-si_init_kernel(int32_t L, int32_t S, int64_t ldT, const int64_t* __restrict__ T, int64_t T_bs, int64_t cols,
+si_init_kernel(int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* __restrict__ T, int64_t T_bs, int64_t cols,
                int64_t* __restrict__ dp, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
     const int p = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j > L) return;
     const int64_t* row0 = T + (int64_t)p * T_bs;
     int64_t v = kInf;
-    if (j >= 1) {
+    if (j >= 1 && j <= max_len) {                         // one stage of j operators
         v = row0[j];
         v = v < kInf ? v : kInf;
     }
@@ -58,7 +58,7 @@ si_init_kernel(int32_t L, int32_t S, int64_t ldT, const int64_t* __restrict__ T,
 
 // One stage count s for the tile blockIdx.x / splits of problem blockIdx.y, rows of split blockIdx.x % splits.
 __global__ void __launch_bounds__(kSiWaves * 64)
-si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t ldT, const int64_t* __restrict__ T,
+si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int32_t max_len, int64_t ldT, const int64_t* __restrict__ T,
                int64_t T_bs, int64_t cols, const int64_t* __restrict__ prev_all, int64_t* __restrict__ cur_all,
                int64_t* __restrict__ pval, int32_t* __restrict__ pidx, int64_t* __restrict__ bottleneck,
                int32_t* __restrict__ cut) {
@@ -74,9 +74,11 @@ si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t ldT, con
     const int j0 = tile * kSiTile + 2 * lane;               // this lane's j0 and j0 + 1
     const bool in_range = j0 <= L;                          // then j0 + 1 < ldT (ldT is even and > L)
 
-    // rows that can matter to this tile: s-1 <= i < min(L, last j of the tile)
+    // rows that can matter to this tile: s-1 <= i < min(L, last j of the tile), and where the caller says that no
+    // stage is longer than max_len (such entries of T are infeasible) only i >= first j of the tile - max_len
     const int j_last = tile * kSiTile + kSiTile - 1 < L ? tile * kSiTile + kSiTile - 1 : L;
-    const int i_begin = s - 1, i_end = j_last;              // exclusive
+    const int i_band = tile * kSiTile - max_len;
+    const int i_begin = s - 1 > i_band ? s - 1 : i_band, i_end = j_last;   // exclusive
     const int n_rows = i_end > i_begin ? i_end - i_begin : 0;
     const int per = (n_rows + splits - 1) / splits;
     const int lo = i_begin + split * per;
@@ -88,7 +90,8 @@ si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t ldT, con
         // a = dp[s-1][i] (already <= 2^52); entries at or left of the diagonal do not take part
         int64_t t0 = t.x < kInf ? t.x : kInf, t1 = t.y < kInf ? t.y : kInf;
         int64_t m0 = a > t0 ? a : t0, m1 = a > t1 ? a : t1;
-        const bool ok0 = i < j0 && m0 < best0, ok1 = i < j0 + 1 && m1 < best1;
+        // stages of more than max_len operators do not take part either, whatever the table holds for them
+        const bool ok0 = i < j0 && j0 - i <= max_len && m0 < best0, ok1 = i < j0 + 1 && j0 + 1 - i <= max_len && m1 < best1;
         best0 = ok0 ? m0 : best0;
         idx0 = ok0 ? i : idx0;
         best1 = ok1 ? m1 : best1;
@@ -135,6 +138,8 @@ si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t ldT, con
             pidx[at] = bi;
         } else if (j <= L) {
             const int64_t v = bi >= 0 ? b : kInf;
+            // every candidate infeasible: the lowest i of the whole range s-1 <= i < j holds that minimum
+            if (v >= kInf) bi = j >= s ? s - 1 : -1;
             cur_all[(int64_t)p * 2 * cols + j] = v;
             cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
             if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
@@ -170,6 +175,7 @@ si_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t cols, i
         }
     }
     const int64_t v = bi >= 0 ? b : kInf;
+    if (v >= kInf) bi = j >= s ? s - 1 : -1;      // every candidate infeasible: the lowest i of the range holds that minimum
     cur_all[(int64_t)p * 2 * cols + j] = v;
     cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
     if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
@@ -198,18 +204,19 @@ size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S) {
     return si_layout(B, L).total;
 }
 
-hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int64_t* T, int64_t* bottleneck,
+hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* T, int64_t* bottleneck,
                                  int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                                  hipStream_t stream) {
     if (B == 0) return hipSuccess;
     const SiLayout lay = si_layout(B, L);
+    if (max_len > L) max_len = L;
     const int64_t cols = (int64_t)lay.tiles * kSiTile;
     const int64_t T_bs = (int64_t)L * ldT;
     char* ws = static_cast<char*>(workspace);
     int64_t* dp = reinterpret_cast<int64_t*>(ws + lay.dp_off);
     int64_t* pval = reinterpret_cast<int64_t*>(ws + lay.pval_off);
     int32_t* pidx = reinterpret_cast<int32_t*>(ws + lay.pidx_off);
-    hipLaunchKernelGGL(si_init_kernel, dim3((L + 256) / 256, B), dim3(256), 0, stream, L, S, ldT, T, T_bs, cols, dp,
+    hipLaunchKernelGGL(si_init_kernel, dim3((L + 256) / 256, B), dim3(256), 0, stream, L, S, max_len, ldT, T, T_bs, cols, dp,
                        bottleneck, cut);
     const dim3 grid((unsigned)(lay.tiles * lay.splits), (unsigned)B);
     const dim3 merge_grid((unsigned)lay.tiles, (unsigned)B);
@@ -217,7 +224,7 @@ hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, c
         // dp[s-1] sits in buffer (s-1) odd ? 0 : 1 of each problem
         const int64_t* prev_all = dp + (size_t)(s & 1) * cols;
         int64_t* cur_all = dp + (size_t)((s & 1) ^ 1) * cols;
-        hipLaunchKernelGGL(si_step_kernel, grid, dim3(kSiWaves * 64), 0, stream, L, S, s, lay.splits, ldT, T, T_bs,
+        hipLaunchKernelGGL(si_step_kernel, grid, dim3(kSiWaves * 64), 0, stream, L, S, s, lay.splits, max_len, ldT, T, T_bs,
                            cols, prev_all, cur_all, pval, pidx, bottleneck, cut);
         if (lay.splits > 1)
             hipLaunchKernelGGL(si_merge_kernel, merge_grid, dim3(kSiTile), 0, stream, L, S, s, lay.splits, cols,

@@ -192,3 +192,74 @@ def test_argument_errors():
     assert sd(ws=None) == -4 and sd(wsb=8) == -4
     assert rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, 8, 9) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("L,K,Kp,B,max_len", [(40, 10, 16, 2, 1), (40, 10, 16, 1, 7), (300, 64, 64, 1, 20),
+                                              (300, 64, 64, 2, 149), (300, 64, 64, 1, 151), (300, 64, 64, 1, 299),
+                                              (300, 64, 64, 1, 5000), (77, 100, 128, 1, 16), (50, 256, 256, 1, 9),
+                                              (1030, 16, 16, 1, 64)])
+def test_table_with_a_limit_on_the_stage_length(L, K, Kp, B, max_len):
+    # both row layouts of the kernel (neighbouring rows for short limits, round-robin rows for long ones), limits
+    # that end inside and at the edge of a 64-column block, and no limit in effect
+    c, R = syn.random_chain_batch(range(B), L, K, 1_000_000, 10_000_000, Kp=Kp)
+    ldT = even_ld(L, 2)
+    T = torch.full((B, L, ldT), -7, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs_banded(B, L, Kp, max_len, torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV), ldT, T)
+    torch.cuda.synchronize()
+    T = T.cpu().numpy()
+    for p in range(B):
+        want = oracle.interval_costs(c[p], R[p], ldT=ldT, nthreads=4, max_len=max_len)
+        assert np.array_equal(T[p, :, :L + 1], want[:, :L + 1]), f"problem {p}"
+    assert (T[:, :, L + 1:] == -7).all()
+
+
+@pytest.mark.parametrize("L,S,B,max_len", [(5, 5, 2, 1), (129, 16, 2, 10), (300, 33, 1, 40), (300, 7, 2, 30),
+                                           (1000, 64, 1, 100), (1000, 20, 1, 1000), (2051, 40, 1, 130)])
+def test_search_with_a_limit_on_the_stage_length(L, S, B, max_len):
+    # any table: the search must ignore what it holds for longer stages; limits so tight that some stage counts
+    # have no solution at all (S * max_len < L) are part of the cases
+    rng = np.random.default_rng(L + S + max_len)
+    ldT = even_ld(L)
+    T = rng.integers(0, 1000 if L % 2 else 6, size=(B, L, ldT)).astype(np.int64)
+    T[rng.random(T.shape) < 0.05] = INF
+    masked = T.copy()
+    i, j = np.meshgrid(np.arange(L), np.arange(ldT), indexing="ij")
+    masked[:, j - i > max_len] = INF
+    s_query = min(S, 6)
+    want = oracle.stage_interval(masked, S, s_query=s_query, nthreads=4)
+    bott = torch.full((B, S), -7, dtype=torch.int64, device=DEV)
+    cut = torch.full((B, S, L + 1), -7, dtype=torch.int32, device=DEV)
+    bounds = torch.full((B, s_query + 1), -7, dtype=torch.int32, device=DEV)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, B, L, S), dtype=torch.uint8, device=DEV)
+    rh.rh_stage_dp_interval_banded(B, L, S, max_len, ldT, torch.from_numpy(T).to(DEV), bott, cut, s_query, bounds, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(bott.cpu().numpy(), want[0])
+    assert np.array_equal(cut.cpu().numpy(), want[1])
+    assert np.array_equal(bounds.cpu().numpy(), want[2])
+
+
+def test_limited_table_and_search_at_full_size():
+    # the bench shape: 4096 operators, 64 strategies, 64 stages, no stage longer than 256 operators; the table is
+    # checked on sampled rows (each an oracle sweep of its own), the search in full on the GPU's own table
+    L, K, S, max_len = 4096, 64, 64, 256
+    c, R = syn.random_chain_batch([11], L, K, 100_000, 200_000)
+    ldT = even_ld(L)
+    d_T = torch.full((1, L, ldT), -7, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs_banded(1, L, K, max_len, torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV), ldT, d_T)
+    torch.cuda.synchronize()
+    T = d_T.cpu().numpy()
+    for i in (0, 1, 15, 16, 17, 1000, 2047, 3839, 3840, 3841, 4000, 4095):
+        j_end = min(L, i + max_len)
+        sub = oracle.interval_costs(c[0, i:j_end].copy(), R[0, i:max(j_end - 1, i)].copy())
+        assert np.array_equal(T[0, i, i + 1:j_end + 1], sub[0, 1:j_end - i + 1]), i
+        assert (T[0, i, :i + 1] == INF).all() and (T[0, i, j_end + 1:L + 1] == INF).all(), i
+    want = oracle.stage_interval(T, S, s_query=S, nthreads=8)
+    bott = torch.empty((1, S), dtype=torch.int64, device=DEV)
+    cut = torch.empty((1, S, L + 1), dtype=torch.int32, device=DEV)
+    bounds = torch.empty((1, S + 1), dtype=torch.int32, device=DEV)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, L, S), dtype=torch.uint8, device=DEV)
+    rh.rh_stage_dp_interval_banded(1, L, S, max_len, ldT, d_T, bott, cut, S, bounds, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(bott.cpu().numpy(), want[0]) and np.array_equal(cut.cpu().numpy(), want[1])
+    assert np.array_equal(bounds.cpu().numpy(), want[2])
+    assert want[0][0, S - 1] < INF and (want[0][0, :15] == INF).all()   # 15 stages of 256 cannot hold 4096 operators
