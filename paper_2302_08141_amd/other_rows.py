@@ -177,7 +177,18 @@ def _interval_rows(dev, L, S, K):
     ws = torch.empty(rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, L, S), dtype=torch.uint8, device=dev)
     t_dp = _best_ms(lambda: rh.rh_stage_dp_interval(1, L, S, ldT, T, bott, cut, S, bounds, ws))
     cells_dp = sum((L - s + 1) * (L - s + 2) // 2 for s in range(2, S + 1))
-    return {"K": K, "table_ms": t_tab, "table_cells": cells_tab, "table_cells_per_s": cells_tab / (t_tab * 1e-3),
+    # the same with no stage longer than four times the balanced length (Sec. 5.2 keeps operators near their stage)
+    max_len = 4 * L // S
+    t_tab_b = _best_ms(lambda: rh.rh_interval_costs_banded(1, L, K, max_len, c, R, ldT, T))
+    cells_tab_b = sum(min(L - 1 - i, max_len - 1) for i in range(L)) * K * K
+    t_dp_b = _best_ms(lambda: rh.rh_stage_dp_interval_banded(1, L, S, max_len, ldT, T, bott, cut, S, bounds, ws))
+    banded = {"max_len": max_len, "table_ms": t_tab_b, "table_cells": cells_tab_b,
+              "table_cells_per_s": cells_tab_b / (t_tab_b * 1e-3), "search_ms": t_dp_b,
+              "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
+    rh.rh_interval_costs(1, L, K, c, R, ldT, T)
+    rh.rh_stage_dp_interval(1, L, S, ldT, T, bott, cut, S, bounds, ws)
+    return {"K": K, "stages_of_limited_length": banded,
+            "table_ms": t_tab, "table_cells": cells_tab, "table_cells_per_s": cells_tab / (t_tab * 1e-3),
             "table_f64_lane_ops_per_s": 2 * cells_tab / (t_tab * 1e-3),
             "search_ms": t_dp, "search_cells": cells_dp, "search_cells_per_s": cells_dp / (t_dp * 1e-3),
             "search_table_read_gbps": cells_dp * 8 / (t_dp * 1e-3) / 1e9,
