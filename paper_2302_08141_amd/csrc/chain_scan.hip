@@ -1,4 +1,4 @@
-// Min-plus chain DP of ONE long chain, parallel along the chain.
+// Min-plus chain DP of a long chain, parallel along the chain.
 //
 // The forward sweep v_{i+1}[b] = c_{i+1}[b] + min_a (v_i[a] + R_i[a][b]) (Sec. 4.2 objective on the
 // linear chain of Sec. 4.3.2) is a chain of N-1 dependent steps; a single workgroup needs about
@@ -6,16 +6,20 @@
 // Min-plus products are associative, so the chain is cut into segments of SL edges:
 //   1. for every segment but the last, all at once: the matrix M_g[a][b] = cost of the best way
 //      through the segment that enters with strategy a and leaves with strategy b (one forward
-//      sweep per entering strategy, Kp sweeps sharing the segment's edge tables; strategies whose
-//      node cost is infeasible are skipped, as entering strategies and as rows of every edge table);
+//      sweep per entering strategy, all sharing the segment's edge tables);
 //   2. the vectors at the segment boundaries, v_{g+1} = v_g (x) M_g, a short sequential pass;
-//   3. the ordinary vector sweep inside every third of a segment (step 1 runs as one launch per
-//      third and keeps the matrices that reach one and two thirds of a segment, so those start
-//      vectors cost one product each), all at once as one batch: it writes arg exactly as the sequential sweep would,
-//      because the boundary vectors are the sequential sweep's own values (saturation at
-//      "infeasible" is monotone, so it commutes with the regrouping).
-// Step 1 does Kp times the arithmetic of the plain sweep, in fp64 (exact for these integers, see
-// interval_costs.hip) at two lane-operations per cell, in exchange for removing the dependent chain.
+//   3. the ordinary vector sweep inside every third of a segment, all thirds at once (step 1
+//      runs as one launch per third and keeps the matrices that reach one and two thirds of a
+//      segment, so those start vectors cost one product each): it writes arg exactly as the
+//      sequential sweep would, because the start vectors are the sequential sweep's own values
+//      (saturation at "infeasible" is monotone, so it commutes with the regrouping).
+// A strategy whose node cost is infeasible can neither be entered nor passed through: all
+// three steps work on the feasible strategies of every operator only, in rank order (rows of M_g,
+// rows and columns of the edge tables, rows of the sweep) -- on tables built from sharding specs
+// about a third of the slots are valid layouts.
+// Step 1 does (feasible strategies) times the arithmetic of the plain sweep, in fp64 (exact for
+// these integers, see interval_costs.hip) at two lane-operations per cell, in exchange for
+// removing the dependent chain.
 #include "kernels.h"
 
 namespace rh {
@@ -27,7 +31,7 @@ constexpr int kScWaves = 16;                 // waves per workgroup of the matri
 constexpr int kScRows = 2;                   // entering strategies (rows of M_g) per wave: R values are read once for both
 constexpr int kScThreads = kScWaves * 64;
 constexpr int kScBlock = kScWaves * kScRows; // rows of M_g per workgroup
-constexpr int kScSub = 3;                    // the final sweep starts at every kScSub-th part of a segment
+constexpr int kScSub = 3;                    // parts per segment: the sweep of step 3 starts at every part
 constexpr int kBdThreads = 1024;             // the boundary kernels
 constexpr int kBdWaves = 16;
 constexpr int kScPiece = 4096;               // elements of R per LDS buffer
