@@ -9,12 +9,14 @@
 // not fit in memory, and faster than streaming once many problems fill the chip.
 //
 // One workgroup per problem.  Per edge: 20 threads compute the time table
-// ([axis][other axis splits][none | gather | all-to-all | all-reduce | impossible]), Kp threads
-// the canonical producer and consumer words; the usable producer strategies (valid spec, feasible
-// v_i) and the valid consumer strategies are listed, a lane owns up to Kp/64 of the listed
-// consumer columns, the waves take the listed rows round-robin; a cell is two byte compares,
-// two nibble extractions from the producer's row of the 3x3 state matrix, two LDS table reads
-// and the min update.  Per-wave minima meet in LDS.
+// ([axis][other axis splits][none | gather | all-to-all | all-reduce | impossible]), 2 Kp threads
+// the canonical producer and consumer words; the valid producer and consumer strategies are
+// listed, a lane owns up to Kp/64 of the listed consumer columns, the waves take the listed rows
+// round-robin (a row whose v_i is infeasible is passed over); a cell is two byte compares, two
+// nibble extractions from the producer's row of the 3x3 state matrix, two LDS table reads and the
+// min update.  Per-wave minima meet in LDS.  None of the tables and lists of an edge depends on
+// the vector, so those of edge i + 1 are made (in a second set of buffers) while edge i is
+// relaxed: two workgroup barriers per edge, and the table's 64-bit divisions off the critical path.
 #include "kernels.h"
 #include "reshard_common.h"
 
@@ -54,37 +56,43 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
                    int64_t* __restrict__ vfinal, int64_t* __restrict__ total, int32_t* __restrict__ last) {
     constexpr int CPL = KP / 64;                // consumer columns per lane: ranks lane + 64*k of the valid ones
     constexpr int kThreads = W * 64;
-    static_assert(KP <= kThreads, "one thread per strategy slot");
+    static_assert(2 * KP <= kThreads, "a thread per strategy slot and side of the edge");
     __shared__ int64_t vs[KP];
-    __shared__ uint32_t prow[KP], qrow[KP];     // canonical producer / consumer words of the edge
-    __shared__ uint16_t lrows[KP], lcols[KP];   // usable producer strategies / valid consumer strategies, ascending
-    __shared__ int64_t cnx[KP];                 // node costs of the consumer operator
-    __shared__ int64_t dml[2][4];
-    __shared__ int32_t cnt[2][CPL];
-    __shared__ int64_t tab[2][2][8];            // kinds 0..4 used
+    // per-edge tables, two sets: while edge i is relaxed out of set i & 1, set (i + 1) & 1 is made ready for the next
+    __shared__ uint32_t prow[2][KP], qrow[2][KP];   // canonical producer / consumer words of the edge
+    __shared__ uint16_t lrows[2][KP], lcols[2][KP]; // valid producer / consumer strategies, ascending
+    __shared__ int64_t cnx[2][KP];                  // node costs of the consumer operator
+    __shared__ int64_t dml[2][4];                   // extents of the edge's tensor (indexed by the spec's dim field)
+    __shared__ int32_t cnt[2][2][CPL];              // [set][producer | consumer][wave]: valid strategies per 64 slots
+    __shared__ int64_t tab[2][2][2][8];             // [set][axis][other axis splits][kind], kinds 0..4 used
     __shared__ u64 pkey[W][KP];
+    __shared__ uint16_t argl[KP];                   // arg of the edge just finished, by strategy slot
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int p = blockIdx.x;
     const int mi = p % n_meshes;                // problem p is searched on mesh p mod n_meshes
-    Mesh mesh;
-    mesh.naxes = meshes.naxes[mi];
-    for (int x = 0; x < 2; ++x) {
-        mesh.lgm[x] = meshes.lgm[mi][x];
-        mesh.bw_bytes_per_us[x] = meshes.bw_bytes_per_us[mi][x];
-        mesh.alpha_ns[x] = meshes.alpha_ns[mi][x];
+    // The mesh is indexed by axis numbers computed at run time: in LDS that is an address, in registers it would
+    // send the struct to scratch memory (and every wait for a scratch access drains the loads that run ahead).
+    __shared__ Mesh mesh;
+    if (tid == 0) {
+        mesh.naxes = meshes.naxes[mi];
+        for (int x = 0; x < 2; ++x) {
+            mesh.lgm[x] = meshes.lgm[mi][x];
+            mesh.bw_bytes_per_us[x] = meshes.bw_bytes_per_us[mi][x];
+            mesh.alpha_ns[x] = meshes.alpha_ns[mi][x];
+        }
     }
     const int64_t* cp = c + (int64_t)p * c_bs;
 
     if (tid < KP) {
         const int64_t x = cp[tid];
         vs[tid] = x < kInf ? x : kInf;
+        argl[tid] = 0;
     }
-    lds_barrier();
 
-    // What edge i needs from memory is asked for during edge i-1: the spec words and node costs of slot tid, the
+    // What edge i needs from memory is asked for two edges ahead: the spec words and node costs of slot tid, the
     // tensor shape, element size and candidate counts.
     struct EdgeIn {
         uint32_t osp, isp;
@@ -94,7 +102,8 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
     auto load_edge = [&](int i) {
         EdgeIn e;
         i = i < N - 1 ? i : N - 2;                   // a load past the last edge repeats it
-        const int slot = tid < KP ? tid : 0;
+        i = i > 0 ? i : 0;
+        const int slot = tid & (KP - 1);
         e.osp = out_spec[(int64_t)i * KP + slot];
         e.isp = in_spec[(int64_t)(i + 1) * KP + slot];
         e.cnext = cp[(int64_t)(i + 1) * KP + slot];
@@ -104,58 +113,85 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
         e.eb = elem_bytes[i];
         return e;
     };
-    // the tensor shape is indexed by the spec's dim field, so it lives in LDS (two edges, alternating)
-    EdgeIn cur = load_edge(0);
-    if (tid < 4) dml[0][tid] = cur.dim;
+    // Everything about an edge that does not depend on the vector: the time table (one wave's 20 lanes; it holds
+    // the only 64-bit divisions), the canonical words of slot tid, which slots are valid layouts, how many per
+    // 64 slots.  Thread t owns strategy slot t of both operators of the edge; the masks stay in registers until
+    // the counts of all waves are visible and the ascending lists can be written (list_edge).
+    struct Prepared {
+        bool row_ok, col_ok;
+        u64 row_mask, col_mask;
+    };
+    auto prepare_edge = [&](const EdgeIn& e, int set) {
+        const int64_t* dm = dml[set];
+        if (wave == W - 1 && lane < 20) {
+            const int x = lane / 10, o = (lane / 5) & 1, kind = lane % 5;
+            tab[set][x][o][kind] = axis_time(x, o, (uint32_t)kind, mesh, dm, e.eb);
+        }
+        // the producer words by the first Kp threads, the consumer words (and node costs) by the next Kp
+        Prepared pr{false, false, 0, 0};
+        if (tid < KP) {
+            const uint32_t pw = canonical(e.osp, tid, e.k_out, dm, mesh);
+            prow[set][tid] = pw;
+            pr.row_ok = !(pw & 0x80000000u);
+        } else if (tid < 2 * KP) {
+            const uint32_t qw = canonical(e.isp, tid - KP, e.k_in, dm, mesh);
+            qrow[set][tid - KP] = qw;
+            cnx[set][tid - KP] = e.cnext;
+            pr.col_ok = !(qw & 0x80000000u);
+        }
+        pr.row_mask = __ballot(pr.row_ok);
+        pr.col_mask = __ballot(pr.col_ok);
+        if (lane == 0) {
+            if (tid < KP) cnt[set][0][wave] = __popcll(pr.row_mask);
+            else if (tid < 2 * KP) cnt[set][1][wave - CPL] = __popcll(pr.col_mask);
+        }
+        return pr;
+    };
+    auto list_edge = [&](const Prepared& pr, int set) {
+        const int which = tid < KP ? 0 : 1, w0 = tid < KP ? wave : wave - CPL;   // which list, which 64 slots of it
+        if (tid < 2 * KP) {
+            int before = 0;
+#pragma unroll
+            for (int w = 0; w < CPL; ++w) before += w < w0 ? cnt[set][which][w] : 0;
+            const u64 below = ((u64)1 << lane) - 1;
+            if (pr.row_ok) lrows[set][before + __popcll(pr.row_mask & below)] = (uint16_t)tid;
+            if (pr.col_ok) lcols[set][before + __popcll(pr.col_mask & below)] = (uint16_t)(tid - KP);
+        }
+    };
+
+    EdgeIn e1 = load_edge(0);
+    if (tid < 4) dml[0][tid] = e1.dim;
+    lds_barrier();
+    Prepared ready = prepare_edge(e1, 0);
+    e1 = load_edge(1);
+    if (tid < 4) dml[1][tid] = e1.dim;
+    lds_barrier();
+    list_edge(ready, 0);
     lds_barrier();
     for (int i = 0; i < N - 1; ++i) {
-        const EdgeIn nxt = load_edge(i + 1);
-        const int64_t* dm = dml[i & 1];
-        // per-edge tables
-        if (tid < 20) {
-            const int x = tid / 10, o = (tid / 5) & 1, kind = tid % 5;
-            tab[x][o][kind] = axis_time(x, o, (uint32_t)kind, mesh, dm, cur.eb);
-        }
-        // Thread t owns strategy slot t of both operators of the edge.  A producer strategy is worth a row only if
-        // its spec is a valid layout and v_i is feasible there; a consumer strategy is worth a column only if its
-        // spec is valid.  Both sets are listed in ascending order and only they are visited (on graphs built from
-        // specs about a third of the slots are valid, so this is a ninth of the cells).
-        bool row_ok = false, col_ok = false;
-        if (tid < KP) {
-            const uint32_t pw = canonical(cur.osp, tid, cur.k_out, dm, mesh);
-            const uint32_t qw = canonical(cur.isp, tid, cur.k_in, dm, mesh);
-            prow[tid] = pw;
-            qrow[tid] = qw;
-            cnx[tid] = cur.cnext;
-            row_ok = !(pw & 0x80000000u) && vs[tid] < kInf;
-            col_ok = !(qw & 0x80000000u);
-        }
-        const u64 row_mask = __ballot(row_ok), col_mask = __ballot(col_ok);
-        if (tid < KP && lane == 0) {
-            cnt[0][wave] = __popcll(row_mask);
-            cnt[1][wave] = __popcll(col_mask);
-        }
-        lds_barrier();
-        int n_rows = 0, n_cols = 0, rows_before = 0, cols_before = 0;
+        const int cs = i & 1, ns = cs ^ 1;           // this edge's set of tables, the next edge's
+        const EdgeIn e2 = load_edge(i + 2);
+        // arg of edge i - 1 leaves now, one store per thread whatever the thread (a store under a condition would
+        // keep the waits below from counting the loads that run ahead; threads beyond Kp repeat a slot)
+        arg[((int64_t)p * (N - 1) + (i > 0 ? i - 1 : 0)) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
+        // ---- first half: relax edge i; on the side, the tables of edge i + 1 ----
+        ready = prepare_edge(e1, ns);
+        int n_rows = 0, n_cols = 0;
 #pragma unroll
         for (int w = 0; w < CPL; ++w) {
-            rows_before += w < wave ? cnt[0][w] : 0;
-            cols_before += w < wave ? cnt[1][w] : 0;
-            n_rows += cnt[0][w];
-            n_cols += cnt[1][w];
+            n_rows += cnt[cs][0][w];
+            n_cols += cnt[cs][1][w];
         }
-        const u64 below = ((u64)1 << lane) - 1;
-        if (row_ok) lrows[rows_before + __popcll(row_mask & below)] = (uint16_t)tid;
-        if (col_ok) lcols[cols_before + __popcll(col_mask & below)] = (uint16_t)tid;
-        lds_barrier();   // tab, prow, qrow and the two lists are ready
-
-        // this lane's consumer columns: ranks lane + 64 k of the valid ones
+        // A producer strategy is worth a row only if its spec is a valid layout (listed) and v_i is feasible there
+        // (checked when its turn comes); a consumer strategy is worth a column only if its spec is valid.  On
+        // graphs built from specs about a third of the slots are valid, so this is a ninth of the cells.
+        // This lane's consumer columns: ranks lane + 64 k of the valid ones.
         const int cplc = (n_cols + 63) >> 6;           // groups of 64 columns in use (wave-uniform)
         uint32_t q0b[CPL], q1b[CPL], sh0[CPL], sh1[CPL], base1[CPL];
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
             const int rank = lane + 64 * k;
-            const uint32_t q = qrow[rank < n_cols ? lcols[rank] : 0];
+            const uint32_t q = qrow[cs][rank < n_cols ? lcols[cs][rank] : 0];
             q0b[k] = q & 0xFFu;
             q1b[k] = (q >> 8) & 0xFFu;
             sh0[k] = 4u * (q0b[k] & 3u);
@@ -163,8 +199,8 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
             base1[k] = ((q0b[k] & 3u) == 1u) ? 8u : 0u;   // axis 1 moves after axis 0 has the consumer's state
         }
         // thread t finishes the column of rank t
-        const int my_col = tid < n_cols ? lcols[tid] : 0;
-        const int64_t cn = cnx[my_col];
+        const int my_col = tid < n_cols ? lcols[cs][tid] : 0;
+        const int64_t cn = cnx[cs][my_col];
         int64_t best[CPL];
         int32_t bidx[CPL];
 #pragma unroll
@@ -173,8 +209,8 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
             bidx[k] = 0;
         }
 
-        const int64_t* tab0 = &tab[0][0][0];
-        const int64_t* tab1 = &tab[1][0][0];
+        const int64_t* tab0 = &tab[cs][0][0][0];
+        const int64_t* tab1 = &tab[cs][1][0][0];
         auto relax_row = [&](int a, uint32_t pw, int64_t va) {
             const uint32_t p0b = pw & 0xFFu, p1b = (pw >> 8) & 0xFFu;
             const uint32_t row0 = kind_row(p0b & 3u), row1 = kind_row(p1b & 3u);
@@ -192,23 +228,24 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
                 }
             }
         };
-        // The waves take the usable rows round-robin, in ascending order within a wave (so that a lane's first
+        // The waves take the listed rows round-robin, in ascending order within a wave (so that a lane's first
         // minimum is its lowest row); two rows per trip so that the second row's words are already on their way.
         for (int r = wave; r < n_rows; r += 2 * W) {
-            const int a = __builtin_amdgcn_readfirstlane((int)lrows[r]);
+            const int a = __builtin_amdgcn_readfirstlane((int)lrows[cs][r]);
             const bool two = r + W < n_rows;
-            const int b = __builtin_amdgcn_readfirstlane((int)lrows[two ? r + W : r]);
-            const uint32_t pa = prow[a], pb = prow[b];
+            const int b = __builtin_amdgcn_readfirstlane((int)lrows[cs][two ? r + W : r]);
+            const uint32_t pa = prow[cs][a], pb = prow[cs][b];
             const int64_t va = vs[a], vb = vs[b];
-            relax_row(a, __builtin_amdgcn_readfirstlane(pa), va);
-            if (two) relax_row(b, __builtin_amdgcn_readfirstlane(pb), vb);
+            if (va < kInf) relax_row(a, __builtin_amdgcn_readfirstlane(pa), va);
+            if (two && vb < kInf) relax_row(b, __builtin_amdgcn_readfirstlane(pb), vb);
         }
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
             const int64_t v = best[k] >= kInf ? kInf : best[k];
             pkey[wave][lane + 64 * k] = ((u64)v << 10) | (u64)(v >= kInf ? 0 : bidx[k]);
         }
-        lds_barrier();   // the waves' minima are in LDS; every read of v_i, tab, prow is done
+        lds_barrier();   // the waves' minima and the next edge's counts are in LDS; every read of v_i is done
+        // ---- second half: v_{i+1} and arg; the lists of edge i + 1 ----
         if (tid < n_cols) {
             u64 mk = pkey[0][tid];
 #pragma unroll
@@ -221,16 +258,18 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
             int64_t nv = cn + (dead ? kInf : b);
             nv = nv < kInf ? nv : kInf;
             vs[my_col] = nv;
-            arg[((int64_t)p * (N - 1) + i) * KP + my_col] = dead ? (uint16_t)0 : (uint16_t)(mk & 1023u);
+            argl[my_col] = dead ? (uint16_t)0 : (uint16_t)(mk & 1023u);
         }
-        if (tid < KP && !col_ok) {                     // a strategy without a valid consumer spec
+        if (tid < KP && (qrow[cs][tid] & 0x80000000u)) {   // a strategy without a valid consumer spec
             vs[tid] = kInf;
-            arg[((int64_t)p * (N - 1) + i) * KP + tid] = 0;
+            argl[tid] = 0;
         }
-        if (tid < 4) dml[(i + 1) & 1][tid] = nxt.dim;
-        lds_barrier();   // v_{i+1} visible
-        cur = nxt;
+        list_edge(ready, ns);
+        if (tid < 4) dml[cs][tid] = e2.dim;            // set cs serves edge i + 2 next
+        lds_barrier();   // v_{i+1} and the lists of edge i + 1 visible
+        e1 = e2;
     }
+    if (N > 1 && tid < KP) arg[((int64_t)p * (N - 1) + (N - 2)) * KP + tid] = argl[tid];
 
     constexpr int MP = 1;
 #pragma unroll
