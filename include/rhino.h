@@ -147,9 +147,9 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
  *           - given rh_workspace_size(RH_WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp) bytes instead
  *             (B <= 32, N >= 128, Kp 64, 128 or 256; more bytes than the above), all problems
  *             take the segmented route (their matrices one problem after the other).  Worth
- *             it when most strategies are infeasible: then a problem takes a thirtieth of what the eight
+ *             it when most strategies are infeasible: then a problem takes a fifteenth of what the eight
  *             workgroups need for up to 32 problems together; with every strategy feasible
- *             it is the better choice only for B <= 2.
+ *             a problem takes two thirds of that.
  *           With NULL, 0 the call needs no workspace.
  * Base pointers and batch strides must keep every row 16-byte aligned.
  */

@@ -56,7 +56,9 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
     constexpr int RW = KP / kGang;           // rows of every edge table this workgroup reduces
     constexpr int RPW = RW / kW;             // rows per wave per edge
     static_assert(KP >= 128 && RPW >= 1 && RPW * kW * kGang == KP, "tile does not fit the gang");
-    constexpr int EA = kEdgesAhead;
+    // at Kp = 256 one edge ahead is 64 KiB in flight per workgroup, plenty for a step of several microseconds, and
+    // more edges would not fit the registers
+    constexpr int EA = KP >= 256 ? 1 : kEdgesAhead;
 
     __shared__ int64_t vs[KP];
     __shared__ u64 pkey[kW][KP];
@@ -160,8 +162,8 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
                 if (merger) {
                     const u64 tag = (u64)((i >> 1) & 1) << 63;
                     u64 m0 = pkey[0][2 * tid], m1 = pkey[0][2 * tid + 1];
-#pragma unroll
-                    for (int w = 1; w < kW; ++w) {
+#pragma unroll 4
+                    for (int w = 1; w < kW; ++w) {   // (a few at a time: the rows in flight hold most registers)
                         const u64 o0 = pkey[w][2 * tid], o1 = pkey[w][2 * tid + 1];
                         m0 = o0 < m0 ? o0 : m0;
                         m1 = o1 < m1 ? o1 : m1;
