@@ -171,10 +171,13 @@ template <int KP>
 __device__ __forceinline__ void rank_operators(const int64_t* __restrict__ c0, int n_ops, uint8_t (*lidx)[KP],
                                                int32_t* nl, int wave, int lane) {
     for (int o = wave; o < n_ops; o += kScWaves) {
+        int64_t x[KP / 64];                       // all loads of the operator first: one trip to memory, not KP / 64
+#pragma unroll
+        for (int k = 0; k < KP / 64; ++k) x[k] = c0[(int64_t)o * KP + lane + 64 * k];
         int base = 0, last_live = 0;
 #pragma unroll
         for (int k = 0; k < KP / 64; ++k) {
-            const bool ok = c0[(int64_t)o * KP + lane + 64 * k] < kInf;
+            const bool ok = x[k] < kInf;
             const uint64_t m = __ballot(ok);
             if (ok) lidx[o][base + __popcll(m & ((1ull << lane) - 1))] = (uint8_t)(lane + 64 * k);
             if (m != 0) last_live = 64 * k + 63 - __builtin_clzll(m);
