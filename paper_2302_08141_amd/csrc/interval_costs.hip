@@ -15,22 +15,19 @@
 // Mapping: a lane owns Kp/64 columns b; a wave keeps one row (start) in registers and
 // broadcasts V[row][a] with two v_readlane per a, so the broadcast operand travels in scalar
 // registers.  A workgroup (16 waves, 16 rows) stages R_l through LDS in 32 KiB pieces, converted
-// to fp64 on the way in, double buffered.  Without a limit on the stage length the rows are dealt to
-// the workgroups round-robin (row i to workgroup i mod NW): every workgroup has rows of all ages, so
-// the triangular work is balanced and all workgroups walk the edges in the same order, which lets
-// one trip to HBM serve the chip.  With a limit of at most half the chain (no stage longer than
-// max_len operators: the sweep of row i stops after max_len operators and the rest of the row is
-// infeasible) a workgroup takes 16 neighbouring rows instead and walks only the max_len + 15 edges
-// they need, all its waves busy at the same time.
+// to fp64 on the way in, double buffered.  A workgroup takes a block of neighbouring rows and walks the
+// edges they need, so that all its waves are busy together.  With a limit of at most half the chain
+// (no stage longer than max_len operators: the sweep of row i stops after max_len operators and the
+// rest of the row is infeasible) every block of 16 rows walks max_len + 15 edges: equal work, one
+// block per workgroup of 16 waves.  Without such a limit the block that starts at operator i walks
+// L - i edges, a triangle: then blocks have 8 rows, a workgroup of 8 waves takes block b and
+// afterwards block (last - b), and every workgroup walks L + 8 edges.
 #include "kernels.h"
 
 namespace rh {
 namespace {
 
-constexpr int kIcThreads = 1024;
-constexpr int kIcWaves = 16;
 constexpr int kIcSlots = 1;                  // rows per wave
-constexpr int kIcRows = kIcWaves * kIcSlots; // rows per workgroup
 constexpr int kPiece = 4096;                 // elements of R per LDS buffer
 constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
 
@@ -83,7 +80,6 @@ struct Shape {
     static constexpr int CH = KP >= 64 ? kPiece / KP : KP;              // rows a of R_l per piece
     static constexpr int NCH = KP / CH;                                 // pieces per edge
     static constexpr int ELEMS = CH * KP;                               // elements per piece
-    static constexpr int EPT = ELEMS / kIcThreads > 0 ? ELEMS / kIcThreads : 1;   // per thread
 };
 
 // acc[q][k] = min(acc[q][k], V[q][a] + R[a][col + 64 k]) for the CH rows a of one piece
@@ -153,28 +149,36 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
     }
 }
 
-template <int KP>
-__global__ void __launch_bounds__(kIcThreads)
-interval_costs_kernel(int32_t L, int32_t max_len, int32_t wg_step, int32_t wave_step,
+// WAVES waves = WAVES rows per block; the workgroup takes block blockIdx.x and, if PASSES == 2, block
+// n_blocks - 1 - blockIdx.x after it.
+template <int KP, int WAVES, int PASSES>
+__global__ void __launch_bounds__(WAVES * 64)
+interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
                       const int64_t* __restrict__ c, int64_t c_bs, const int64_t* __restrict__ R, int64_t R_bs,
                       int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
     using G = Shape<KP>;
+    constexpr int kThreads = WAVES * 64;
+    constexpr int EPT = G::ELEMS / kThreads > 0 ? G::ELEMS / kThreads : 1;   // elements of a piece per thread
     extern __shared__ double lds[];               // two pieces of kPiece doubles
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    const int w = blockIdx.x;
     c += (int64_t)blockIdx.y * c_bs;
     R += (int64_t)blockIdx.y * R_bs;
     T += (int64_t)blockIdx.y * T_bs;
     const bool live_lane = lane < KP;             // KP < 64: the upper lanes carry infeasible columns
     const int col = live_lane ? lane : 0;
 
-    // rows of this wave, ascending: slot q holds start w wg_step + wave_step (kIcWaves q + wave)
-    // (round-robin: wg_step 1, wave_step = number of workgroups; neighbouring rows: wg_step 16, wave_step 1)
+#pragma unroll 1
+  for (int pass = 0; pass < PASSES; ++pass) {
+    const int block = pass == 0 ? (int)blockIdx.x : n_blocks - 1 - (int)blockIdx.x;
+    if (pass > 0 && block <= (int)blockIdx.x) break;      // an odd number of blocks: the middle one has no partner
+    lds_barrier();                                // the pass before has read its last piece
+
+    // rows of this wave: slot q holds start block * WAVES + wave (kIcSlots is 1)
     int row[kIcSlots];
 #pragma unroll
-    for (int q = 0; q < kIcSlots; ++q) row[q] = w * wg_step + wave_step * (kIcWaves * q + wave);
+    for (int q = 0; q < kIcSlots; ++q) row[q] = block * WAVES + wave;
 
     // entries at and left of the diagonal, and those of stages longer than max_len operators
 #pragma unroll
@@ -184,23 +188,22 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t wg_step, int32_t wave_
                 if (j <= row[q] || j - row[q] > max_len) T[(int64_t)row[q] * ldT + j] = kInf;
     }
 
-    const int l0 = w * wg_step;                   // the first row of this workgroup starts at operator l0
-    // the last operator any row of this workgroup reaches: its highest row, max_len operators on, or the chain's end
-    int row_hi = l0 + wave_step * (kIcRows - 1);
-    while (row_hi >= L) row_hi -= wave_step;
+    const int l0 = block * WAVES;                 // the first row of this block starts at operator l0
+    // the last operator any row of this block reaches: its highest row, max_len operators on, or the chain's end
+    const int row_hi = l0 + WAVES - 1 < L - 1 ? l0 + WAVES - 1 : L - 1;
     const int l_last = row_hi + max_len - 1 < L - 1 ? row_hi + max_len - 1 : L - 1;
     const int n_edges = l_last - l0;              // edges l0 .. l_last - 1
     const int n_pieces = n_edges * G::NCH;
 
     // piece g = (edge l0 + g / NCH, rows a of piece g % NCH); the pieces of one edge are contiguous in R
-    int64_t pre[G::EPT];
+    int64_t pre[EPT];
     auto fetch = [&](int g) {
         const int64_t* src = R + ((int64_t)l0 * KP * KP + (int64_t)g * G::ELEMS);
-        if constexpr (G::EPT >= 2) {
+        if constexpr (EPT >= 2) {
             typedef long long ll2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-            for (int e = 0; e < G::EPT / 2; ++e) {
-                const ll2 v = *reinterpret_cast<const ll2*>(src + 2 * (e * kIcThreads + tid));
+            for (int e = 0; e < EPT / 2; ++e) {
+                const ll2 v = *reinterpret_cast<const ll2*>(src + 2 * (e * kThreads + tid));
                 pre[2 * e] = v.x;
                 pre[2 * e + 1] = v.y;
             }
@@ -210,10 +213,10 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t wg_step, int32_t wave_
     };
     auto stash = [&](int g) {
         double* dst = lds + (g & 1) * kPiece;
-        if constexpr (G::EPT >= 2) {
+        if constexpr (EPT >= 2) {
 #pragma unroll
-            for (int e = 0; e < G::EPT / 2; ++e) {
-                const int at = 2 * (e * kIcThreads + tid);
+            for (int e = 0; e < EPT / 2; ++e) {
+                const int at = 2 * (e * kThreads + tid);
                 dst[at] = to_f64(pre[2 * e]);
                 dst[at + 1] = to_f64(pre[2 * e + 1]);
             }
@@ -320,6 +323,7 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t wg_step, int32_t wave_
             cC[k] = cD[k];
         }
     }
+  }
 }
 
 }  // namespace
@@ -329,28 +333,36 @@ hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_l
                                  hipStream_t stream) {
     if (B == 0) return hipSuccess;
     if (max_len > L) max_len = L;
-    const int NW = (L + kIcRows - 1) / kIcRows;
-    // short stages only: neighbouring rows per workgroup (each walks max_len + 15 edges); else round-robin rows
-    const bool neighbours = max_len <= L / 2;
-    const int wg_step = neighbours ? kIcRows : 1, wave_step = neighbours ? 1 : NW;
+    // short stages only: blocks of 16 rows, equal work, one per workgroup; else blocks of 8 rows, a long one and a
+    // short one per workgroup
+    const bool equal_blocks = max_len <= L / 2;
     const size_t lds = 2 * kPiece * sizeof(double);
-    const dim3 grid((unsigned)NW, (unsigned)B);
-#define RH_IC(KP)                                                                                                  \
+#define RH_IC(KP, WAVES, PASSES)                                                                                   \
     do {                                                                                                           \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(interval_costs_kernel<KP>),               \
+        const int n_blocks = (L + (WAVES)-1) / (WAVES);                                                            \
+        const dim3 grid((unsigned)((n_blocks + (PASSES)-1) / (PASSES)), (unsigned)B);                              \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(interval_costs_kernel<KP, WAVES, PASSES>),        \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                  \
         if (e != hipSuccess) return e;                                                                             \
-        hipLaunchKernelGGL((interval_costs_kernel<KP>), grid, dim3(kIcThreads), lds, stream, L, max_len, wg_step,  \
-                           wave_step, c, c_bs, R, R_bs, ldT, T, T_bs);                                             \
+        hipLaunchKernelGGL((interval_costs_kernel<KP, WAVES, PASSES>), grid, dim3((WAVES)*64), lds, stream, L, max_len,    \
+                           n_blocks, c, c_bs, R, R_bs, ldT, T, T_bs);                                              \
+    } while (0)
+#define RH_IC_KP(KP)                                                                                               \
+    do {                                                                                                           \
+        if (equal_blocks)                                                                                          \
+            RH_IC(KP, 16, 1);                                                                                      \
+        else                                                                                                       \
+            RH_IC(KP, 8, 2);                                                                                       \
     } while (0)
     switch (Kp) {
-        case 16: RH_IC(16); break;
-        case 32: RH_IC(32); break;
-        case 64: RH_IC(64); break;
-        case 128: RH_IC(128); break;
-        case 256: RH_IC(256); break;
+        case 16: RH_IC_KP(16); break;
+        case 32: RH_IC_KP(32); break;
+        case 64: RH_IC_KP(64); break;
+        case 128: RH_IC_KP(128); break;
+        case 256: RH_IC_KP(256); break;
         default: return hipErrorInvalidValue;
     }
+#undef RH_IC_KP
 #undef RH_IC
     return hipGetLastError();
 }
