@@ -105,6 +105,9 @@ int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, c
     rh::Mesh ms[64];
     for (int p = 0; p < n_meshes; ++p)
         if (const int rc = convert_mesh(meshes + p, ms + p)) return rc;
+    if (N == 1)   // no edge, nothing to compute from specs (their pointers may be NULL): v_0 = c_0 by the plain kernel
+        return from_hip(rh::launch_chain(B, 1, Kp, c, c_batch_stride, nullptr, 0, nullptr, vfinal, total, last,
+                                         static_cast<hipStream_t>(stream)));
     return from_hip(rh::launch_chain_fused(B, N, Kp, n_meshes, ms, c, c_batch_stride, K, out_spec, in_spec, dims,
                                            elem_bytes, arg, vfinal, total, last,
                                            static_cast<hipStream_t>(stream)));

@@ -114,3 +114,21 @@ def test_argument_errors():
     assert call(Kp=32) == -3 and call(Kp=512) == -3 and call(nm=65) == -2 and call(nm=0) == -2 and call(N=0) == -2
     assert call(m=bad) == -2 and call(m=None) == -1 and call(B=0) == 0
     torch.cuda.synchronize()
+
+
+def test_single_operator_needs_no_specs():
+    # one operator, no edge: v_0 = c_0, and none of the spec arrays is looked at (they may be missing)
+    rng = np.random.default_rng(5)
+    B, Kp = 3, 64
+    c = rng.integers(0, 1000, size=(B, 1, Kp)).astype(np.int64)
+    c[1, 0, :] = INF
+    c[2, 0, :7] = INF
+    vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+    total = torch.zeros(B, dtype=torch.int64, device=DEV)
+    last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain_specs(B, 1, Kp, [rh.Mesh.make((8, 8), (12_500, 150_000), (0, 0))], dev(c), Kp, None, None, None,
+                              None, None, None, vfinal, total, last)
+    torch.cuda.synchronize()
+    _, o_vf, o_total, o_last = oracle.chain(c, np.zeros((B, 0, Kp, Kp), dtype=np.int64))
+    assert np.array_equal(total.cpu().numpy(), o_total) and np.array_equal(last.cpu().numpy(), o_last)
+    assert np.array_equal(vfinal.cpu().numpy(), o_vf)
