@@ -268,6 +268,39 @@ def test_several_chains_through_the_segmented_route():
         assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_segmented_chain_on_random_shapes_and_feasible_sets(seed):
+    # shapes, batch sizes and feasibility patterns drawn at random: every operator gets its own share of feasible
+    # strategies (now and then a single one, now and then all), some pairs cannot be converted, ties are common
+    rng = np.random.default_rng(1000 + seed)
+    Kp = int(rng.choice([64, 128, 256]))
+    N = int(rng.integers(128, 420))
+    B = int(rng.integers(1, 4))
+    c = rng.integers(0, 40, size=(B, N, Kp)).astype(np.int64)
+    R = rng.integers(0, 40, size=(B, N - 1, Kp, Kp)).astype(np.int64)
+    for p in range(B):
+        for i in range(N):
+            share = rng.choice([1.0 / Kp, 0.1, 0.3, 0.6, 1.0], p=[0.05, 0.2, 0.4, 0.25, 0.1])
+            keep = rng.random(Kp) < share
+            keep[int(rng.integers(0, Kp))] = True
+            c[p, i, ~keep] = INF
+    R[rng.random(size=R.shape) < 0.02] = INF
+    o_arg, o_vf, o_total, o_last = oracle.chain(c, R, nthreads=8)
+    dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp)
+    assert need > 0
+    ws = torch.full((need,), 0x3C, dtype=torch.uint8, device=DEV)
+    arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+    vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
+    total = torch.zeros(B, dtype=torch.int64, device=DEV)
+    last = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(B, N, Kp, dc, N * Kp, dR, (N - 1) * Kp * Kp, arg, vfinal, total, last, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(total.cpu().numpy(), o_total) and np.array_equal(last.cpu().numpy(), o_last)
+    assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+
+
 def test_long_chain_that_dies_in_the_middle():
     # nothing is feasible from one operator on: every later segment starts from an all-infeasible vector
     Kp, N = 64, 700
