@@ -86,6 +86,23 @@ def _fused_rows(g, dev):
                                                        total, last), reps=2)
         cells = B * (N - 1) * Kp * Kp
         out[f"B{B}"] = {"ms": t, "cells_per_s": cells / (t * 1e-3), "tables_not_stored_gb": cells * 8 / 1e9}
+    # the same 11 mesh shapes by the other route: build every mesh's tables, then the segmented chains
+    B = len(shapes)
+    meshes = [rh.Mesh.make(shapes[(p + B // 2) % B], g["bw_bytes_per_us"], g["alpha_ns"]) for p in range(B)]
+    c = to(g["c"][None]).repeat(B, 1, 1).contiguous()
+    R = torch.empty((B, N - 1, Kp, Kp), dtype=torch.int64, device=dev)
+    arg = torch.empty((B, N - 1, Kp), dtype=torch.int16, device=dev)
+    total = torch.empty(B, dtype=torch.int64, device=dev)
+    last = torch.empty(B, dtype=torch.int32, device=dev)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp), dtype=torch.uint8, device=dev)
+
+    def with_tables():
+        for p in range(B):
+            rh.rh_build_reshard(meshes[p], N - 1, Kp, K, osp, isp, dims, eb, R[p])
+        rh.rh_minplus_chain(B, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, None, total, last, ws)
+
+    out["B11_tables_then_segmented_chains_ms"] = _best_ms(with_tables, reps=2)
+    out["B11_totals_ns"] = [int(x) for x in total.tolist()]
     return out
 
 
