@@ -139,8 +139,9 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
  *             Same outputs bit for bit; 8192 operators x 256 take a quarter of the time when
  *             every strategy is feasible and a fortieth on tables from sharding specs, where a
  *             third of the slots are valid layouts (infeasible strategies are skipped);
- *           - otherwise a few (B <= 32) long (N >= 64) chains of wide tables (Kp 128 or 256)
- *             are spread over eight workgroups each, which meet once per edge through the
+ *           - otherwise a few long (N >= 64) chains of wide tables (Kp 128 or 256) are spread
+ *             over eight workgroups each (B <= 32; four each for B <= 64), which meet once per
+ *             edge through the
  *             workspace.  That meeting is a bounded wait: if a workgroup ever gives up (never
  *             seen; it needs the eight workgroups of a problem resident together), the
  *             problem returns total = -1;

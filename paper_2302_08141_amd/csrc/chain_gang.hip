@@ -1,4 +1,5 @@
-// Min-plus chain DP for a handful of problems: eight workgroups (a gang) share one problem.
+// Min-plus chain DP for a handful of problems: eight workgroups (a gang; four when there are more
+// than 32 problems) share one problem.
 //
 // A single workgroup cannot pull more than about 55 GB/s through its CU, so one long chain
 // (the search over one model graph, Sec. 4.3.2) is latency-bound there.  Here every workgroup
@@ -13,7 +14,7 @@
 // until all show the tag of the current edge.  Two key buffers alternate by edge parity: a
 // workgroup can publish edge i+2 into the slots of edge i only after it has read every
 // workgroup's keys of edge i+1, which those publish only after they have read edge i.  The
-// gang must be resident at once (the launcher only uses this kernel when B * 8 <= 256 CUs);
+// gang must be resident at once (the launcher sizes the gangs so that all of them fit the 256 CUs);
 // the poll is bounded all the same, and a problem whose gang gave up reports total = -1.
 #include "kernels.h"
 
@@ -23,7 +24,7 @@ namespace {
 typedef long long ll2 __attribute__((ext_vector_type(2)));
 typedef unsigned long long u64;
 
-constexpr int kGang = 8;                 // workgroups per problem
+constexpr int kMaxGang = 8;              // workgroups per problem: 8 or 4
 constexpr int kW = 16;                   // waves per workgroup
 constexpr int kEdgesAhead = 4;           // edges whose rows are in flight per wave
 constexpr uint32_t kSpinLimit = 1u << 22;
@@ -45,7 +46,7 @@ __global__ void __launch_bounds__(256) gang_clear_kernel(uint32_t* failed, int32
     if (t < n_words) xbuf[t] = ~0ull;
 }
 
-template <int KP>
+template <int KP, int kGang>
 __global__ void __launch_bounds__(kW * 64)
 chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const int64_t* __restrict__ R,
                   int64_t R_bs, uint16_t* __restrict__ arg, int64_t* __restrict__ vfinal,
@@ -56,9 +57,14 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
     constexpr int RW = KP / kGang;           // rows of every edge table this workgroup reduces
     constexpr int RPW = RW / kW;             // rows per wave per edge
     static_assert(KP >= 128 && RPW >= 1 && RPW * kW * kGang == KP, "tile does not fit the gang");
-    // at Kp = 256 one edge ahead is 64 KiB in flight per workgroup, plenty for a step of several microseconds, and
-    // more edges would not fit the registers
-    constexpr int EA = KP >= 256 ? 1 : kEdgesAhead;
+    // the rows in flight must fit the registers (more than 32 live there, and every wait for a scratch access
+    // drains the loads that run ahead): at most 8 sixteen-byte words per lane, 4 in a gang of eight, whose exchange
+    // holds more registers.  One edge ahead is already 64 KiB or more in flight per workgroup, plenty for a step of
+    // several microseconds.
+    constexpr int kEdgeWords = (KP / kGang / kW) * (KP / 128);      // words per lane and edge
+    constexpr int kBudget = kGang == 8 ? 4 : 8;
+    constexpr int EA = kBudget / kEdgeWords >= kEdgesAhead ? kEdgesAhead : (kBudget / kEdgeWords >= 1 ? kBudget / kEdgeWords : 1);
+    static_assert(kEdgeWords <= kBudget, "an edge's rows do not fit the registers of this gang size");
 
     __shared__ int64_t vs[KP];
     __shared__ u64 pkey[kW][KP];
@@ -244,28 +250,44 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
 
 }  // namespace
 
+// Workgroups per problem: as many as keep all gangs resident together (one workgroup per compute unit), four at
+// least (two do not beat a workgroup on its own: measured at Kp = 128; at Kp = 256 their rows would not fit the
+// registers).
+static int gang_size(int32_t B, int32_t Kp) {
+    (void)Kp;
+    for (int g = kMaxGang; g >= 4; g /= 2)
+        if (B * g <= 256) return g;
+    return 0;
+}
+
 size_t gang_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
     // worth it only for long chains of wide tables, and safe only while every gang is resident
-    if (B < 1 || B * kGang > 256 || N < 64 || (Kp != 128 && Kp != 256)) return 0;
-    return (size_t)B * 2 * kGang * Kp * sizeof(u64) + (((size_t)B * 4 + 255) & ~(size_t)255);
+    if (B < 1 || N < 64 || (Kp != 128 && Kp != 256)) return 0;
+    const int g = gang_size(B, Kp);
+    if (g == 0) return 0;
+    return (size_t)B * 2 * g * Kp * sizeof(u64) + (((size_t)B * 4 + 255) & ~(size_t)255);
 }
 
 hipError_t launch_chain_gang(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs,
                              const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
                              int64_t* total, int32_t* last, void* workspace, hipStream_t stream) {
+    const int g = gang_size(B, Kp);
+    if (g == 0) return hipErrorInvalidValue;
     char* wsb = static_cast<char*>(workspace);
     uint32_t* counters = reinterpret_cast<uint32_t*>(wsb);   // one failure flag per problem
     u64* xbuf = reinterpret_cast<u64*>(wsb + (((size_t)B * 4 + 255) & ~(size_t)255));
-    const int64_t n_words = (int64_t)B * 2 * kGang * Kp;
+    const int64_t n_words = (int64_t)B * 2 * g * Kp;
     hipLaunchKernelGGL(gang_clear_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, stream, counters, B,
                        xbuf, n_words);
-    const dim3 grid((unsigned)(B * kGang));
-    if (Kp == 128)
-        hipLaunchKernelGGL(chain_gang_kernel<128>, grid, dim3(kW * 64), 0, stream, N, c, c_bs, R, R_bs, arg, vfinal,
-                           total, last, xbuf, counters);
-    else
-        hipLaunchKernelGGL(chain_gang_kernel<256>, grid, dim3(kW * 64), 0, stream, N, c, c_bs, R, R_bs, arg, vfinal,
-                           total, last, xbuf, counters);
+    const dim3 grid((unsigned)(B * g));
+#define RH_GANG(KP, G)                                                                                             \
+    hipLaunchKernelGGL((chain_gang_kernel<KP, G>), grid, dim3(kW * 64), 0, stream, N, c, c_bs, R, R_bs, arg, vfinal, \
+                       total, last, xbuf, counters)
+    if (Kp == 128 && g == 8) RH_GANG(128, 8);
+    else if (Kp == 128) RH_GANG(128, 4);
+    else if (g == 8) RH_GANG(256, 8);
+    else RH_GANG(256, 4);
+#undef RH_GANG
     return hipGetLastError();
 }
 

@@ -86,9 +86,11 @@ def test_longer_chains(Kp, N, B):
     check(c, R)
 
 
-@pytest.mark.parametrize("Kp,N,B", [(256, 64, 1), (256, 131, 3), (128, 64, 2), (128, 257, 32), (256, 70, 32)])
+@pytest.mark.parametrize("Kp,N,B", [(256, 64, 1), (256, 131, 3), (128, 64, 2), (128, 257, 32), (256, 70, 32),
+                                    (256, 70, 33), (256, 64, 40), (128, 80, 50), (128, 64, 64)])
 def test_few_long_chains_spread_over_several_workgroups(Kp, N, B):
-    # with a workspace, few long chains of wide tables run eight workgroups per problem
+    # with a workspace, few long chains of wide tables run eight workgroups per problem, four when there are more
+    # than 32 problems
     need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp)
     assert need > 0
     rng = np.random.default_rng(B * 1000 + N)
@@ -119,7 +121,8 @@ def test_few_long_chains_spread_over_several_workgroups(Kp, N, B):
         assert np.array_equal(last.cpu().numpy(), o_last)
         assert np.array_equal(vfinal.cpu().numpy(), o_vf)
         assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
-    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 33, N, Kp) == 0   # too many problems to keep every gang resident
+    # too many problems to keep every gang resident
+    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 65, N, Kp) == 0
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, 63, Kp) == 0 and rh.rh_workspace_size(0, B, N, 64) == 0
 
 
