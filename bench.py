@@ -20,6 +20,7 @@ Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import gc
 import hashlib
 import json
 import os
@@ -212,7 +213,9 @@ def main():
         out["cpu_baseline"] = cpu_baseline(c, R, B, N, K)
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
 
-    del c, R, arg, plan
+    # the other rows need room of their own (one of them holds the tables of 11 meshes): every view of R goes too
+    del c, R, arg, plan, probe, copy_src, fn
+    gc.collect()
     torch.cuda.empty_cache()
     if not args.no_other_rows:
         from paper_2302_08141_amd import other_rows
