@@ -84,11 +84,25 @@ def _owned(spec_axes, dims, mesh, dev):
     for x, (state, d, stride) in enumerate(spec_axes):
         if state != sp.SPLIT:
             continue
-        sel = np.array([oracle.owner(u, stride, mesh[x]) == dev[x] for u in range(dims[d])])
+        # Sec. 4.1: blocks of `stride` consecutive units are dealt to the shards in turn (written out here, not
+        # taken from the oracle; test_owner_rule_is_the_stride_definition ties the two together)
+        sel = (np.arange(dims[d]) // stride) % mesh[x] == dev[x]
         shape = [1] * len(dims)
         shape[d] = dims[d]
         own &= sel.reshape(shape)
     return own
+
+
+def test_owner_rule_is_the_stride_definition():
+    for extent, m in ((8, 2), (8, 4), (24, 4), (64, 8)):
+        stride = extent // m
+        while stride >= 1 and extent % (stride * m) == 0:
+            blocks = [oracle.owner(u, stride, m) for u in range(extent)]
+            assert blocks == [(u // stride) % m for u in range(extent)]
+            # consecutive units of a block share a device; the next block goes to the next device
+            assert all(blocks[u] == blocks[u - 1] for u in range(1, extent) if u % stride)
+            assert all(blocks[u] == (blocks[u - 1] + 1) % m for u in range(stride, extent, stride))
+            stride //= 2
 
 
 def test_element_level_ownership_on_a_tiny_tensor():
@@ -109,7 +123,7 @@ def test_element_level_ownership_on_a_tiny_tensor():
             res.append((state, d, stride))
         return res
 
-    checked = 0
+    checked = nested = 0
     for a, b in itertools.product(range(K), repeat=2):
         p, q = axes_of(specs[a]), axes_of(specs[b])
         same_dim = lambda s: s[0][0] == sp.SPLIT and s[1][0] == sp.SPLIT and s[0][1] == s[1][1]
@@ -119,8 +133,10 @@ def test_element_level_ownership_on_a_tiny_tensor():
         if any(s[0] == sp.PARTIAL for s in p + q):
             continue                                        # partial sums are not an ownership question
         mid = [q[0], p[1]]                                  # axis 0 converted first
-        if same_dim(mid):
-            continue                                        # the intermediate nests both axes on one dim
+        # when producer and consumer swap the dims of the two axes, `mid` splits ONE dim on both axes: a device then
+        # holds the units that both per-axis owner rules give it (what `_owned` computes); that layout can be
+        # uneven over the devices, and the cost is the exact per-device average like everywhere else
+        nested += same_dim(mid)
         per_dev = []
         for dev in itertools.product(range(mesh[0]), range(mesh[1])):
             o_p, o_m, o_q = (_owned(s, dims, mesh, dev) for s in (p, mid, q))
@@ -129,7 +145,37 @@ def test_element_level_ownership_on_a_tiny_tensor():
         assert sum(per_dev) % len(per_dev) == 0
         assert R[0, a, b] == sum(per_dev) // len(per_dev), (sp.unpack(specs[a]), sp.unpack(specs[b]))
         checked += 1
-    assert checked > 1000
+    assert checked > 1000 and nested >= 24
+
+
+def test_swapped_dims_go_through_a_nested_intermediate(golden_dir):
+    """Producer splits dim 0 on axis 0 and dim 1 on axis 1, the consumer the other way round.  With axis 0 converted
+    first (Sec. 4: sharding is applied per mesh axis) the layout in between has BOTH axes on dim 1: device (k0, k1)
+    holds the units u of dim 1 with owner(u, stride_q0, m0) == k0 and owner(u, stride_p1, m1) == k1.  The bytes every
+    device receives in the two steps are counted element by element and averaged; the hand-worked figures of the
+    fixture (local*(m-1)/m^2 per step) must come out, although the devices' shares differ."""
+    row = [r for r in _rows(os.path.join(golden_dir, "reshard_swapped_dims.txt"))][0]
+    n, m0, m1, eb, step0, step1 = map(int, row)
+    dims, mesh = (n, n, n), (m0, m1)
+    p = [(sp.SPLIT, 0, n // m0), (sp.SPLIT, 1, n // m1)]
+    q = [(sp.SPLIT, 1, n // m0), (sp.SPLIT, 0, n // m1)]
+    mid = [q[0], p[1]]
+    got0, got1 = [], []
+    for dev in itertools.product(range(m0), range(m1)):
+        o_p, o_m, o_q = (_owned(s, dims, mesh, dev) for s in (p, mid, q))
+        got0.append(int((o_m & ~o_p).sum()) * eb)
+        got1.append(int((o_q & ~o_m).sum()) * eb)
+    # the intermediate is a partition of the tensor, but not an even one
+    held = [int(_owned(mid, dims, mesh, dev).sum()) for dev in itertools.product(range(m0), range(m1))]
+    assert sum(held) == n ** 3 and min(held) == 0 and max(held) == 2 * n ** 3 // (m0 * m1)
+    assert sum(got0) == step0 * m0 * m1 and sum(got1) == step1 * m0 * m1
+    R = oracle.build_reshard(mesh, (1000, 1000), (0, 0), np.array([1, 1], np.int32),
+                             np.array([[sp.word(sp.S_(0), sp.S_(1))], [0]], np.uint32),
+                             np.array([[0], [sp.word(sp.S_(1), sp.S_(0))]], np.uint32),
+                             np.array([[n, n, n, 1]], np.int64), np.array([eb], np.int32))
+    assert R[0, 0, 0] == step0 + step1                     # 1 byte per ns
+    assert oracle.axis_bytes(sp.S_(0), sp.S_(1), dims, m0, n ** 3 * eb // m1) == step0
+    assert oracle.axis_bytes(sp.S_(1), sp.S_(0), dims, m1, n ** 3 * eb // m0) == step1
 
 
 def test_invariants_of_the_paper():
