@@ -73,28 +73,46 @@ def host_threads() -> int:
     return max(n, 1)
 
 
-def cpu_baseline(c, R, B, N, K, sample_problems=2048, batch=64):
+def cpu_baseline(c, R, B, N, K, gpu_total, gpu_last, gpu_plan, sample_problems=4096, batch=64, single=256):
     """The oracle as it stands, on the host cores, on the first `sample_problems` problems of the batch
-    (copied back from HBM in slices; copies are not timed)."""
+    (copied back from HBM in slices; copies are not timed), then on `single` of them with one thread.  Its totals,
+    last strategies and plans are compared with what the timed GPU steps left behind: a mismatch ends the run."""
     import numpy as np
     import oracle
     threads = host_threads()
     n = min(sample_problems, B)
-    spent, done = 0.0, 0
+    spent, done, bad = 0.0, 0, []
+    g_total, g_last, g_plan = gpu_total[:n].cpu().numpy(), gpu_last[:n].cpu().numpy(), gpu_plan[:n].cpu().numpy()
     while done < n:
         m = min(batch, n - done)
         hc = c[done:done + m].cpu().numpy()
         hR = R[done:done + m].cpu().numpy()
         t0 = time.perf_counter()
         arg, _, total, last = oracle.chain(hc, hR, nthreads=threads)
-        oracle.backtrack(arg, last)
+        plan = oracle.backtrack(arg, last)
         spent += time.perf_counter() - t0
+        ok = (total == g_total[done:done + m]) & (last == g_last[done:done + m]) & \
+             (plan == g_plan[done:done + m]).all(axis=1)
+        bad += [done + int(i) for i in np.nonzero(~ok)[0]]
         done += m
         del hc, hR
+    if bad:
+        print(f"PARITY FAILURE: the GPU's total, last or plan differs from the oracle's on problems {bad[:16]} "
+              f"({len(bad)} of {n})", file=sys.stderr)
+        sys.exit(1)
     cells = n * (N - 1) * K * K
+    n1 = min(single, n)
+    hc, hR = c[:n1].cpu().numpy(), R[:n1].cpu().numpy()
+    t0 = time.perf_counter()
+    arg, _, total, last = oracle.chain(hc, hR, nthreads=1)
+    oracle.backtrack(arg, last)
+    spent1 = time.perf_counter() - t0
     return {"value": cells / spent, "unit": "cells/s", "cores": threads, "kind": "oracle",
             "sample": f"first {n} of {B} problems (N={N}, K={K}), {spent:.1f} s of oracle time, "
-                      f"one problem per thread"}
+                      f"one problem per thread",
+            "single_thread_value": n1 * (N - 1) * K * K / spent1,
+            "single_thread_sample": f"first {n1} problems, {spent1:.1f} s on one thread",
+            "parity_checked_problems": n}
 
 
 def main():
@@ -210,7 +228,8 @@ def main():
     out["roofline"]["copy_kernel_bytes_each_way"] = copy_src.numel() * 8
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(c, R, B, N, K)
+        out["cpu_baseline"] = cpu_baseline(c, R, B, N, K, total, last, plan)
+        out["parity_checked_problems"] = out["cpu_baseline"]["parity_checked_problems"]
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
 
     # the other rows need room of their own (one of them holds the tables of 11 meshes): every view of R goes too

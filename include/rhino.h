@@ -140,17 +140,24 @@ int rh_build_reshard(const rh_mesh_t* mesh, int32_t n_edges, int32_t Kp,
  *             every strategy is feasible and a fortieth on tables from sharding specs, where a
  *             third of the slots are valid layouts (infeasible strategies are skipped);
  *           - otherwise a few long (N >= 64) chains of wide tables (Kp 128 or 256) are spread
- *             over eight workgroups each (B <= 32; four each for B <= 64), which meet once per
- *             edge through the
- *             workspace.  That meeting is a bounded wait: if a workgroup ever gives up (never
- *             seen; it needs the eight workgroups of a problem resident together), the
- *             problem returns total = -1;
- *           - given rh_workspace_size(RH_WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp) bytes instead
- *             (B <= 32, N >= 128, Kp 64, 128 or 256; more bytes than the above), all problems
+ *             over eight workgroups each, or four each, whichever lets every workgroup of the
+ *             launch have a compute unit of the current device to itself (rh_gang_workgroups;
+ *             B <= 32 resp. B <= 64 on 256 compute units); the workgroups of a problem meet once
+ *             per edge through the workspace.  This route needs the device otherwise idle: the
+ *             meeting is a bounded wait, and if the workgroups of a problem are not resident
+ *             together (other kernels hold compute units) a workgroup gives up after 2^22 polls
+ *             and the problem returns total = -1 with undefined arg, vfinal and last, under
+ *             RH_OK.  A caller that overlaps this call with other work on the device checks
+ *             total >= 0 before rh_backtrack (rh_plan_memory never takes such a problem as
+ *             feasible) or passes no workspace;
+ *           - given EXACTLY rh_workspace_size(RH_WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp) bytes
+ *             (3 <= B <= 32, N >= 128, Kp 64, 128 or 256; more bytes than the above), all problems
  *             take the segmented route (their matrices one problem after the other).  Worth
  *             it when most strategies are infeasible: then a problem takes a fifteenth of what the eight
  *             workgroups need for up to 32 problems together; with every strategy feasible
- *             a problem takes two thirds of that.
+ *             a problem takes two thirds of that.  Any other size of at least the
+ *             RH_WS_MINPLUS_CHAIN bytes takes the route above, so a caller that passes one large
+ *             pool to every call never lands here by accident.
  *           With NULL, 0 the call needs no workspace.
  * Base pointers and batch strides must keep every row 16-byte aligned.
  */
@@ -381,6 +388,13 @@ int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len
  * if the sizes are invalid). */
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,
                          int32_t Kp_or_S);
+
+/* Workgroups per problem that rh_minplus_chain's several-workgroups route uses for B
+ * problems on a device with `compute_units` compute units: 8 or 4, the largest that gives
+ * every workgroup of the launch a compute unit of its own, or 0 if not even 4 fit (the call
+ * then runs one workgroup per problem and RH_WS_MINPLUS_CHAIN asks for no bytes).  Pure host
+ * arithmetic; the library itself asks the current device for its count. */
+int rh_gang_workgroups(int32_t B, int32_t compute_units);
 
 /*
  * rh_check_costs -- optional guard for the cost contract.  Counts the entries

@@ -73,6 +73,8 @@ def lib():
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
         L.rh_workspace_size.restype = sz
         L.rh_check_costs.argtypes = [vp, i64, vp, vp]
+        L.rh_gang_workgroups.argtypes = [i32, i32]
+        L.rh_gang_workgroups.restype = ctypes.c_int
         L.rh_strerror.argtypes = [ctypes.c_int]
         L.rh_strerror.restype = ctypes.c_char_p
         for f in (L.rh_build_reshard, L.rh_minplus_chain, L.rh_backtrack, L.rh_stage_dp, L.rh_check_costs,
@@ -88,6 +90,10 @@ def strerror(code: int) -> str:
 
 def rh_version() -> int:
     return lib().rh_version()
+
+
+def rh_gang_workgroups(B: int, compute_units: int) -> int:
+    return lib().rh_gang_workgroups(B, compute_units)
 
 
 def _stream():

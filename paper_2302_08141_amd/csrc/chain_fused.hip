@@ -172,7 +172,10 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
         const int cs = i & 1, ns = cs ^ 1;           // this edge's set of tables, the next edge's
         const EdgeIn e2 = load_edge(i + 2);
         // arg of edge i - 1 leaves now, one store per thread whatever the thread (a store under a condition would
-        // keep the waits below from counting the loads that run ahead; threads beyond Kp repeat a slot)
+        // keep the waits below from counting the loads that run ahead; threads beyond Kp repeat a slot).  At i = 0
+        // the store puts a placeholder into edge 0's row.  Every thread that writes a slot writes the same slot of
+        // the same row again one edge later (or after the loop) with the final value, and a thread's own stores to
+        // one address keep their order, so whichever thread's store lands last, it is a final one.
         arg[((int64_t)p * (N - 1) + (i > 0 ? i - 1 : 0)) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
         // ---- first half: relax edge i; on the side, the tables of edge i + 1 ----
         ready = prepare_edge(e1, ns);
@@ -269,7 +272,7 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
         lds_barrier();   // v_{i+1} and the lists of edge i + 1 visible
         e1 = e2;
     }
-    if (N > 1 && tid < KP) arg[((int64_t)p * (N - 1) + (N - 2)) * KP + tid] = argl[tid];
+    if (N > 1) arg[((int64_t)p * (N - 1) + (N - 2)) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
 
     constexpr int MP = 1;
 #pragma unroll

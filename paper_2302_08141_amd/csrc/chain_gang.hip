@@ -14,8 +14,9 @@
 // until all show the tag of the current edge.  Two key buffers alternate by edge parity: a
 // workgroup can publish edge i+2 into the slots of edge i only after it has read every
 // workgroup's keys of edge i+1, which those publish only after they have read edge i.  The
-// gang must be resident at once (the launcher sizes the gangs so that all of them fit the 256 CUs);
-// the poll is bounded all the same, and a problem whose gang gave up reports total = -1.
+// gang must be resident at once (the launcher asks the device for its number of compute units and sizes the gangs
+// so that every workgroup of the launch has a compute unit of its own; more problems than that take the
+// one-workgroup kernel); the poll is bounded all the same, and a problem whose gang gave up reports total = -1.
 #include "kernels.h"
 
 namespace rh {
@@ -194,7 +195,9 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
                         if ((stale >> 63) == 0 || gave_up) break;
                         if (++spins > kSpinLimit) {   // stop waiting, here and from now on
                             gave_up = true;
-                            __hip_atomic_store(failed, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            // the flag reaches device memory before anything this thread publishes afterwards
+                            __hip_atomic_store(failed, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");
                         }
                         __builtin_amdgcn_s_sleep(1);
                     }
@@ -241,7 +244,7 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
         }
         if (lane == 0) {
             // a thread that gave up flagged the problem before it published anything further
-            const bool bad = gave_up || __hip_atomic_load(failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+            const bool bad = gave_up || __hip_atomic_load(failed, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != 0;
             total[p] = bad ? -1 : (int64_t)(key >> 10);
             last[p] = (int32_t)(key & 1023u);
         }
@@ -250,20 +253,28 @@ chain_gang_kernel(int32_t N, const int64_t* __restrict__ c, int64_t c_bs, const 
 
 }  // namespace
 
-// Workgroups per problem: as many as keep all gangs resident together (one workgroup per compute unit), four at
-// least (two do not beat a workgroup on its own: measured at Kp = 128; at Kp = 256 their rows would not fit the
-// registers).
-static int gang_size(int32_t B, int32_t Kp) {
-    (void)Kp;
+// Workgroups per problem: as many as keep all gangs resident together (one workgroup of 1024 threads per compute
+// unit), four at least (two do not beat a workgroup on its own: measured at Kp = 128; at Kp = 256 their rows would
+// not fit the registers).  0 = the route is not taken.
+int gang_workgroups(int32_t B, int32_t compute_units) {
+    if (B < 1) return 0;
     for (int g = kMaxGang; g >= 4; g /= 2)
-        if (B * g <= 256) return g;
+        if ((int64_t)B * g <= compute_units) return g;
     return 0;
+}
+
+// Compute units of the current device; 0 if there is none to ask (then the route is never taken).
+static int device_compute_units() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return n;
 }
 
 size_t gang_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
     // worth it only for long chains of wide tables, and safe only while every gang is resident
     if (B < 1 || N < 64 || (Kp != 128 && Kp != 256)) return 0;
-    const int g = gang_size(B, Kp);
+    const int g = gang_workgroups(B, device_compute_units());
     if (g == 0) return 0;
     return (size_t)B * 2 * g * Kp * sizeof(u64) + (((size_t)B * 4 + 255) & ~(size_t)255);
 }
@@ -271,7 +282,7 @@ size_t gang_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
 hipError_t launch_chain_gang(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs,
                              const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
                              int64_t* total, int32_t* last, void* workspace, hipStream_t stream) {
-    const int g = gang_size(B, Kp);
+    const int g = gang_workgroups(B, device_compute_units());
     if (g == 0) return hipErrorInvalidValue;
     char* wsb = static_cast<char*>(workspace);
     uint32_t* counters = reinterpret_cast<uint32_t*>(wsb);   // one failure flag per problem

@@ -20,7 +20,8 @@ hipError_t launch_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int6
                         int64_t* total, int32_t* last, hipStream_t stream);
 
 // Few long chains of wide tables: eight workgroups per problem (needs a workspace).
-size_t gang_workspace_bytes(int32_t B, int32_t N, int32_t Kp);   // 0 = not applicable to these sizes
+int gang_workgroups(int32_t B, int32_t compute_units);            // workgroups per problem, 0 = route not taken
+size_t gang_workspace_bytes(int32_t B, int32_t N, int32_t Kp);   // 0 = not applicable to these sizes or this device
 hipError_t launch_chain_gang(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs,
                              const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* vfinal,
                              int64_t* total, int32_t* last, void* workspace, hipStream_t stream);

@@ -66,7 +66,8 @@ first_feasible_kernel(int32_t B, const int64_t* __restrict__ total, const int64_
     __shared__ int32_t best[kThreads];
     int32_t mine = INT32_MAX;
     for (int b = threadIdx.x; b < B; b += kThreads)
-        if (total[b] < kInf && plan_mem[b] <= limit) { mine = b; break; }   // b ascends per thread
+        if (total[b] >= 0 && total[b] < kInf && plan_mem[b] <= limit) { mine = b; break; }   // b ascends per thread;
+            // a negative total marks a problem whose search did not finish (rh_minplus_chain): never feasible
     best[threadIdx.x] = mine;
     __syncthreads();
     for (int s = kThreads / 2; s > 0; s >>= 1) {

@@ -79,10 +79,11 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t
     if (workspace != nullptr && (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
         return RH_ERR_WORKSPACE;
     // One or two long chains are cut into segments; three and more take the segmented route only when the caller
-    // brings its (larger) workspace, which says that the tables are sparse enough for it to pay.
+    // states the size of that route's workspace exactly, which says that the tables are sparse enough for it to
+    // pay (a caller that hands over one large pool for every call must not land on it by accident).
     const size_t scan = rh::scan_workspace_bytes(B, N, Kp);
     const size_t gang = rh::gang_workspace_bytes(B, N, Kp);
-    if (scan != 0 && workspace != nullptr && workspace_bytes >= scan && (B <= 2 || scan > gang))
+    if (scan != 0 && workspace != nullptr && (B <= 2 ? workspace_bytes >= scan : workspace_bytes == scan))
         return from_hip(rh::launch_chain_scan(B, N, Kp, c, c_batch_stride, R, R_batch_stride, arg, vfinal, total,
                                               last, workspace, static_cast<hipStream_t>(stream)));
     if (gang != 0 && workspace != nullptr && workspace_bytes >= gang)
@@ -267,6 +268,8 @@ const char* rh_strerror(int code) {
     }
 }
 
-int rh_version(void) { return 100; }
+int rh_gang_workgroups(int32_t B, int32_t compute_units) { return rh::gang_workgroups(B, compute_units); }
+
+int rh_version(void) { return 101; }
 
 }  // extern "C"

@@ -162,8 +162,11 @@ hipError_t launch_stage_fast(int32_t B, int32_t L, int32_t S, const int64_t* seg
                              int32_t* cut, int32_t s_query, int32_t* bounds, hipStream_t stream) {
     if (B == 0) return hipSuccess;
     const size_t lds = 3 * ((size_t)L + 1) * sizeof(int64_t);
+    // always the kernel's largest size, never this call's own: the attribute is shared by every caller of the
+    // process, and a smaller value set by one thread would refuse the launch of another
+    constexpr size_t kMaxLds = 3 * ((size_t)kFastMaxL + 1) * sizeof(int64_t);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(stage_fast_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(stage_fast_kernel, dim3(B), dim3(kFastThreads), lds, stream, L, S, seg_cost, bottleneck, cut,
                        s_query, bounds);

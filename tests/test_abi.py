@@ -32,9 +32,10 @@ def test_host_only_calls():
     assert one > 3 * 70 * 256 * 256 * 8 and rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 2, 8192, 256) == 2 * one
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 128, 64) > 0
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 127, 64) == 0          # too short to cut
-    assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 127, 256) > 0          # eight workgroups instead
-    gang = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 3, 8192, 256)             # three chains: eight workgroups each
-    assert 0 < gang < one
+    # several workgroups per problem only where every workgroup gets a compute unit of the device to itself; this
+    # process may have no device at all, and then the route asks for nothing
+    gang = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 3, 8192, 256)
+    assert gang == 0 or 0 < gang < one
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 1, 8192, 512) == 0
     # the segmented route for more problems
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, 16, 8192, 256) == 16 * one
@@ -58,3 +59,18 @@ def test_host_only_calls():
     assert L.rh_backtrack(-1, 2, 128, None, None, None, None) == -2
     assert L.rh_build_reshard(None, 1, 128, None, None, None, None, None, None, None) == -1
     assert L.rh_check_costs(None, 5, None, None) == -1
+
+
+def test_workgroups_per_problem_follow_the_compute_units():
+    # eight workgroups per problem while they all fit, then four, then the route is not taken
+    g = rh.rh_gang_workgroups
+    assert [g(B, 256) for B in (1, 32, 33, 64, 65)] == [8, 8, 4, 4, 0]
+    assert [g(B, 304) for B in (38, 39, 76, 77)] == [8, 4, 4, 0]
+    assert [g(B, 64) for B in (8, 9, 16, 17)] == [8, 4, 4, 0]
+    assert g(1, 8) == 8 and g(1, 7) == 4 and g(1, 3) == 0 and g(1, 0) == 0      # a device with few units, or none
+    assert g(0, 256) == 0 and g(-1, 256) == 0
+    for cus in (1, 8, 60, 104, 256, 304):
+        for B in range(1, 80):
+            n = g(B, cus)
+            assert n in (0, 4, 8) and B * n <= cus
+            assert n == 8 or B * 8 > cus                                      # never fewer than what fits

@@ -259,7 +259,9 @@ def test_several_chains_through_the_segmented_route():
         dc, dR = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
         need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SEGMENTED, B, N, Kp)
         assert need > rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, B, N, Kp) > 0
-        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        # only the exact size asks for the segmented route; a larger pool takes the default route of these sizes
+        # (same results either way)
+        ws = torch.empty(need if shared else need + 4096, dtype=torch.uint8, device=DEV)
         arg = torch.full((B, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
         vfinal = torch.zeros((B, Kp), dtype=torch.int64, device=DEV)
         total = torch.zeros(B, dtype=torch.int64, device=DEV)

@@ -109,16 +109,33 @@ def test_batched_random_chains_full_size():
     obj = objective_of_plans(c, R, plan)
     assert torch.equal(obj, total)
     assert int(plan.min()) >= 0 and int(plan.max()) < K and torch.equal(plan[:, -1], last)
-    # a seeded sample of problems in full against the oracle, inputs regenerated on the host
+    # the device-side generator is the seeded twin of the host generator: a sample of its problems is regenerated
+    # on the host and compared element by element
     sample = [0, 1, 255, 256, 1777, 2048, 3333, B - 1]
     hc, hR = syn.random_chain_batch(sample, N, K, w["c_range"], w["r_range"])
     idx = torch.tensor(sample, device=DEV)
     assert np.array_equal(c[idx].cpu().numpy(), hc) and np.array_equal(R[idx].cpu().numpy(), hR)
-    o_arg, _, o_total, o_last = oracle.chain(hc, hR, nthreads=8)
-    assert np.array_equal(total[idx].cpu().numpy(), o_total)
-    assert np.array_equal(last[idx].cpu().numpy(), o_last)
-    assert np.array_equal(arg[idx].cpu().numpy().view(np.uint16), o_arg)
-    assert np.array_equal(plan[idx].cpu().numpy(), oracle.backtrack(o_arg, o_last))
+    del hc, hR
+    # 264 seeded problems in full against the oracle (every arg row, total, last, plan): the eight above, plus 256
+    # spread over the batch by a fixed stride that is coprime to the wave, workgroup and fill-slice sizes
+    picked = sorted(set(sample) | {(7 + 13 * t) % B for t in range(256)})
+    assert len(picked) >= 256
+    for s0 in range(0, len(picked), 32):
+        part = picked[s0:s0 + 32]
+        pidx = torch.tensor(part, device=DEV)
+        hc, hR = c[pidx].cpu().numpy(), R[pidx].cpu().numpy()
+        o_arg, _, o_total, o_last = oracle.chain(hc, hR, nthreads=8)
+        assert np.array_equal(total[pidx].cpu().numpy(), o_total), part
+        assert np.array_equal(last[pidx].cpu().numpy(), o_last), part
+        assert np.array_equal(arg[pidx].cpu().numpy().view(np.uint16), o_arg), part
+        assert np.array_equal(plan[pidx].cpu().numpy(), oracle.backtrack(o_arg, o_last)), part
+    # total and last of a further 1024 problems (every fourth), the oracle run on them in slices
+    for s0 in range(2, B, 4 * 64):
+        part = list(range(s0, min(B, s0 + 4 * 64), 4))
+        pidx = torch.tensor(part, device=DEV)
+        _, _, o_total, o_last = oracle.chain(c[pidx].cpu().numpy(), R[pidx].cpu().numpy(), nthreads=8)
+        assert np.array_equal(total[pidx].cpu().numpy(), o_total), s0
+        assert np.array_equal(last[pidx].cpu().numpy(), o_last), s0
 
 
 def test_moe_shaped_graph_full_size():
