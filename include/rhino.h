@@ -46,6 +46,7 @@ extern "C" {
 #define RH_ERR_WORKSPACE (-4) /* workspace missing or too small */
 #define RH_ERR_OVERFLOW (-5)  /* a cost violates the cost contract (rh_check_costs) */
 #define RH_ERR_HIP (-6)       /* the HIP runtime refused a launch */
+#define RH_ERR_STATIC_SCRATCH (-7) /* sizes beyond the static scratch of rh_stage_dp_window_static */
 
 /* Logical device mesh the plans are searched for (Sec. 4: devices form a
  * mesh and sharding is applied per mesh axis).  A search input: no device
@@ -311,6 +312,28 @@ int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                        const int64_t* xfer, int64_t eps_num, int64_t eps_den,
                        int64_t* bottleneck, int32_t* cut, int32_t* bounds,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * rh_stage_dp_window_static -- rh_stage_dp_window for callers that cannot allocate device
+ * memory and have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (without the workspace), same kernels, same
+ * results bit for bit; the scratch is a static array in device memory, rh_static_scratch_bytes()
+ * = 8 MiB per GPU, which every GPU the library runs on holds until the process ends.  The call
+ * allocates and frees nothing.
+ *   - Sizes whose rh_workspace_size(RH_WS_STAGE_DP_WINDOW, B, L, S) exceeds that maximum return
+ *     RH_ERR_STATIC_SCRATCH and launch nothing (e.g. one problem with L = 4096, S = 64 needs
+ *     0.9 MiB and with L = 65536 2.5 MiB; eight problems with L = 65536 do not fit).
+ *   - The scratch used is the copy of the device that is current at the call; `stream` must
+ *     belong to that device.
+ *   - All calls on one GPU share the one array: two calls that overlap on a GPU (different
+ *     streams, different host threads) race and return garbage.  Calls in stream order are safe;
+ *     nothing needs clearing between them.
+ */
+int rh_stage_dp_window_static(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
+                              const int64_t* xfer, int64_t eps_num, int64_t eps_den,
+                              int64_t* bottleneck, int32_t* cut, int32_t* bounds,
+                              void* stream);
+size_t rh_static_scratch_bytes(void);
 
 /*
  * rh_interval_costs -- the time of every candidate pipeline stage of an operator chain.

@@ -65,6 +65,10 @@ def lib():
         L.rh_mask_replicated.restype = L.rh_plan_memory.restype = ctypes.c_int
         L.rh_stage_dp_window.argtypes = [i32, i32, i32, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
         L.rh_stage_dp_window.restype = ctypes.c_int
+        L.rh_stage_dp_window_static.argtypes = [i32, i32, i32, vp, vp, i64, i64, vp, vp, vp, vp]
+        L.rh_stage_dp_window_static.restype = ctypes.c_int
+        L.rh_static_scratch_bytes.argtypes = []
+        L.rh_static_scratch_bytes.restype = sz
         L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp]
         L.rh_stage_dp_interval.argtypes = [i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_interval_costs_banded.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp, vp]
@@ -232,6 +236,22 @@ def rh_stage_dp_window(B: int, L: int, S: int, seg_cost, xfer, eps_num: int, eps
                                     _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)),
                                     _ptr(bounds, torch.int32, "bounds", b * (s_ + 1)), ws_ptr, ws_bytes, _stream()),
            "rh_stage_dp_window")
+
+
+def rh_stage_dp_window_static(B: int, L: int, S: int, seg_cost, xfer, eps_num: int, eps_den: int, bottleneck, cut,
+                              bounds):
+    """rh_stage_dp_window on the library's own static scratch (no workspace, nothing allocated)."""
+    b, l, s_ = max(B, 0), max(L, 0), max(S, 0)
+    _check(lib().rh_stage_dp_window_static(B, L, S, _ptr(seg_cost, torch.int64, "seg_cost", b * l),
+                                           _ptr(xfer, torch.int64, "xfer", b * (l + 1)), eps_num, eps_den,
+                                           _ptr(bottleneck, torch.int64, "bottleneck", b),
+                                           _ptr(cut, torch.int32, "cut", b * s_ * (l + 1)),
+                                           _ptr(bounds, torch.int32, "bounds", b * (s_ + 1)), _stream()),
+           "rh_stage_dp_window_static")
+
+
+def rh_static_scratch_bytes() -> int:
+    return int(lib().rh_static_scratch_bytes())
 
 
 def rh_interval_costs(B: int, L: int, Kp: int, c, R, ldT: int, T):

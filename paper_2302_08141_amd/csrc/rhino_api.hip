@@ -4,7 +4,32 @@
 
 #include "kernels.h"
 
+#include <mutex>
+
+// Scratch memory of rh_stage_dp_window_static: one copy per GPU, held until the process ends.  In host code the
+// name below is only a handle for hipGetSymbolAddress; the device address is looked up once per device.
+#define RH_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+static __device__ __align__(256) unsigned char scratch[RH_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, nullptr until first asked for
+
+// Address of the current device's copy of `scratch`.
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RH_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return RH_ERR_HIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return RH_OK;
+}
 
 bool valid_kp(int32_t Kp) { return Kp >= RH_KMIN && Kp <= RH_KMAX && (Kp & (Kp - 1)) == 0; }
 
@@ -187,6 +212,24 @@ int rh_stage_dp_window(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost,
                                             workspace, static_cast<hipStream_t>(stream)));
 }
 
+int rh_stage_dp_window_static(int32_t B, int32_t L, int32_t S, const int64_t* seg_cost, const int64_t* xfer,
+                              int64_t eps_num, int64_t eps_den, int64_t* bottleneck, int32_t* cut, int32_t* bounds,
+                              void* stream) {
+    if (B < 0 || B > 65535 || L < 1 || L > 65536 || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+    if (eps_den < 1 || eps_den > (1 << 20) || eps_num > ((int64_t)1 << 30)) return RH_ERR_SHAPE;
+    if (B == 0) return RH_OK;
+    if (!seg_cost || !bottleneck || !cut) return RH_ERR_NULL;
+    if (rh::stage_window_workspace_bytes(B, L, S) > RH_STATIC_SCRATCH_BYTES) return RH_ERR_STATIC_SCRATCH;
+    void* ws = nullptr;
+    if (const int rc = scratch_of_current_device(&ws)) return rc;
+    // the kernels write every word of the scratch they read (as with a caller's workspace of undefined contents),
+    // so nothing has to be cleared between calls
+    return from_hip(rh::launch_stage_window(B, L, S, seg_cost, xfer, eps_num, eps_den, bottleneck, cut, bounds, ws,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+size_t rh_static_scratch_bytes(void) { return RH_STATIC_SCRATCH_BYTES; }
+
 int rh_interval_costs_banded(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, const int64_t* R,
                              int64_t ldT, int64_t* T, void* stream) {
     if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX || max_len < 1) return RH_ERR_SHAPE;
@@ -264,6 +307,8 @@ const char* rh_strerror(int code) {
         case RH_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case RH_ERR_OVERFLOW: return "a cost violates the cost contract";
         case RH_ERR_HIP: return "the HIP runtime refused a launch";
+        case RH_ERR_STATIC_SCRATCH:
+            return "these sizes need more scratch than the library's static 8 MiB (use rh_stage_dp_window with a workspace)";
         default: return "unknown error code";
     }
 }
