@@ -175,7 +175,14 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
  * operator graph, several logical meshes (mesh shapes are searched in parallel, Sec. 3 /
  * Sec. 4): problem p is searched on meshes[p mod n_meshes].  Nothing of size Kp x Kp is ever
  * stored, so it serves batches whose tables would not fit in memory.  Bound by the vector
- * ALU, not by HBM.
+ * ALU, not by HBM.  Without a workspace a workgroup walks each problem edge by edge; with
+ * rh_workspace_size(RH_WS_MINPLUS_CHAIN_SPECS, B, N, Kp) bytes (B <= 32, N >= 128; 0 = does not
+ * apply) the chains are cut into segments as in rh_minplus_chain -- the min-plus matrix of
+ * every segment (the per-segment strategy tables of Sec. 4.3.2), the vectors at the segment
+ * boundaries, then the sweep inside all segments at once -- with every table entry computed
+ * from the spec words: one 8192-operator chain of 256 strategies takes a twentieth of the time,
+ * and less than building the tables and running rh_minplus_chain on them.  Same outputs bit
+ * for bit on either route.
  *
  *   B >= 0, 1 <= N <= RH_NMAX, Kp 64, 128 or 256, 1 <= n_meshes <= 64
  *   meshes   host, [n_meshes], read during the call
@@ -183,13 +190,16 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c,
  *   K, out_spec, in_spec, dims, elem_bytes   as for rh_build_reshard with n_edges = N-1, shared by
  *            all problems
  *   arg [B][N-1][Kp], vfinal [B][Kp] (may be NULL), total [B], last [B]   as for rh_minplus_chain
+ *   workspace  NULL, 0 or the bytes above (256-byte aligned, contents undefined before and after;
+ *            calls that share a workspace must not overlap)
  */
 int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes,
                            const rh_mesh_t* meshes,
                            const int64_t* c, int64_t c_batch_stride, const int32_t* K,
                            const uint32_t* out_spec, const uint32_t* in_spec,
                            const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg,
-                           int64_t* vfinal, int64_t* total, int32_t* last, void* stream);
+                           int64_t* vfinal, int64_t* total, int32_t* last, void* workspace,
+                           size_t workspace_bytes, void* stream);
 
 /*
  * rh_backtrack -- the plan X of Sec. 4.2 in index form:
@@ -407,6 +417,7 @@ int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len
 #define RH_WS_STAGE_DP_WINDOW 2
 #define RH_WS_STAGE_DP_INTERVAL 3
 #define RH_WS_MINPLUS_CHAIN_SEGMENTED 4
+#define RH_WS_MINPLUS_CHAIN_SPECS 5
 /* Bytes of workspace the call `which` needs for these sizes (0 if none or
  * if the sizes are invalid). */
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,

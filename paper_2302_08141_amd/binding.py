@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG, "librhino.so")
 INF = 1 << 52
 KMIN, KMAX, NMAX = 16, 1024, 16384
 WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW, WS_STAGE_DP_INTERVAL, WS_MINPLUS_CHAIN_SEGMENTED = 0, 1, 2, 3, 4
+WS_MINPLUS_CHAIN_SPECS = 5
 
 
 class RhinoError(RuntimeError):
@@ -54,7 +55,7 @@ def lib():
         L.rh_build_reshard.argtypes = [ctypes.POINTER(Mesh), i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.rh_minplus_chain.argtypes = [i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         L.rh_minplus_chain_specs.argtypes = [i32, i32, i32, i32, ctypes.POINTER(Mesh), vp, i64, vp, vp, vp, vp, vp, vp, vp,
-                                             vp, vp, vp]
+                                             vp, vp, vp, sz, vp]
         L.rh_minplus_chain_specs.restype = ctypes.c_int
         L.rh_backtrack.argtypes = [i32, i32, i32, vp, vp, vp, vp]
         L.rh_stage_dp.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
@@ -152,11 +153,13 @@ def rh_minplus_chain(B: int, N: int, Kp: int, c, c_batch_stride: int, R, R_batch
 
 
 def rh_minplus_chain_specs(B: int, N: int, Kp: int, meshes, c, c_batch_stride: int, K, out_spec, in_spec, dims,
-                           elem_bytes, arg, vfinal, total, last):
+                           elem_bytes, arg, vfinal, total, last, workspace=None):
     """meshes: list of at most 64 Mesh, problem p uses meshes[p % len(meshes)]; c int64[B][N][Kp]; K int32[N];
     out_spec, in_spec int32-typed words [N][Kp]; dims int64[N-1][4]; elem_bytes int32[N-1]; outputs as for
-    rh_minplus_chain."""
+    rh_minplus_chain; workspace: optional uint8 tensor of rh_workspace_size(WS_MINPLUS_CHAIN_SPECS, B, N, Kp) bytes."""
     marr = (Mesh * max(len(meshes), 1))(*meshes)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     b, n, k = max(B, 0), max(N, 1), max(Kp, 0)
     span = (b - 1) * c_batch_stride + n * k if b > 0 else 0
     _check(lib().rh_minplus_chain_specs(B, N, Kp, len(meshes), marr, _ptr(c, torch.int64, "c", span), c_batch_stride,
@@ -166,7 +169,8 @@ def rh_minplus_chain_specs(B: int, N: int, Kp: int, meshes, c, c_batch_stride: i
                                         _ptr(elem_bytes, torch.int32, "elem_bytes", n - 1),
                                         _ptr(arg, torch.int16, "arg", b * (n - 1) * k),
                                         _ptr(vfinal, torch.int64, "vfinal", b * k), _ptr(total, torch.int64, "total", b),
-                                        _ptr(last, torch.int32, "last", b), _stream()), "rh_minplus_chain_specs")
+                                        _ptr(last, torch.int32, "last", b), ws_ptr, ws_bytes, _stream()),
+           "rh_minplus_chain_specs")
 
 
 def rh_backtrack(B: int, N: int, Kp: int, arg, last, plan):

@@ -22,6 +22,14 @@
 
 namespace rh {
 
+// Sweeping parts of chains instead of whole chains (the segmented route): see the kernel.
+struct FusedParts {
+    int32_t len;                 // edges per part; 0 = whole chains
+    int32_t n_full;              // parts of that length per problem; one more part takes the rest of the chain
+    const int64_t* v_start;      // start vector of part q of problem p at v_start + p * v_bs + q * v_stride
+    int64_t v_stride, v_bs;
+};
+
 struct MeshBatch {
     static constexpr int kMax = 64;
     int8_t naxes[kMax];
@@ -40,20 +48,14 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// row of the state matrix for a producer state, one nibble per consumer state (0 R, 1 S, 2 P)
-__device__ __forceinline__ uint32_t kind_row(uint32_t ps) {
-    // R -> {R none, S none (local slice), P impossible}; S -> {R gather, S all-to-all, P impossible};
-    // P -> {R all-reduce, S reduce-scatter = gather volume, P none}
-    return ps == 0u ? 0x400u : (ps == 1u ? 0x421u : 0x013u);
-}
-
 template <int KP, int W>
 __global__ void __launch_bounds__(W * 64)
-chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t* __restrict__ c, int64_t c_bs,
+chain_fused_kernel(int32_t N_chain, int32_t n_meshes, MeshBatch meshes, const int64_t* __restrict__ c, int64_t c_bs,
                    const int32_t* __restrict__ K, const uint32_t* __restrict__ out_spec,
                    const uint32_t* __restrict__ in_spec, const int64_t* __restrict__ dims,
                    const int32_t* __restrict__ elem_bytes, uint16_t* __restrict__ arg,
-                   int64_t* __restrict__ vfinal, int64_t* __restrict__ total, int32_t* __restrict__ last) {
+                   int64_t* __restrict__ vfinal, int64_t* __restrict__ total, int32_t* __restrict__ last,
+                   FusedParts parts) {
     constexpr int CPL = KP / 64;                // consumer columns per lane: ranks lane + 64*k of the valid ones
     constexpr int kThreads = W * 64;
     static_assert(2 * KP <= kThreads, "a thread per strategy slot and side of the edge");
@@ -71,7 +73,20 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    const int p = blockIdx.x;
+    // Whole chains: workgroup = problem.  Parts of chains (parts.len > 0): workgroup (q, p) sweeps part q of problem
+    // p from the start vector it is handed: parts.len edges from operator q * parts.len, the last workgroup of a
+    // problem (q = parts.n_full) the rest of the chain, and only that one writes vfinal, total and last.
+    const int p = parts.len > 0 ? blockIdx.y : blockIdx.x;
+    const int q = parts.len > 0 ? blockIdx.x : 0;
+    const int o_first = q * parts.len;
+    const int N = parts.len > 0 ? (q < parts.n_full ? parts.len : N_chain - 1 - o_first) + 1 : N_chain;
+    const bool writes_final = parts.len == 0 || q == parts.n_full;
+    K += o_first;
+    out_spec += (int64_t)o_first * KP;
+    in_spec += (int64_t)o_first * KP;
+    dims += (int64_t)o_first * 4;
+    elem_bytes += o_first;
+    uint16_t* argp = arg + ((int64_t)p * (N_chain - 1) + o_first) * KP;
     const int mi = p % n_meshes;                // problem p is searched on mesh p mod n_meshes
     // The mesh is indexed by axis numbers computed at run time: in LDS that is an address, in registers it would
     // send the struct to scratch memory (and every wait for a scratch access drains the loads that run ahead).
@@ -84,10 +99,11 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
             mesh.alpha_ns[x] = meshes.alpha_ns[mi][x];
         }
     }
-    const int64_t* cp = c + (int64_t)p * c_bs;
+    const int64_t* cp = c + (int64_t)p * c_bs + (int64_t)o_first * KP;
 
     if (tid < KP) {
-        const int64_t x = cp[tid];
+        const int64_t x = parts.len > 0 ? parts.v_start[(int64_t)p * parts.v_bs + (int64_t)q * parts.v_stride + tid]
+                                        : cp[tid];
         vs[tid] = x < kInf ? x : kInf;
         argl[tid] = 0;
     }
@@ -176,7 +192,7 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
         // the store puts a placeholder into edge 0's row.  Every thread that writes a slot writes the same slot of
         // the same row again one edge later (or after the loop) with the final value, and a thread's own stores to
         // one address keep their order, so whichever thread's store lands last, it is a final one.
-        arg[((int64_t)p * (N - 1) + (i > 0 ? i - 1 : 0)) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
+        argp[(int64_t)(i > 0 ? i - 1 : 0) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
         // ---- first half: relax edge i; on the side, the tables of edge i + 1 ----
         ready = prepare_edge(e1, ns);
         int n_rows = 0, n_cols = 0;
@@ -272,7 +288,8 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
         lds_barrier();   // v_{i+1} and the lists of edge i + 1 visible
         e1 = e2;
     }
-    if (N > 1) arg[((int64_t)p * (N - 1) + (N - 2)) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
+    if (N > 1) argp[(int64_t)(N - 2) * KP + (tid & (KP - 1))] = argl[tid & (KP - 1)];
+    if (!writes_final) return;
 
     constexpr int MP = 1;
 #pragma unroll
@@ -300,11 +317,11 @@ chain_fused_kernel(int32_t N, int32_t n_meshes, MeshBatch meshes, const int64_t*
 
 }  // namespace
 
-hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
-                              const int64_t* c, int64_t c_bs,
-                              const int32_t* K, const uint32_t* out_spec, const uint32_t* in_spec,
-                              const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg, int64_t* vfinal,
-                              int64_t* total, int32_t* last, hipStream_t stream) {
+static hipError_t launch_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                               const int64_t* c, int64_t c_bs,
+                               const int32_t* K, const uint32_t* out_spec, const uint32_t* in_spec,
+                               const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg, int64_t* vfinal,
+                               int64_t* total, int32_t* last, const FusedParts& parts, hipStream_t stream) {
     if (B == 0) return hipSuccess;
     MeshBatch mb{};
     for (int p = 0; p < n_meshes; ++p) {
@@ -315,9 +332,10 @@ hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes
             mb.alpha_ns[p][x] = meshes[p].alpha_ns[x];
         }
     }
+    const dim3 grid = parts.len > 0 ? dim3((unsigned)(parts.n_full + 1), (unsigned)B) : dim3((unsigned)B);
 #define RH_FUSED(KP, W)                                                                                         \
-    hipLaunchKernelGGL((chain_fused_kernel<KP, W>), dim3(B), dim3(W * 64), 0, stream, N, n_meshes, mb, c, c_bs, K, \
-                       out_spec, in_spec, dims, elem_bytes, arg, vfinal, total, last)
+    hipLaunchKernelGGL((chain_fused_kernel<KP, W>), grid, dim3(W * 64), 0, stream, N, n_meshes, mb, c, c_bs, K, \
+                       out_spec, in_spec, dims, elem_bytes, arg, vfinal, total, last, parts)
     switch (Kp) {
         case 64: RH_FUSED(64, 8); break;
         case 128: RH_FUSED(128, 16); break;
@@ -326,6 +344,25 @@ hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes
     }
 #undef RH_FUSED
     return hipGetLastError();
+}
+
+hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                              const int64_t* c, int64_t c_bs,
+                              const int32_t* K, const uint32_t* out_spec, const uint32_t* in_spec,
+                              const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg, int64_t* vfinal,
+                              int64_t* total, int32_t* last, hipStream_t stream) {
+    return launch_fused(B, N, Kp, n_meshes, meshes, c, c_bs, K, out_spec, in_spec, dims, elem_bytes, arg, vfinal, total,
+                        last, FusedParts{0, 0, nullptr, 0, 0}, stream);
+}
+
+hipError_t launch_chain_fused_parts(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                                    const int64_t* c, int64_t c_bs, const int32_t* K, const uint32_t* out_spec,
+                                    const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes,
+                                    int32_t part_len, int32_t n_full, const int64_t* v_start, int64_t v_stride,
+                                    int64_t v_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last,
+                                    hipStream_t stream) {
+    return launch_fused(B, N, Kp, n_meshes, meshes, c, c_bs, K, out_spec, in_spec, dims, elem_bytes, arg, vfinal, total,
+                        last, FusedParts{part_len, n_full, v_start, v_stride, v_bs}, stream);
 }
 
 }  // namespace rh

@@ -21,11 +21,23 @@
 // these integers, see interval_costs.hip) at two lane-operations per cell, in exchange for
 // removing the dependent chain.
 #include "kernels.h"
+#include "reshard_common.h"
 
 namespace rh {
 namespace {
 
 typedef long long ll2 __attribute__((ext_vector_type(2)));
+
+// What the matrix kernel needs to compute an edge table's entries from sharding specs instead of reading them
+// (rh_minplus_chain_specs with a workspace): the arrays of rh_build_reshard and the problem's mesh.
+struct SpecSource {
+    const int32_t* K;
+    const uint32_t* out_spec;
+    const uint32_t* in_spec;
+    const int64_t* dims;
+    const int32_t* elem_bytes;
+    Mesh mesh;
+};
 
 constexpr int kScWaves = 16;                 // waves per workgroup of the matrix kernel
 constexpr int kScRows = 2;                   // entering strategies (rows of M_g) per wave: R values are read once for both
@@ -37,6 +49,9 @@ constexpr int kBdWaves = 16;
 constexpr int kScPiece = 4096;               // elements of R per LDS buffer
 constexpr int kMaxSegLen = 255;              // edges per segment (the planner stays below)
 constexpr int kMaxPartLen = kMaxSegLen / kScSub;   // edges per part of a segment
+constexpr int kSpecPartLen = 48;             // the same when the tables are computed from specs: the canonical words and
+                                             // time tables of a whole part live in LDS next to the staged pieces
+constexpr int kSpecTab = 20;                 // [axis][other axis splits][none | gather | all-to-all | all-reduce | impossible]
 constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
 
 __device__ __forceinline__ void lds_barrier() {
@@ -195,20 +210,27 @@ __device__ __forceinline__ void rank_operators(const int64_t* __restrict__ c0, i
 // Workgroup (rb, g): up to kScBlock feasible entering strategies of segment g, kScRows per wave.  blockIdx.x = rb *
 // nseg_pad + g with nseg_pad a multiple of 8, so the workgroups of one segment, which read the same tables at
 // the same time, share an XCD and its L2.
-template <int KP>
+template <int KP, bool SPECS>
 __global__ void __launch_bounds__(kScThreads)
 scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t nseg_pad,
                    const int64_t* __restrict__ c, const int64_t* __restrict__ R, const int64_t* __restrict__ Vin,
-                   int64_t in_stride, int64_t* __restrict__ Vout, int64_t out_stride) {
+                   int64_t in_stride, int64_t* __restrict__ Vout, int64_t out_stride, SpecSource sp) {
     using G = Shape<KP>;
+    constexpr int PL = SPECS ? kSpecPartLen : kMaxPartLen;    // edges of a part at most
     extern __shared__ double lds[];               // two pieces of kScPiece doubles
     __shared__ int32_t live_rows[KP];
     __shared__ int32_t wave_cnt[KP / 64];
     // lidx[o][rank] = the rank-th feasible strategy of operator l0 + o (ranks past the last repeat it, so that a
     // lookup is always a valid strategy); nl[o] = how many there are
-    __shared__ __align__(4) uint8_t lidx[kMaxPartLen + 1][KP];
-    __shared__ int32_t nl[kMaxPartLen + 1];
+    __shared__ __align__(4) uint8_t lidx[PL + 1][KP];
+    __shared__ int32_t nl[PL + 1];
     __shared__ double c_arrive[2][KP];            // node costs (rank order) of the operator each staged piece's edge arrives at
+    // SPECS: per edge of the part the canonical producer and consumer words of every strategy slot (two bytes each,
+    // 0xFFFF = not a usable layout) and the edge's table of per-axis times; an entry of the edge table is then two
+    // classifications and two table reads (exactly what rh_build_reshard stores)
+    __shared__ uint16_t pwords[SPECS ? PL : 1][KP], qwords[SPECS ? PL : 1][KP];
+    __shared__ int64_t tabs[SPECS ? PL : 1][kSpecTab];
+    __shared__ Mesh mesh_s;                        // in LDS: indexed by axis numbers computed at run time
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -226,6 +248,7 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     if (tid < KP) live = cseg[tid] < kInf;
     const uint64_t mask = __ballot(live);
     if (tid < KP && lane == 0) wave_cnt[wave] = __popcll(mask);
+    if (SPECS && tid == 0) mesh_s = sp.mesh;
     __syncthreads();
     int n_live = 0, before = 0;
 #pragma unroll
@@ -253,6 +276,21 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     // edge table that leaves from its operator and its column of the table that arrives there irrelevant (the
     // vector is infeasible there whatever the table says): such rows and columns are neither fetched nor used.
     rank_operators<KP>(c0, SLq + 1, lidx, nl, wave, lane);
+    if constexpr (SPECS) {
+        for (int idx = tid; idx < SLq * KP; idx += kScThreads) {
+            const int e = idx / KP, slot = idx & (KP - 1);
+            const int64_t* dm = sp.dims + (int64_t)(l0 + e) * 4;
+            const uint32_t pw = canonical(sp.out_spec[(int64_t)(l0 + e) * KP + slot], slot, sp.K[l0 + e], dm, mesh_s);
+            const uint32_t qw = canonical(sp.in_spec[(int64_t)(l0 + e + 1) * KP + slot], slot, sp.K[l0 + e + 1], dm, mesh_s);
+            pwords[e][slot] = (pw & 0x80000000u) ? (uint16_t)0xFFFFu : (uint16_t)pw;
+            qwords[e][slot] = (qw & 0x80000000u) ? (uint16_t)0xFFFFu : (uint16_t)qw;
+        }
+        for (int idx = tid; idx < SLq * kSpecTab; idx += kScThreads) {
+            const int e = idx / kSpecTab, r = idx - e * kSpecTab;
+            const int x = r / 10, o = (r / 5) & 1, kind = r % 5;
+            tabs[e][r] = axis_time(x, o, (uint32_t)kind, mesh_s, sp.dims + (int64_t)(l0 + e) * 4, sp.elem_bytes[l0 + e]);
+        }
+    }
     lds_barrier();
     auto count_at = [&](int o) -> int { return __builtin_amdgcn_readfirstlane(nl[o]); };
 
@@ -285,14 +323,16 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
     };
     Raw raw0, raw1;
     auto fetch = [&](const Cursor& cur, Raw& raw) {
-        const int lgw = 6 + cur.s.lgc;
-        const int row = tid >> lgw, col = tid & ((1 << lgw) - 1);
-        const int b = lidx[cur.e + 1][col];
-        const int64_t* src = R + (int64_t)(l0 + cur.e) * KP * KP + b;
+        if constexpr (!SPECS) {
+            const int lgw = 6 + cur.s.lgc;
+            const int row = tid >> lgw, col = tid & ((1 << lgw) - 1);
+            const int b = lidx[cur.e + 1][col];
+            const int64_t* src = R + (int64_t)(l0 + cur.e) * KP * KP + b;
 #pragma unroll
-        for (int i = 0; i < G::EPT; ++i) {
-            const int a = lidx[cur.e][(cur.j << (12 - lgw)) + (i << (10 - lgw)) + row];
-            raw.r[i] = src[a * KP];
+            for (int i = 0; i < G::EPT; ++i) {
+                const int a = lidx[cur.e][(cur.j << (12 - lgw)) + (i << (10 - lgw)) + row];
+                raw.r[i] = src[a * KP];
+            }
         }
         raw.c = c0[(int64_t)(cur.e + 1) * KP + lidx[cur.e + 1][tid & (KP - 1)]];
     };
@@ -301,10 +341,31 @@ scan_matrix_kernel(int32_t SL, int32_t SLq, int32_t part, int32_t nseg, int32_t 
         const int lgw = 6 + cur.s.lgc;
         const int row = tid >> lgw, col = tid & ((1 << lgw) - 1);
         const bool col_ok = col < cur.s.nb;
+        if constexpr (SPECS) {
+            // the entries of this thread's column, rows (cur.j ...) of the edge's table in rank order
+            const uint32_t qw = qwords[cur.e][lidx[cur.e + 1][col]];
+            const uint32_t q0 = qw & 0xFFu, q1 = qw >> 8;
+            const uint32_t sh0 = 4u * (q0 & 3u), sh1 = 4u * (q1 & 3u);
+            const int64_t* t0 = &tabs[cur.e][0];
+            const int64_t* t1 = &tabs[cur.e][10 + ((q0 & 3u) == 1u ? 5 : 0)];   // axis 1 moves after axis 0 has the consumer's state
 #pragma unroll
-        for (int i = 0; i < G::EPT; ++i) {
-            const bool row_ok = (cur.j << (12 - lgw)) + (i << (10 - lgw)) + row < cur.s.na;
-            dst[i * kScThreads + tid] = (row_ok && col_ok) ? to_f64(raw.r[i]) : kInfD;
+            for (int i = 0; i < G::EPT; ++i) {
+                const int rank = (cur.j << (12 - lgw)) + (i << (10 - lgw)) + row;
+                const uint32_t pw = pwords[cur.e][lidx[cur.e][rank]];
+                const uint32_t p0 = pw & 0xFFu, p1 = pw >> 8;
+                const uint32_t k0 = q0 == p0 ? 0u : ((kind_row(p0 & 3u) >> sh0) & 7u);
+                const uint32_t k1 = q1 == p1 ? 0u : ((kind_row(p1 & 3u) >> sh1) & 7u);
+                // axis 0 moves while axis 1 still has the producer's state
+                const int64_t t = t0[((p1 & 3u) == 1u ? 5u : 0u) + k0] + t1[k1];
+                const bool ok = rank < cur.s.na && col_ok && pw != 0xFFFFu && qw != 0xFFFFu;
+                dst[i * kScThreads + tid] = ok ? to_f64(t) : kInfD;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < G::EPT; ++i) {
+                const bool row_ok = (cur.j << (12 - lgw)) + (i << (10 - lgw)) + row < cur.s.na;
+                dst[i * kScThreads + tid] = (row_ok && col_ok) ? to_f64(raw.r[i]) : kInfD;
+            }
         }
         if (tid < KP) c_arrive[parity][tid] = to_f64(raw.c);
     };
@@ -685,17 +746,19 @@ struct ScanPlan {
 // the shortest last segment wins (that segment is swept after the batch).
 constexpr int kMaxMatrixSegments = 85;
 
-__host__ ScanPlan plan_scan(int32_t N, int32_t Kp) {
+__host__ ScanPlan plan_scan(int32_t N, int32_t Kp, int32_t max_sl = kMaxSegLen) {
     ScanPlan p{};
     const int E = N - 1;
+    const int step = Kp == 64 ? 4 * kScSub : kScSub;
+    const int top = max_sl / step * step;        // longest segment allowed
     int s0 = 16;
     while ((int64_t)(s0 + 1) * (s0 + 1) <= E) ++s0;
-    while ((E - 1) / s0 > kMaxMatrixSegments) ++s0;
-    const int step = Kp == 64 ? 4 * kScSub : kScSub;
+    while ((E - 1) / s0 > kMaxMatrixSegments && s0 < top) ++s0;   // (beyond `top` the matrix launches take more rounds)
     s0 = (s0 + step - 1) / step * step;
+    s0 = s0 < top ? s0 : top;
     int best_sl = s0, best_r = E;
     const int candidates = Kp == 64 ? 5 : 16;
-    for (int sl = s0; sl < s0 + candidates * step; sl += step) {
+    for (int sl = s0; sl < s0 + candidates * step && sl <= top; sl += step) {
         const int r = (E - 1) % sl + 1;           // 1..sl
         if (r < best_r) {
             best_r = r;
@@ -750,7 +813,7 @@ hipError_t run_scan(const ScanPlan& pl, int32_t B, int32_t N, const int64_t* c, 
     int64_t* Msub0 = reinterpret_cast<int64_t*>(ws0 + pl.msub_off);
     int64_t* c_seg0 = reinterpret_cast<int64_t*>(ws0 + pl.cseg_off);
 
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)(((KP + kScBlock - 1) / kScBlock) * nseg_pad));
@@ -769,9 +832,9 @@ hipError_t run_scan(const ScanPlan& pl, int32_t B, int32_t N, const int64_t* c, 
                            N - l_last, pl.r, KP, 1, cp + (int64_t)l_last * KP, c_seg + (int64_t)n_part * prob_c);
         for (int j = 0; j < kScSub; ++j) {
             const bool fin = j + 1 == kScSub;
-            hipLaunchKernelGGL((scan_matrix_kernel<KP>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,
+            hipLaunchKernelGGL((scan_matrix_kernel<KP, false>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,
                                nseg_pad, cp, Rp, j ? Msub + (j - 1) * mat : nullptr, sub, fin ? M : Msub + j * mat,
-                               fin ? mat : sub);
+                               fin ? mat : sub, SpecSource{});
         }
     }
     hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3((unsigned)B), dim3(kBdThreads), 0, stream, pl.SL, SLq, nseg, c,
@@ -804,6 +867,82 @@ hipError_t run_scan(const ScanPlan& pl, int32_t B, int32_t N, const int64_t* c, 
 }
 
 }  // namespace
+
+namespace {
+
+// The same route with every table entry computed from the sharding specs: the matrices problem by problem on the
+// problem's own mesh, the boundary and part vectors as above, then all parts and last segments of all problems in
+// one launch of the kernel that relaxes edges from spec words (it starts every part from its vector and writes arg).
+template <int KP>
+hipError_t run_scan_specs(const ScanPlan& pl, int32_t B, int32_t N, int32_t n_meshes, const Mesh* meshes,
+                          const int64_t* c, int64_t c_bs, const int32_t* K, const uint32_t* out_spec,
+                          const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg,
+                          int64_t* vfinal, int64_t* total, int32_t* last, void* workspace, hipStream_t stream) {
+    const int nseg = pl.G - 1;
+    const int nseg_pad = (nseg + 7) & ~7;
+    const size_t lds = 2 * kScPiece * sizeof(double);
+    const int SLq = pl.SL / kScSub, n_part = nseg * kScSub;
+    const int64_t prob_c = (int64_t)(SLq + 1) * KP;
+    const int64_t mat = (int64_t)KP * KP, sub = (kScSub - 1) * mat;
+    const int64_t ws_elems = (int64_t)(pl.total / sizeof(int64_t));
+    char* ws0 = static_cast<char*>(workspace);
+    int64_t* M0 = reinterpret_cast<int64_t*>(ws0 + pl.m_off);
+    int64_t* Msub0 = reinterpret_cast<int64_t*>(ws0 + pl.msub_off);
+    int64_t* c_seg0 = reinterpret_cast<int64_t*>(ws0 + pl.cseg_off);
+
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(scan_matrix_kernel<KP, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)(((KP + kScBlock - 1) / kScBlock) * nseg_pad));
+    for (int p = 0; p < B; ++p) {
+        int64_t* M = M0 + p * ws_elems;
+        int64_t* Msub = Msub0 + p * ws_elems;
+        const int64_t* cp = c + (int64_t)p * c_bs;
+        const SpecSource sp{K, out_spec, in_spec, dims, elem_bytes, meshes[p % n_meshes]};
+        for (int j = 0; j < kScSub; ++j) {
+            const bool fin = j + 1 == kScSub;
+            hipLaunchKernelGGL((scan_matrix_kernel<KP, true>), grid, dim3(kScThreads), lds, stream, pl.SL, SLq, j, nseg,
+                               nseg_pad, cp, static_cast<const int64_t*>(nullptr), j ? Msub + (j - 1) * mat : nullptr,
+                               sub, fin ? M : Msub + j * mat, fin ? mat : sub, sp);
+        }
+    }
+    hipLaunchKernelGGL((scan_boundary_kernel<KP>), dim3((unsigned)B), dim3(kBdThreads), 0, stream, pl.SL, SLq, nseg, c,
+                       c_bs, M0, c_seg0, ws_elems);
+    hipLaunchKernelGGL((scan_part_vectors_kernel<KP>), dim3(kScSub - 1, nseg, (unsigned)B), dim3(kBdThreads), 0, stream,
+                       pl.SL, SLq, c, c_bs, Msub0, c_seg0, ws_elems);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_chain_fused_parts(B, N, KP, n_meshes, meshes, c, c_bs, K, out_spec, in_spec, dims, elem_bytes, SLq,
+                                    n_part, c_seg0, prob_c, ws_elems, arg, vfinal, total, last, stream);
+}
+
+}  // namespace
+
+size_t scan_specs_workspace_bytes(int32_t B, int32_t N, int32_t Kp) {
+    if (B < 1 || B > 32 || N < 128 || (Kp != 64 && Kp != 128 && Kp != 256)) return 0;
+    const ScanPlan pl = plan_scan(N, Kp, kSpecPartLen * kScSub);
+    return (size_t)B * pl.total;
+}
+
+hipError_t launch_chain_scan_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                                   const int64_t* c, int64_t c_bs, const int32_t* K, const uint32_t* out_spec,
+                                   const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes,
+                                   uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last, void* workspace,
+                                   hipStream_t stream) {
+    const ScanPlan pl = plan_scan(N, Kp, kSpecPartLen * kScSub);
+    switch (Kp) {
+        case 64:
+            return run_scan_specs<64>(pl, B, N, n_meshes, meshes, c, c_bs, K, out_spec, in_spec, dims, elem_bytes, arg,
+                                      vfinal, total, last, workspace, stream);
+        case 128:
+            return run_scan_specs<128>(pl, B, N, n_meshes, meshes, c, c_bs, K, out_spec, in_spec, dims, elem_bytes, arg,
+                                       vfinal, total, last, workspace, stream);
+        case 256:
+            return run_scan_specs<256>(pl, B, N, n_meshes, meshes, c, c_bs, K, out_spec, in_spec, dims, elem_bytes, arg,
+                                       vfinal, total, last, workspace, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_chain_scan(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t c_bs, const int64_t* R,
                              int64_t R_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last,

@@ -41,6 +41,25 @@ hipError_t launch_chain_fused(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes
                               const int64_t* dims, const int32_t* elem_bytes, uint16_t* arg, int64_t* vfinal,
                               int64_t* total, int32_t* last, hipStream_t stream);
 
+// The same kernel sweeping parts of chains: part q of problem p (part_len edges from operator q * part_len; part
+// n_full takes the rest of the chain and alone writes vfinal, total, last) starts from the vector at
+// v_start + p * v_bs + q * v_stride.
+hipError_t launch_chain_fused_parts(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                                    const int64_t* c, int64_t c_bs, const int32_t* K, const uint32_t* out_spec,
+                                    const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes,
+                                    int32_t part_len, int32_t n_full, const int64_t* v_start, int64_t v_stride,
+                                    int64_t v_bs, uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last,
+                                    hipStream_t stream);
+
+// Long chains from specs, parallel along the chain (needs a workspace): the segmented route with every table
+// entry computed from the spec words.
+size_t scan_specs_workspace_bytes(int32_t B, int32_t N, int32_t Kp);   // 0 = not applicable to these sizes
+hipError_t launch_chain_scan_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const Mesh* meshes,
+                                   const int64_t* c, int64_t c_bs, const int32_t* K, const uint32_t* out_spec,
+                                   const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes,
+                                   uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last, void* workspace,
+                                   hipStream_t stream);
+
 hipError_t launch_backtrack(int32_t B, int32_t N, int32_t Kp, const uint16_t* arg,
                             const int32_t* last, int32_t* plan, hipStream_t stream);
 

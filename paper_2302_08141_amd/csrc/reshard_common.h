@@ -37,6 +37,14 @@ __device__ __forceinline__ uint32_t canonical(uint32_t w, int slot, int k_real, 
     return ok ? out : (out | 0x80000000u);
 }
 
+// Row of the state matrix for a producer state, one nibble per consumer state (0 replicate, 1 split, 2 partial):
+// replicate -> {none, none (local slice), impossible}; split -> {gather, all-to-all, impossible};
+// partial -> {all-reduce, reduce-scatter = gather volume, none}.  Two equal canonical bytes cost nothing whatever
+// the row says (same dim and stride).
+__device__ __forceinline__ uint32_t kind_row(uint32_t ps) {
+    return ps == 0u ? 0x400u : (ps == 1u ? 0x421u : 0x013u);
+}
+
 // Time of one mesh axis x for one kind of byte volume, when the other axis splits the tensor
 // (o = 1) or not: the local tensor is the whole tensor over the other axis' shard count, and
 // the bytes a device receives are T(m-1)/m (all-gather, reduce-scatter), T(m-1)/m^2

@@ -121,7 +121,8 @@ int rh_minplus_chain(int32_t B, int32_t N, int32_t Kp, const int64_t* c, int64_t
 int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, const rh_mesh_t* meshes, const int64_t* c,
                            int64_t c_batch_stride, const int32_t* K, const uint32_t* out_spec,
                            const uint32_t* in_spec, const int64_t* dims, const int32_t* elem_bytes,
-                           uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last, void* stream) {
+                           uint16_t* arg, int64_t* vfinal, int64_t* total, int32_t* last, void* workspace,
+                           size_t workspace_bytes, void* stream) {
     if (B < 0 || N < 1 || N > RH_NMAX || n_meshes < 1 || n_meshes > 64) return RH_ERR_SHAPE;
     if (Kp != 64 && Kp != 128 && Kp != 256) return RH_ERR_K_RANGE;
     if (B == 0) return RH_OK;
@@ -134,6 +135,13 @@ int rh_minplus_chain_specs(int32_t B, int32_t N, int32_t Kp, int32_t n_meshes, c
     if (N == 1)   // no edge, nothing to compute from specs (their pointers may be NULL): v_0 = c_0 by the plain kernel
         return from_hip(rh::launch_chain(B, 1, Kp, c, c_batch_stride, nullptr, 0, nullptr, vfinal, total, last,
                                          static_cast<hipStream_t>(stream)));
+    if (workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RH_ERR_WORKSPACE;
+    // with its workspace a few long chains are cut into segments, as in rh_minplus_chain
+    const size_t scan = rh::scan_specs_workspace_bytes(B, N, Kp);
+    if (scan != 0 && workspace != nullptr && workspace_bytes >= scan)
+        return from_hip(rh::launch_chain_scan_specs(B, N, Kp, n_meshes, ms, c, c_batch_stride, K, out_spec, in_spec,
+                                                    dims, elem_bytes, arg, vfinal, total, last, workspace,
+                                                    static_cast<hipStream_t>(stream)));
     return from_hip(rh::launch_chain_fused(B, N, Kp, n_meshes, ms, c, c_batch_stride, K, out_spec, in_spec, dims,
                                            elem_bytes, arg, vfinal, total, last,
                                            static_cast<hipStream_t>(stream)));
@@ -276,6 +284,7 @@ size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or
         return scan != 0 ? scan : rh::gang_workspace_bytes(B, N_or_L, Kp_or_S);
     }
     if (which == RH_WS_MINPLUS_CHAIN_SEGMENTED) return rh::scan_workspace_bytes(B, N_or_L, Kp_or_S);
+    if (which == RH_WS_MINPLUS_CHAIN_SPECS) return rh::scan_specs_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_STAGE_DP) {
         if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);
@@ -315,6 +324,6 @@ const char* rh_strerror(int code) {
 
 int rh_gang_workgroups(int32_t B, int32_t compute_units) { return rh::gang_workgroups(B, compute_units); }
 
-int rh_version(void) { return 101; }
+int rh_version(void) { return 102; }
 
 }  // extern "C"

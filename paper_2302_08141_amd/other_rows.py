@@ -29,7 +29,7 @@ def _best_ms(fn, reps=3):
     return best
 
 
-def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
+def _memory_sweep_rows(g, R, dev, n_k=16, k0=176):
     """Memory-constrained search on the graph: n_k values of k as one chain batch sharing the edge tables."""
     N, Kp = g["N"], g["Kp"]
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -41,7 +41,7 @@ def _memory_sweep_rows(g, R, dev, n_k=16, k0=184):
     plan = torch.empty((n_k, N), dtype=torch.int32, device=dev)
     plan_mem = torch.empty(n_k, dtype=torch.int64, device=dev)
     first = torch.empty(1, dtype=torch.int32, device=dev)
-    limit = 64 << 30
+    limit = 1 << 40                               # per-device parameter memory; the sweep ends at k = 186
     times = {}
     # the chain batch spread over eight workgroups per problem, and (these tables are sparse: a third of the slots
     # are valid layouts) all problems through the segmented route
@@ -86,6 +86,20 @@ def _fused_rows(g, dev):
                                                        total, last), reps=2)
         cells = B * (N - 1) * Kp * Kp
         out[f"B{B}"] = {"ms": t, "cells_per_s": cells / (t * 1e-3), "tables_not_stored_gb": cells * 8 / 1e9}
+    # the segmented route with every table entry computed from the spec words (no table in memory either)
+    for B in (1, len(shapes)):
+        meshes = [rh.Mesh.make(shapes[(p + len(shapes) // 2) % len(shapes)], g["bw_bytes_per_us"], g["alpha_ns"])
+                  for p in range(B)]
+        c = to(g["c"][None]).repeat(B, 1, 1).contiguous()
+        arg = torch.empty((B, N - 1, Kp), dtype=torch.int16, device=dev)
+        total = torch.empty(B, dtype=torch.int64, device=dev)
+        last = torch.empty(B, dtype=torch.int32, device=dev)
+        ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SPECS, B, N, Kp), dtype=torch.uint8, device=dev)
+        t = _best_ms(lambda: rh.rh_minplus_chain_specs(B, N, Kp, meshes, c, N * Kp, K, osp, isp, dims, eb, arg, None,
+                                                       total, last, ws), reps=3)
+        out[f"B{B}_segmented_from_specs_ms"] = t
+        seg_totals = [int(x) for x in total.tolist()]
+        del ws
     # the same 11 mesh shapes by the other route: build every mesh's tables, then the segmented chains
     B = len(shapes)
     meshes = [rh.Mesh.make(shapes[(p + B // 2) % B], g["bw_bytes_per_us"], g["alpha_ns"]) for p in range(B)]
@@ -103,6 +117,8 @@ def _fused_rows(g, dev):
 
     out["B11_tables_then_segmented_chains_ms"] = _best_ms(with_tables, reps=2)
     out["B11_totals_ns"] = [int(x) for x in total.tolist()]
+    if out["B11_totals_ns"] != seg_totals:
+        raise RuntimeError("the two routes over the 11 mesh shapes disagree")
     return out
 
 
@@ -126,6 +142,18 @@ def _graph_rows(g, dev):
     t_chain = _best_ms(lambda: rh.rh_minplus_chain(1, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, None, total, last,
                                                    ws))
     t_back = _best_ms(lambda: rh.rh_backtrack(1, N, Kp, arg, last, plan))
+    table_total = int(total.item())
+    # tables and chain in one go, against the segmented route that computes the entries from the spec words
+    def tables_then_chain():
+        rh.rh_build_reshard(mesh, N - 1, Kp, K, osp, isp, dims, eb, R)
+        rh.rh_minplus_chain(1, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, None, total, last, ws)
+    t_both = _best_ms(tables_then_chain)
+    ws_s = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SPECS, 1, N, Kp), dtype=torch.uint8, device=dev)
+    t_specs = _best_ms(lambda: rh.rh_minplus_chain_specs(1, N, Kp, [mesh], c, N * Kp, K, osp, isp, dims, eb, arg, None,
+                                                         total, last, ws_s))
+    if int(total.item()) != table_total:
+        raise RuntimeError("the chain from specs disagrees with the chain over the tables")
+    del ws_s
     cells = (N - 1) * Kp * Kp
     extra = {"memory_sweep": _memory_sweep_rows(g, R, dev), "fused_no_tables": _fused_rows(g, dev)} if Kp == 256 else {}
     return {**extra, "N": N, "K": Kp, "mesh": list(g["m"]), "total_ns": int(total.item()),
@@ -134,6 +162,7 @@ def _graph_rows(g, dev):
             "chain_method": "segments: matrices, boundary vectors, batched sweep" if ws_bytes else "one workgroup",
             "chain_ms": t_chain, "chain_cells_per_s": cells / (t_chain * 1e-3),
             "chain_hbm_gbps": cells * 8 * (1 + 1.25 / Kp) / (t_chain * 1e-3) / 1e9,
+            "reshard_then_chain_ms": t_both, "chain_from_specs_segmented_ms": t_specs,
             "backtrack_ms": t_back}
 
 
@@ -171,9 +200,11 @@ def _stage_rows(dev):
     interval = _interval_rows(dev, L, S, K)
     return {"L": L, "S": S, "segment_chain": {"ops": M, "K": K}, "segment_chains_ms": t_seg,
             "interval_stage_times": interval,
-            "stage_dp_ms": t_dp, "stage_dp_cells": cells, "stage_dp_cells_per_s": cells / (t_dp * 1e-3),
-            "stage_dp_256_problems_ms": t_dp_m, "stage_dp_256_problems_cells_per_s": Bm * cells / (t_dp_m * 1e-3),
-            "stage_dp_method": "bisection on the monotone crossing point (exact); cells = size of the full scan",
+            "stage_dp_ms": t_dp, "stage_dp_us_per_stage_count": t_dp * 1e3 / S,
+            "stage_dp_256_problems_ms": t_dp_m, "stage_dp_256_problems_per_s": Bm / (t_dp_m * 1e-3),
+            "stage_dp_method": "bisection on the monotone crossing point (exact, O(S L log L)); one workgroup per "
+                               "problem, bound by one compute unit's vector ALU",
+            "stage_dp_full_scan_cells_not_visited": cells,
             "bottleneck_ns_at_S": int(bott[0, S - 1].item()),
             "window_eps_half_with_transfers_ms": t_win, "window_bottleneck_ns": int(wb.item())}
 

@@ -166,11 +166,28 @@ def test_moe_shaped_graph_full_size():
     assert np.array_equal(got, want)
     c = dev(g["c"][None])
     o_arg, _, o_total, o_last = oracle.chain(g["c"][None], want[None])
-    for workspace in (False, True):                          # one workgroup, then eight, on the one chain
+    o_plan = oracle.backtrack(o_arg, o_last)
+    for workspace in (False, True):                          # one workgroup, then cut into segments
         arg, total, last, plan = gpu_chain(c, R, 1, N, Kp, workspace=workspace)
         assert total.item() == o_total[0] < INF and last.item() == o_last[0]
         assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
-        assert np.array_equal(plan.cpu().numpy(), oracle.backtrack(o_arg, o_last))
+        assert np.array_equal(plan.cpu().numpy(), o_plan)
+    # and without any table in memory: every entry computed from the spec words, the chain cut into segments
+    del R
+    arg = torch.full((1, N - 1, Kp), -1, dtype=torch.int16, device=DEV)
+    total = torch.zeros(1, dtype=torch.int64, device=DEV)
+    last = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    plan = torch.full((1, N), -1, dtype=torch.int32, device=DEV)
+    ws = torch.full((rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SPECS, 1, N, Kp),), 0x11, dtype=torch.uint8, device=DEV)
+    assert ws.numel() > 0
+    rh.rh_minplus_chain_specs(1, N, Kp, [rh.Mesh.make(g["m"], g["bw_bytes_per_us"], g["alpha_ns"])], c, N * Kp,
+                              dev(g["K"]), dev(g["out_spec"].view(np.int32)), dev(g["in_spec"].view(np.int32)),
+                              dev(g["dims"]), dev(g["elem_bytes"]), arg, None, total, last, ws)
+    rh.rh_backtrack(1, N, Kp, arg, last, plan)
+    torch.cuda.synchronize()
+    assert total.item() == o_total[0] and last.item() == o_last[0]
+    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+    assert np.array_equal(plan.cpu().numpy(), o_plan)
 
 
 def test_stage_partition_with_per_segment_chains():

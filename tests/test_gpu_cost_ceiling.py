@@ -111,15 +111,18 @@ def test_spec_route_at_the_cost_ceiling():
     o_arg, o_vf, o_total, o_last = oracle.chain(c, R[None])
     assert N_MAX * (TOP - 1024) <= o_total[0] < INF         # 2^50 and more
 
-    arg = torch.full((1, N_MAX - 1, Kp), -1, dtype=torch.int16, device=DEV)
-    vfinal = torch.zeros((1, Kp), dtype=torch.int64, device=DEV)
-    total = torch.zeros(1, dtype=torch.int64, device=DEV)
-    last = torch.full((1,), -1, dtype=torch.int32, device=DEV)
     d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
-    rh.rh_minplus_chain_specs(1, N_MAX, Kp, [rh.Mesh.make(*mesh)], d(c), N_MAX * Kp, d(g["K"]),
-                              d(g["out_spec"].view(np.int32)), d(g["in_spec"].view(np.int32)), d(g["dims"]),
-                              d(g["elem_bytes"]), arg, vfinal, total, last)
-    torch.cuda.synchronize()
-    assert total.item() == o_total[0] and last.item() == o_last[0]
-    assert np.array_equal(vfinal.cpu().numpy(), o_vf)
-    assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
+    need = rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN_SPECS, 1, N_MAX, Kp)
+    assert need > 0
+    for ws in (None, torch.full((need,), 0x2E, dtype=torch.uint8, device=DEV)):   # edge by edge, then in segments
+        arg = torch.full((1, N_MAX - 1, Kp), -1, dtype=torch.int16, device=DEV)
+        vfinal = torch.zeros((1, Kp), dtype=torch.int64, device=DEV)
+        total = torch.zeros(1, dtype=torch.int64, device=DEV)
+        last = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+        rh.rh_minplus_chain_specs(1, N_MAX, Kp, [rh.Mesh.make(*mesh)], d(c), N_MAX * Kp, d(g["K"]),
+                                  d(g["out_spec"].view(np.int32)), d(g["in_spec"].view(np.int32)), d(g["dims"]),
+                                  d(g["elem_bytes"]), arg, vfinal, total, last, ws)
+        torch.cuda.synchronize()
+        assert total.item() == o_total[0] and last.item() == o_last[0], ws is None
+        assert np.array_equal(vfinal.cpu().numpy(), o_vf)
+        assert np.array_equal(arg.cpu().numpy().view(np.uint16), o_arg)
