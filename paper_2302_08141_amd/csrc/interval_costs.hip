@@ -12,22 +12,31 @@
 // is 2^52 - 1 (so that the conversion from int64 is an OR and a subtraction); feasible sums stay
 // below 2^51 (at most 2^15 terms below 2^36), so the two thresholds cut at the same place.
 //
-// Mapping: a lane owns Kp/64 columns b; a wave keeps one row (start) in registers and
-// broadcasts V[row][a] with two v_readlane per a, so the broadcast operand travels in scalar
-// registers.  A workgroup (16 waves, 16 rows) stages R_l through LDS in 32 KiB pieces, converted
-// to fp64 on the way in, double buffered.  A workgroup takes a block of neighbouring rows and walks the
+// Mapping for Kp other than 64: a lane owns Kp/64 columns b; a wave keeps one row (start) in registers and
+// broadcasts V[row][a] with two v_readlane per a, so the broadcast operand travels in scalar registers.
+// Mapping at Kp = 64: the four rows of 16 lanes of a wave take different a at the same time (a = 4 n + r in step n
+// for lanes 16 r .. 16 r + 15): one v_mov_b64_dpp row_newbcast per row and step hands V[row][a] to the 16
+// lanes, each of which then relaxes four columns (j, j + 16, j + 32, j + 48); the four partial minima per
+// column meet once per edge through two lane exchanges.  Per 256 cells that is 9 vector instructions instead of
+// 16.  A wave keeps one row when every row walks its own number of edges (so that eight waves share a table),
+// two neighbouring rows when the rows are of limited length.
+// A workgroup stages R_l through LDS in 32 KiB pieces, converted to fp64 on the way in, double buffered, each
+// piece asked for two pieces ahead.  At Kp = 64 four further waves do nothing but stage, so that fetching and
+// converting run beside the arithmetic of the row waves instead of in turn with it.
+// A workgroup takes a block of neighbouring rows and walks the
 // edges they need, so that all its waves are busy together.  With a limit of at most half the chain
 // (no stage longer than max_len operators: the sweep of row i stops after max_len operators and the
 // rest of the row is infeasible) every block of 16 rows walks max_len + 15 edges: equal work, one
-// block per workgroup of 16 waves.  Without such a limit the block that starts at operator i walks
-// L - i edges, a triangle: then blocks have 8 rows, a workgroup of 8 waves takes block b and
+// block per workgroup.  Without such a limit the block that starts at operator i walks
+// L - i edges, a triangle: then blocks have 8 rows, a workgroup takes block b and
 // afterwards block (last - b), and every workgroup walks L + 8 edges.
 #include "kernels.h"
+
+#include <type_traits>
 
 namespace rh {
 namespace {
 
-constexpr int kIcSlots = 1;                  // rows per wave
 constexpr int kPiece = 4096;                 // elements of R per LDS buffer
 constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
 
@@ -53,6 +62,20 @@ __device__ __forceinline__ int64_t to_i64(double m) { return m >= kInfD ? kInf :
 __device__ __forceinline__ double bcast(double x, int lane) {
     const int lo = __builtin_amdgcn_readlane(__double2loint(x), lane);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(x), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// x of lane N of this lane's row of 16 lanes (one v_mov_b64_dpp)
+template <int N>
+__device__ __forceinline__ double row_bcast(double x) {
+    const long long v = __double_as_longlong(x);
+    return __longlong_as_double(__builtin_amdgcn_update_dpp(v, v, 0x150 + N, 0xF, 0xF, false));
+}
+
+// x of another lane of the wave
+__device__ __forceinline__ double from_lane(double x, int lane) {
+    const int lo = __builtin_amdgcn_ds_bpermute(lane << 2, __double2loint(x));
+    const int hi = __builtin_amdgcn_ds_bpermute(lane << 2, __double2hiint(x));
     return __hiloint2double(hi, lo);
 }
 
@@ -83,10 +106,10 @@ struct Shape {
 };
 
 // acc[q][k] = min(acc[q][k], V[q][a] + R[a][col + 64 k]) for the CH rows a of one piece
-template <int KP, int NA>
+template <int KP, int NA, int SLOTS>
 __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, int col, int ch,
-                                            const double (&V)[kIcSlots][Shape<KP>::CPT],
-                                            double (&acc)[kIcSlots][Shape<KP>::CPT]) {
+                                            const double (&V)[SLOTS][Shape<KP>::CPT],
+                                            double (&acc)[SLOTS][Shape<KP>::CPT]) {
     using G = Shape<KP>;
     const int a0 = ch * G::CH;
     const int k_src = a0 >> 6, lane0 = a0 & 63;    // V[q][a] sits in register k_src, lane a mod 64
@@ -116,7 +139,7 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
         first = 0;
     }
     // eight rows a at a time: their R values are fetched while the eight before them are worked on
-    constexpr int AB = G::CPT >= 4 ? 4 : 8;
+    constexpr int AB = G::CPT >= 4 ? 2 : 8;
     static_assert(G::CH % AB == 0, "piece height");
     double r[2][AB][G::CPT];
 #pragma unroll
@@ -149,20 +172,84 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
     }
 }
 
-// WAVES waves = WAVES rows per block; the workgroup takes block blockIdx.x and, if PASSES == 2, block
-// n_blocks - 1 - blockIdx.x after it.
-template <int KP, int WAVES, int PASSES>
-__global__ void __launch_bounds__(WAVES * 64)
+// Kp = 64, the whole table of an edge in one piece: acc[q][0] = min(acc[q][0], min_a V[q][a] + piece[a][lane]) for
+// the first NA of the wave's two rows.  Lane 16 r + j: in step n its row of 16 lanes works on a = 4 n + r, and the
+// lane relaxes columns j + 16 (k ^ r), k = 0..3 (the exclusive-or spreads the four rows of lanes over the LDS
+// banks); its partial minimum for column j + 16 (k ^ r) is acc4[k].
+template <int NA, int SLOTS>
+__device__ __forceinline__ void relax_rows64(const double* __restrict__ piece, int lane, const double (&V)[SLOTS][1],
+                                             double (&acc)[SLOTS][1]) {
+    const int r = lane >> 4, j = lane & 15;
+    double src[NA], acc4[NA][4];
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+        src[q] = from_lane(V[q][0], 4 * j + r);    // lane 16 r + n holds V[q][4 n + r]
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc4[q][k] = kInfD;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const double* base = piece + r * 64 + j;
+    // The values of three steps are on their way from LDS while one step is worked on (a wave may have a SIMD to
+    // itself here, so nothing else covers the trip): the registers of a step are refilled for three steps later
+    // as soon as they have been used, and the scheduler is told to keep that order.
+    double x[3][4];
+    auto load = [&](double (&xs)[4], int n) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xs[k] = base[(4 * n) * 64 + 16 * (k ^ r)];
+    };
+    auto step = [&](auto n_tag) {
+        constexpr int N = decltype(n_tag)::value;
+        double (&xs)[4] = x[N % 3];
+#pragma unroll
+        for (int q = 0; q < NA; ++q) {
+            const double sv = row_bcast<N>(src[q]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc4[q][k] = __builtin_fmin(acc4[q][k], xs[k] + sv);
+        }
+        if constexpr (N + 3 < 16) load(xs, N + 3);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    load(x[0], 0);
+    load(x[1], 1);
+    load(x[2], 2);
+    __builtin_amdgcn_sched_barrier(0);
+    step(std::integral_constant<int, 0>{});  step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});  step(std::integral_constant<int, 3>{});
+    step(std::integral_constant<int, 4>{});  step(std::integral_constant<int, 5>{});
+    step(std::integral_constant<int, 6>{});  step(std::integral_constant<int, 7>{});
+    step(std::integral_constant<int, 8>{});  step(std::integral_constant<int, 9>{});
+    step(std::integral_constant<int, 10>{}); step(std::integral_constant<int, 11>{});
+    step(std::integral_constant<int, 12>{}); step(std::integral_constant<int, 13>{});
+    step(std::integral_constant<int, 14>{}); step(std::integral_constant<int, 15>{});
+    // Column 16 r + j (this lane's own) is acc4[0] here, acc4[1] in the lane 16 further (its r differs in bit 0),
+    // acc4[2] and acc4[3] in the lanes 32 and 48 further: fold the four rows of lanes.
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+        const double a0 = __builtin_fmin(acc4[q][0], from_lane(acc4[q][1], lane ^ 16));
+        const double a2 = __builtin_fmin(acc4[q][2], from_lane(acc4[q][3], lane ^ 16));
+        acc[q][0] = __builtin_fmin(acc[q][0], __builtin_fmin(a0, from_lane(a2, lane ^ 32)));
+    }
+}
+
+// WAVES waves of SLOTS rows each = WAVES * SLOTS rows per block (wave w keeps rows SLOTS w .. SLOTS w + SLOTS - 1 of
+// the block); the workgroup takes block blockIdx.x and, if PASSES == 2, block n_blocks - 1 - blockIdx.x after it.
+// STAGERS = 0: every wave takes part in staging the tables.  STAGERS > 0: that many further waves do nothing but
+// stage (fetch, convert, store to LDS) while the WAVES row waves do nothing but relax, so that the memory side and
+// the arithmetic of an edge run side by side instead of one after the other in every wave.
+template <int KP, int WAVES, int PASSES, int SLOTS, int STAGERS>
+__global__ void __launch_bounds__((WAVES + STAGERS) * 64)
 interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
                       const int64_t* __restrict__ c, int64_t c_bs, const int64_t* __restrict__ R, int64_t R_bs,
                       int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
     using G = Shape<KP>;
-    constexpr int kThreads = WAVES * 64;
+    constexpr int kThreads = (STAGERS > 0 ? STAGERS : WAVES) * 64;         // threads that stage
     constexpr int EPT = G::ELEMS / kThreads > 0 ? G::ELEMS / kThreads : 1;   // elements of a piece per thread
     extern __shared__ double lds[];               // two pieces of kPiece doubles
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const bool stages = STAGERS == 0 || wave >= WAVES;                      // wave-uniform
+    const bool has_rows = wave < WAVES;
+    const int tid = STAGERS > 0 ? (int)threadIdx.x - WAVES * 64 : (int)threadIdx.x;   // index among the staging threads
     c += (int64_t)blockIdx.y * c_bs;
     R += (int64_t)blockIdx.y * R_bs;
     T += (int64_t)blockIdx.y * T_bs;
@@ -175,102 +262,121 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
     if (pass > 0 && block <= (int)blockIdx.x) break;      // an odd number of blocks: the middle one has no partner
     lds_barrier();                                // the pass before has read its last piece
 
-    // rows of this wave: slot q holds start block * WAVES + wave (kIcSlots is 1)
-    int row[kIcSlots];
+    // rows of this wave: slot q holds the start block * WAVES * SLOTS + wave * SLOTS + q
+    int row[SLOTS];
 #pragma unroll
-    for (int q = 0; q < kIcSlots; ++q) row[q] = block * WAVES + wave;
+    for (int q = 0; q < SLOTS; ++q) row[q] = has_rows ? (block * WAVES + wave) * SLOTS + q : L;   // L: never starts
 
     // entries at and left of the diagonal, and those of stages longer than max_len operators
 #pragma unroll
-    for (int q = 0; q < kIcSlots; ++q) {
+    for (int q = 0; q < SLOTS; ++q) {
         if (row[q] < L)
             for (int j = lane; j <= L; j += 64)
                 if (j <= row[q] || j - row[q] > max_len) T[(int64_t)row[q] * ldT + j] = kInf;
     }
 
-    const int l0 = block * WAVES;                 // the first row of this block starts at operator l0
+    constexpr int kRows = WAVES * SLOTS;          // rows of a block
+    const int l0 = block * kRows;                 // the first row of this block starts at operator l0
     // the last operator any row of this block reaches: its highest row, max_len operators on, or the chain's end
-    const int row_hi = l0 + WAVES - 1 < L - 1 ? l0 + WAVES - 1 : L - 1;
+    const int row_hi = l0 + kRows - 1 < L - 1 ? l0 + kRows - 1 : L - 1;
     const int l_last = row_hi + max_len - 1 < L - 1 ? row_hi + max_len - 1 : L - 1;
     const int n_edges = l_last - l0;              // edges l0 .. l_last - 1
     const int n_pieces = n_edges * G::NCH;
 
-    // piece g = (edge l0 + g / NCH, rows a of piece g % NCH); the pieces of one edge are contiguous in R
-    int64_t pre[EPT];
-    auto fetch = [&](int g) {
+    // piece g = (edge l0 + g / NCH, rows a of piece g % NCH); the pieces of one edge are contiguous in R.
+    // A piece is asked for two pieces before it is used and waits in registers (two sets, taken in turn) until
+    // its predecessor is being used, when it is converted and stored to LDS: one trip to memory takes about as
+    // long as two edges.  Every load is unconditional (a piece past the end repeats the last one) so that the waits
+    // count the loads still under way instead of draining them.
+    struct Raw {
+        int64_t r[EPT];
+    };
+    Raw preA, preB;
+    auto fetch = [&](int g, Raw& pre) {
+        g = g < n_pieces ? g : n_pieces - 1;
         const int64_t* src = R + ((int64_t)l0 * KP * KP + (int64_t)g * G::ELEMS);
         if constexpr (EPT >= 2) {
             typedef long long ll2 __attribute__((ext_vector_type(2)));
 #pragma unroll
             for (int e = 0; e < EPT / 2; ++e) {
                 const ll2 v = *reinterpret_cast<const ll2*>(src + 2 * (e * kThreads + tid));
-                pre[2 * e] = v.x;
-                pre[2 * e + 1] = v.y;
+                pre.r[2 * e] = v.x;
+                pre.r[2 * e + 1] = v.y;
             }
         } else {
-            pre[0] = tid < G::ELEMS ? src[tid] : 0;
+            pre.r[0] = src[tid < G::ELEMS ? tid : 0];
         }
     };
-    auto stash = [&](int g) {
+    auto stash = [&](int g, const Raw& pre) {
         double* dst = lds + (g & 1) * kPiece;
         if constexpr (EPT >= 2) {
 #pragma unroll
             for (int e = 0; e < EPT / 2; ++e) {
                 const int at = 2 * (e * kThreads + tid);
-                dst[at] = to_f64(pre[2 * e]);
-                dst[at + 1] = to_f64(pre[2 * e + 1]);
+                dst[at] = to_f64(pre.r[2 * e]);
+                dst[at + 1] = to_f64(pre.r[2 * e + 1]);
             }
         } else {
-            if (tid < G::ELEMS) dst[tid] = to_f64(pre[0]);
+            if (tid < G::ELEMS) dst[tid] = to_f64(pre.r[0]);
         }
     };
-    if (n_pieces > 0) {
-        fetch(0);
-        stash(0);
+    if (n_pieces > 0 && stages) {
+        fetch(0, preA);
+        fetch(1, preB);
+        stash(0, preA);
     }
     lds_barrier();
 
-    // node costs of operators l and l+1 in this lane's columns; operator l+2 on its way
+    // node costs of operators l and l+1 in this lane's columns; operators l+2 and l+3 on their way
     double cA[G::CPT], cB[G::CPT];
-    int64_t cC[G::CPT];
+    int64_t cC[G::CPT], cD[G::CPT];
     auto load_c = [&](int l, int k) -> int64_t {
-        return (l < L && live_lane) ? c[(int64_t)l * KP + col + 64 * k] : kInf;
+        const int64_t x = c[(int64_t)(l < L ? l : L - 1) * KP + col + 64 * k];
+        return (l < L && live_lane) ? x : kInf;
     };
 #pragma unroll
     for (int k = 0; k < G::CPT; ++k) {
         cA[k] = to_f64(load_c(l0, k));
         cB[k] = to_f64(load_c(l0 + 1, k));
         cC[k] = load_c(l0 + 2, k);
+        cD[k] = kInf;
     }
 
-    double V[kIcSlots][G::CPT];
+    double V[SLOTS][G::CPT], acc[SLOTS][G::CPT];
 #pragma unroll
-    for (int q = 0; q < kIcSlots; ++q)
+    for (int q = 0; q < SLOTS; ++q)
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) V[q][k] = kInfD;
+        for (int k = 0; k < G::CPT; ++k) {
+            V[q][k] = kInfD;
+            acc[q][k] = kInfD;
+        }
 
-    double tcol[kIcSlots];                        // finished columns of T waiting for their store
+    double tcol[SLOTS];                           // finished columns of T waiting for their store
+    bool running[SLOTS];                          // rows under way: started, not yet max_len operators long
 #pragma unroll
-    for (int q = 0; q < kIcSlots; ++q) tcol[q] = kInfD;
+    for (int q = 0; q < SLOTS; ++q) {
+        tcol[q] = kInfD;
+        running[q] = false;
+    }
 
-    int g = 0;
-    for (int l = l0; l <= l_last; ++l) {
-        int n_act = 0;                            // rows under way: started (they start in slot order), not yet max_len long
-        static_assert(kIcSlots == 1, "a finished row in slot 0 beside a running one in slot 1 has no case below");
+    // What happens when the sweeps arrive at operator l: rows that start here take its node costs; every row
+    // under way gets its entry T[row][l+1] = cheapest strategy of operator l for the chain row..l.  Lane j mod 64
+    // keeps column j; a full block of 64 columns (or the last, partial one) leaves as one coalesced store.
+    auto arrive = [&](int l) {
 #pragma unroll
-        for (int q = 0; q < kIcSlots; ++q) {
+        for (int q = 0; q < SLOTS; ++q) {
             if (row[q] == l) {
 #pragma unroll
                 for (int k = 0; k < G::CPT; ++k) V[q][k] = cA[k];
             }
-            n_act += (row[q] <= l && l - row[q] < max_len) ? 1 : 0;
+            // (the rows of a wave start one after the other and stop one after the other, so with two slots the
+            // cases are: 0 alone, both, 1 alone)
+            running[q] = row[q] <= l && l - row[q] < max_len;     // wave-uniform
         }
-        // T[row][l+1] = cheapest strategy of operator l for the chain row..l.  Lane j mod 64 keeps column
-        // j; a full block of 64 columns (or the last, partial one) leaves as one coalesced store.
         const int j = l + 1;
 #pragma unroll
-        for (int q = 0; q < kIcSlots; ++q) {
-            if (q < n_act) {
+        for (int q = 0; q < SLOTS; ++q) {
+            if (running[q]) {
                 double m = V[q][0];
 #pragma unroll
                 for (int k = 1; k < G::CPT; ++k) m = __builtin_fmin(m, V[q][k]);
@@ -282,47 +388,61 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
                 }
             }
         }
-        if (l == l_last) break;
-
-        // node costs three operators ahead: asked for now, so that the arithmetic below covers the trip
-        int64_t cD[G::CPT];
+    };
+    // one piece: `mine` held piece g (it is in LDS by now) and takes piece g + 2, `next` holds piece g + 1
+    auto one_piece = [&](int g, Raw& mine, const Raw& next) {
+        const int e = g / G::NCH, ch = g - e * G::NCH;
+        const int l = l0 + e;
+        if (ch == 0 && has_rows) {
+            arrive(l);
+            // node costs three operators ahead: asked for now, so that the arithmetic below covers the trip
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) cD[k] = load_c(l + 3, k);
-
-        double acc[kIcSlots][G::CPT];
+            for (int k = 0; k < G::CPT; ++k) cD[k] = load_c(l + 3, k);
 #pragma unroll
-        for (int q = 0; q < kIcSlots; ++q)
+            for (int q = 0; q < SLOTS; ++q)
 #pragma unroll
-            for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
-        for (int ch = 0; ch < G::NCH; ++ch, ++g) {
-            const bool more = g + 1 < n_pieces;
-            if (more) fetch(g + 1);               // in flight during the arithmetic
-            const double* piece = lds + (g & 1) * kPiece;
-            static_assert(kIcSlots <= 2, "one case per number of live rows");
-            if (n_act == 1) relax_piece<KP, 1>(piece, col, ch, V, acc);
-            if constexpr (kIcSlots == 2) {
-                if (n_act == 2) relax_piece<KP, 2>(piece, col, ch, V, acc);
-            }
-            if (more) stash(g + 1);
-            lds_barrier();                        // piece g+1 is in LDS; piece g has been read for the last time
+                for (int k = 0; k < G::CPT; ++k) acc[q][k] = kInfD;
         }
+        if (stages) fetch(g + 2, mine);
+        const double* piece = lds + (g & 1) * kPiece;
+        if constexpr (KP == 64) {
+            if constexpr (SLOTS == 2) {
+                // (slot 1 alone: slot 0 has stopped and is relaxed along with it, its results are not used)
+                if (running[1]) relax_rows64<2, SLOTS>(piece, lane, V, acc);
+                else if (running[0]) relax_rows64<1, SLOTS>(piece, lane, V, acc);
+            } else {
+                if (running[0]) relax_rows64<1, SLOTS>(piece, lane, V, acc);
+            }
+        } else {
+            static_assert(SLOTS == 1 || KP == 64, "two rows per wave only in the Kp = 64 layout");
+            if (running[0]) relax_piece<KP, 1, SLOTS>(piece, col, ch, V, acc);
+        }
+        if (stages && g + 1 < n_pieces) stash(g + 1, next);
+        lds_barrier();                            // piece g+1 is in LDS; piece g has been read for the last time
+        if (ch == G::NCH - 1 && has_rows) {                   // the edge is done: on to the operator it arrives at
 #pragma unroll
-        for (int q = 0; q < kIcSlots; ++q) {
-            if (q < n_act) {
+            for (int q = 0; q < SLOTS; ++q) {
+                if (running[q]) {
 #pragma unroll
-                for (int k = 0; k < G::CPT; ++k) {
-                    const double m = __builtin_fmin(acc[q][k], kInfD);
-                    V[q][k] = __builtin_fmin(cB[k] + m, kInfD);
+                    for (int k = 0; k < G::CPT; ++k) {
+                        const double m = __builtin_fmin(acc[q][k], kInfD);
+                        V[q][k] = __builtin_fmin(cB[k] + m, kInfD);
+                    }
                 }
             }
-        }
 #pragma unroll
-        for (int k = 0; k < G::CPT; ++k) {
-            cA[k] = cB[k];
-            cB[k] = to_f64(cC[k]);
-            cC[k] = cD[k];
+            for (int k = 0; k < G::CPT; ++k) {
+                cA[k] = cB[k];
+                cB[k] = to_f64(cC[k]);
+                cC[k] = cD[k];
+            }
         }
+    };
+    for (int g = 0; g < n_pieces; g += 2) {
+        one_piece(g, preA, preB);
+        if (g + 1 < n_pieces) one_piece(g + 1, preB, preA);
     }
+    if (has_rows) arrive(l_last);                 // the entries of the last operator
   }
 }
 
@@ -334,30 +454,36 @@ hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_l
     if (B == 0) return hipSuccess;
     if (max_len > L) max_len = L;
     // short stages only: blocks of 16 rows, equal work, one per workgroup; else blocks of 8 rows, a long one and a
-    // short one per workgroup
+    // short one per workgroup.  At Kp = 64: 8 waves of two rows, or 8 waves of one row, and four staging waves.
     const bool equal_blocks = max_len <= L / 2;
     const size_t lds = 2 * kPiece * sizeof(double);
-#define RH_IC(KP, WAVES, PASSES)                                                                                   \
+#define RH_IC(KP, WAVES, PASSES, SLOTS, STAGERS)                                                                            \
     do {                                                                                                           \
-        const int n_blocks = (L + (WAVES)-1) / (WAVES);                                                            \
+        const int n_blocks = (L + (WAVES) * (SLOTS)-1) / ((WAVES) * (SLOTS));                                      \
         const dim3 grid((unsigned)((n_blocks + (PASSES)-1) / (PASSES)), (unsigned)B);                              \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(interval_costs_kernel<KP, WAVES, PASSES>),        \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(interval_costs_kernel<KP, WAVES, PASSES, SLOTS, STAGERS>), \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                  \
         if (e != hipSuccess) return e;                                                                             \
-        hipLaunchKernelGGL((interval_costs_kernel<KP, WAVES, PASSES>), grid, dim3((WAVES)*64), lds, stream, L, max_len,    \
-                           n_blocks, c, c_bs, R, R_bs, ldT, T, T_bs);                                              \
+        hipLaunchKernelGGL((interval_costs_kernel<KP, WAVES, PASSES, SLOTS, STAGERS>), grid,                       \
+                           dim3(((WAVES) + (STAGERS)) * 64), lds, stream, L,                                       \
+                           max_len, n_blocks, c, c_bs, R, R_bs, ldT, T, T_bs);                                     \
     } while (0)
 #define RH_IC_KP(KP)                                                                                               \
     do {                                                                                                           \
         if (equal_blocks)                                                                                          \
-            RH_IC(KP, 16, 1);                                                                                      \
+            RH_IC(KP, 16, 1, 1, 0);                                                                                   \
         else                                                                                                       \
-            RH_IC(KP, 8, 2);                                                                                       \
+            RH_IC(KP, 8, 2, 1, 0);                                                                                    \
     } while (0)
     switch (Kp) {
         case 16: RH_IC_KP(16); break;
         case 32: RH_IC_KP(32); break;
-        case 64: RH_IC_KP(64); break;
+        case 64:
+            if (equal_blocks)
+                RH_IC(64, 8, 1, 2, 4);
+            else
+                RH_IC(64, 8, 2, 1, 4);
+            break;
         case 128: RH_IC_KP(128); break;
         case 256: RH_IC_KP(256); break;
         default: return hipErrorInvalidValue;
