@@ -119,6 +119,24 @@ def cone(branches, c_root: np.ndarray):
     return table, int(total[0]), int(choice[0]), plans
 
 
+def tree(parent: np.ndarray, c: np.ndarray, R: np.ndarray):
+    """In-tree DP: parent int32[n] (parent[i] > i, root n-1 has -1), c[n][Kp], R[n-1][Kp][Kp] (edge i -> parent[i],
+    row = strategy of i) -> table[Kp], total, root_choice, plan int32[n], arg uint16[n-1][Kp]."""
+    _chk(parent, np.int32, "parent"); _chk(c, np.int64, "c"); _chk(R, np.int64, "R")
+    n, Kp = c.shape
+    assert parent.shape == (n,) and R.shape == (max(n - 1, 0), Kp, Kp)
+    table = np.zeros(Kp, dtype=np.int64)
+    total = np.zeros(1, dtype=np.int64)
+    choice = np.zeros(1, dtype=np.int32)
+    plan = np.zeros(n, dtype=np.int32)
+    arg = np.zeros((max(n - 1, 0), Kp), dtype=np.uint16)
+    rc = lib().oracle_tree(ctypes.c_int32(n), ctypes.c_int32(Kp), _p(parent), _p(c), _p(R), _p(table), _p(total),
+                           _p(choice), _p(plan), _p(arg))
+    if rc != 0:
+        raise ValueError(f"oracle_tree rc={rc}")
+    return table, int(total[0]), int(choice[0]), plan, arg
+
+
 def memory_sweep(c, R, param_bytes, repl, mem, limit: int, n_k: int, k0: int = 0):
     """c[N][Kp], R[N-1][Kp][Kp], param_bytes int64[N], repl uint8[N][Kp], mem int64[N][Kp] ->
     total[n_k], plan int32[n_k][N], plan_mem[n_k], first (offset of the smallest feasible k, or -1)."""

@@ -210,6 +210,83 @@ int oracle_cone(int32_t n_br, int32_t Kp, const int32_t *len,
 }
 
 /* ------------------------------------------------------------------ */
+/* In-tree: every operator feeds exactly one consumer (its parent) and   */
+/* may have several inputs; the root feeds nobody.  This is the shape of */
+/* a cone whose inner nodes also join several inputs (Sec. 4.3.2, level  */
+/* 1), and the objective is that of Sec. 4.2 with the tree's edges as E: */
+/*   C = sum_i c_i[x_i] + sum_{i != root} R_i[x_i][x_parent(i)]          */
+/* (R_i is the table of the edge from i to its parent: row = strategy of */
+/* i, column = strategy of the parent).  By recursion over the parent    */
+/* array, for a node i:                                                  */
+/*   v_i[a] = c_i[a] + sum over the inputs j of i of w_j[a]              */
+/*   w_i[b] = min_a ( v_i[a] + R_i[a][b] ),  arg_i[b] = lowest such a    */
+/*            (0 if every candidate is infeasible)                       */
+/* with saturating sums; at the root table = v_root, total = its minimum */
+/* at the lowest r; the plan follows the args from the root down.  Nodes */
+/* are numbered so that parent[i] > i (inputs before consumers), the     */
+/* root is node n-1 and has parent -1; the inputs of a node are added in */
+/* ascending order (saturating addition of non-negative costs does not   */
+/* depend on the order).                                                 */
+static void tree_node_vector(int32_t n, int32_t Kp, const int32_t *parent,
+                             const int64_t *c, const int64_t *R, int i,
+                             int64_t *v_all, uint16_t *arg_all)
+{
+    int64_t *v = v_all + (size_t)i * Kp;
+    for (int a = 0; a < Kp; ++a) {
+        const int64_t x = c[(size_t)i * Kp + a];
+        v[a] = x >= ORC_INF ? ORC_INF : x;
+    }
+    for (int j = 0; j < n; ++j) {
+        if (parent[j] != i) continue;
+        /* the input's own vector first (recursion), then what it costs */
+        /* this node per strategy b of this node                        */
+        tree_node_vector(n, Kp, parent, c, R, j, v_all, arg_all);
+        const int64_t *vj = v_all + (size_t)j * Kp;
+        const int64_t *Rj = R + (size_t)j * Kp * Kp;
+        for (int b = 0; b < Kp; ++b) {
+            int64_t best = sat_add(vj[0], Rj[b]);
+            int besta = 0;
+            for (int a = 1; a < Kp; ++a) {
+                const int64_t t = sat_add(vj[a], Rj[(size_t)a * Kp + b]);
+                if (t < best) { best = t; besta = a; }
+            }
+            arg_all[(size_t)j * Kp + b] = (uint16_t)(best >= ORC_INF ? 0 : besta);
+            v[b] = sat_add(v[b], best);
+        }
+    }
+}
+
+/* c[n][Kp], R[n-1][Kp][Kp] (entry i = edge from node i to parent[i]);   */
+/* outputs: table[Kp], *total, *root_choice, plan[n], and optionally     */
+/* arg[n-1][Kp] (may be NULL).  Returns -1 on a malformed parent array.  */
+int oracle_tree(int32_t n, int32_t Kp, const int32_t *parent, const int64_t *c,
+                const int64_t *R, int64_t *table, int64_t *total,
+                int32_t *root_choice, int32_t *plan, uint16_t *arg)
+{
+    if (n < 1 || Kp < 1 || parent[n - 1] != -1) return -1;
+    for (int i = 0; i + 1 < n; ++i)
+        if (parent[i] <= i || parent[i] >= n) return -1;
+    int64_t *v_all = (int64_t *)malloc(sizeof(int64_t) * (size_t)n * Kp);
+    uint16_t *arg_all = (uint16_t *)calloc((size_t)n * Kp, sizeof(uint16_t));
+    tree_node_vector(n, Kp, parent, c, R, n - 1, v_all, arg_all);
+    const int64_t *vr = v_all + (size_t)(n - 1) * Kp;
+    int64_t best = vr[0];
+    int bestr = 0;
+    for (int r = 0; r < Kp; ++r) {
+        table[r] = vr[r];
+        if (vr[r] < best) { best = vr[r]; bestr = r; }
+    }
+    *total = best;
+    *root_choice = best >= ORC_INF ? 0 : bestr;
+    plan[n - 1] = *root_choice;
+    for (int i = n - 2; i >= 0; --i)   /* parent[i] > i: the parent's entry is there already */
+        plan[i] = arg_all[(size_t)i * Kp + plan[parent[i]]];
+    if (arg != NULL) memcpy(arg, arg_all, sizeof(uint16_t) * (size_t)(n - 1) * Kp);
+    free(v_all); free(arg_all);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Memory-constrained search (Sec. 4.4).  Parameters are ranked by size, */
 /* largest first (equal sizes: lower operator index first); for          */
 /* k = k0 .. k0+n_k-1 the candidates that replicate one of the k largest */
