@@ -242,6 +242,59 @@ int rh_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp,
                   int32_t* root_choice, int32_t* branch_last, void* stream);
 
 /*
+ * rh_tree_plan, rh_tree_dp -- the dynamic program over an in-tree of operators: every operator
+ * feeds exactly one consumer (its parent) and may join several inputs; the root feeds nobody.
+ * This is the cone of Sec. 4.3.2 (level 1: given the root's strategy the other nodes are
+ * optimised by dynamic programming, and every root strategy is kept for the next level) when
+ * nodes below the root join several inputs too, with the objective of Sec. 4.2 on the tree's
+ * edges.  With R_i the table of the edge from node i to its parent (row = strategy of i):
+ *     v_i[a] = c_i[a] + sum over the inputs j of i of w_j[a]
+ *     w_i[b] = min_a ( v_i[a] + R_i[a][b] ),  arg_i[b] = the lowest such a (0 if none is feasible)
+ *     table  = v_root,  total = min_r table[r],  root_choice = the lowest such r
+ *     plan[root] = root_choice,  plan[i] = arg_i[ plan[parent(i)] ]
+ * with saturating sums (rh_minplus_chain is the case of a path, rh_cone_merge that of a root
+ * whose inputs are paths).  Nodes are numbered inputs-first: parent[i] > i, node n-1 is the root
+ * and has parent -1.  B problems share the tree (one operator graph searched on several logical
+ * meshes, Sec. 3 / Sec. 4) and differ in their costs.
+ *
+ * rh_tree_plan is host arithmetic (all its pointers are HOST pointers; nothing touches a device).
+ * It cuts the tree into runs -- stretches of consecutive nodes in which every node but the first
+ * has the node before it as its only input, i.e. chains laid out like the operators of
+ * rh_minplus_chain -- and gives every run a round: one more than the highest round among the
+ * runs that feed its first node, 0 if that node has no input.  rh_tree_dp then takes one launch
+ * per round (a workgroup per run and problem) and as many for the plan.
+ *   n             1 <= n <= RH_NMAX
+ *   parent        [n]
+ *   run_first, run_last   [n] out, entries 0 .. *n_runs - 1 used: run u = nodes run_first[u] ..
+ *                 run_last[u]; sorted by round, by first node within a round
+ *   round_start   [n + 1] out: the runs of round t are round_start[t] .. round_start[t+1] - 1
+ *   child_start   [n + 1] out, child_list [n] out: the inputs of node i are
+ *                 child_list[child_start[i] .. child_start[i+1] - 1], ascending
+ *   returns the number of rounds (>= 1), or RH_ERR_SHAPE if parent is not such a tree
+ *
+ * rh_tree_dp: round_start is the HOST array above (read during the call); run_first, run_last,
+ * parent, child_start, child_list are DEVICE copies of the arrays above.
+ *   0 <= B <= 65535
+ *   c       [B][n][Kp], problem p at c + p*c_batch_stride; empty slots hold RH_INF
+ *   R       [B][n-1][Kp][Kp], problem p at R + p*R_batch_stride (0 = one R for all problems);
+ *           may be NULL if n == 1
+ *   arg     [B][n-1][Kp] out
+ *   w       [B][n][Kp] out: w_i for the last node of every run (the other rows are not written),
+ *           row n-1 = table
+ *   total   [B] out;  root_choice [B] out
+ *   plan    [B][n] out, may be NULL (then no plan is made)
+ */
+int rh_tree_plan(int32_t n, const int32_t* parent, int32_t* run_first, int32_t* run_last,
+                 int32_t* round_start, int32_t* child_start, int32_t* child_list,
+                 int32_t* n_runs);
+int rh_tree_dp(int32_t B, int32_t n, int32_t Kp, int32_t n_runs, int32_t n_rounds,
+               const int32_t* round_start, const int32_t* run_first, const int32_t* run_last,
+               const int32_t* parent, const int32_t* child_start, const int32_t* child_list,
+               const int64_t* c, int64_t c_batch_stride, const int64_t* R,
+               int64_t R_batch_stride, uint16_t* arg, int64_t* w, int64_t* total,
+               int32_t* root_choice, int32_t* plan, void* stream);
+
+/*
  * rh_mask_replicated, rh_plan_memory -- the memory-constrained search of Sec. 4.4:
  * sort the parameters by size, mark the k largest, remove the candidates that
  * replicate a marked parameter, search again, and take the smallest k whose plan

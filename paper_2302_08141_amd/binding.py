@@ -61,6 +61,9 @@ def lib():
         L.rh_stage_dp.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_cone_merge.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.rh_cone_merge.restype = ctypes.c_int
+        L.rh_tree_plan.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
+        L.rh_tree_dp.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp]
+        L.rh_tree_plan.restype = L.rh_tree_dp.restype = ctypes.c_int
         L.rh_mask_replicated.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.rh_plan_memory.argtypes = [i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
         L.rh_mask_replicated.restype = L.rh_plan_memory.restype = ctypes.c_int
@@ -190,6 +193,50 @@ def rh_cone_merge(n_cones: int, n_branches: int, Kp: int, branch_start, w, c_roo
                                _ptr(table, torch.int64, "table", q * k), _ptr(total, torch.int64, "total", q),
                                _ptr(root_choice, torch.int32, "root_choice", q),
                                _ptr(branch_last, torch.int32, "branch_last", b), _stream()), "rh_cone_merge")
+
+
+class TreePlan:
+    """What rh_tree_plan returns for one parent array: the host arrays and device copies of those rh_tree_dp reads on
+    the device."""
+
+    def __init__(self, parent, device):
+        import numpy as np
+        parent = np.ascontiguousarray(parent, dtype=np.int32)
+        n = parent.shape[0]
+        self.n = n
+        host = {k: np.zeros(n + 1, dtype=np.int32) for k in ("run_first", "run_last", "round_start", "child_start",
+                                                              "child_list")}
+        n_runs = ctypes.c_int32(0)
+        hp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+        rounds = lib().rh_tree_plan(n, hp(parent), hp(host["run_first"]), hp(host["run_last"]), hp(host["round_start"]),
+                                    hp(host["child_start"]), hp(host["child_list"]), ctypes.byref(n_runs))
+        _check(min(rounds, 0), "rh_tree_plan")
+        self.n_rounds, self.n_runs = rounds, n_runs.value
+        self.host = dict(host, parent=parent)
+        self.round_start = host["round_start"]
+        self.dev = {k: torch.from_numpy(v).to(device) for k, v in self.host.items() if k != "round_start"}
+
+
+def rh_tree_dp(B: int, Kp: int, tp: TreePlan, c, c_batch_stride: int, R, R_batch_stride: int, arg, w, total,
+               root_choice, plan):
+    """tp: TreePlan; c int64[B][n][Kp]; R int64[B][n-1][Kp][Kp] (stride 0 = shared); arg int16[B][n-1][Kp];
+    w int64[B][n][Kp]; total int64[B]; root_choice int32[B]; plan int32[B][n] or None."""
+    n = tp.n
+    b, k = max(B, 0), max(Kp, 0)
+    c_span = (b - 1) * c_batch_stride + n * k if b > 0 else 0
+    r_span = (b - 1) * R_batch_stride + (n - 1) * k * k if b > 0 else 0
+    d = tp.dev
+    _check(lib().rh_tree_dp(B, n, Kp, tp.n_runs, tp.n_rounds, tp.round_start.ctypes.data_as(ctypes.c_void_p),
+                            _ptr(d["run_first"], torch.int32, "run_first", tp.n_runs),
+                            _ptr(d["run_last"], torch.int32, "run_last", tp.n_runs),
+                            _ptr(d["parent"], torch.int32, "parent", n),
+                            _ptr(d["child_start"], torch.int32, "child_start", n + 1),
+                            _ptr(d["child_list"], torch.int32, "child_list", n),
+                            _ptr(c, torch.int64, "c", c_span), c_batch_stride, _ptr(R, torch.int64, "R", r_span),
+                            R_batch_stride, _ptr(arg, torch.int16, "arg", b * (n - 1) * k),
+                            _ptr(w, torch.int64, "w", b * n * k), _ptr(total, torch.int64, "total", b),
+                            _ptr(root_choice, torch.int32, "root_choice", b), _ptr(plan, torch.int32, "plan", b * n),
+                            _stream()), "rh_tree_dp")
 
 
 def rh_mask_replicated(N: int, Kp: int, n_k: int, k0: int, c, param_bytes, repl, c_out):

@@ -71,6 +71,15 @@ hipError_t launch_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp, co
                              const int64_t* w, const int64_t* c_root, int64_t* table, int64_t* total,
                              int32_t* root_choice, int32_t* branch_last, hipStream_t stream);
 
+// In-tree of operators: runs, rounds and input lists on the host, then one launch per round and the backtrack.
+int plan_tree(int32_t n, const int32_t* parent, int32_t* run_first, int32_t* run_last, int32_t* round_start,
+              int32_t* child_start, int32_t* child_list, int32_t* n_runs_out);
+hipError_t launch_tree_dp(int32_t B, int32_t n, int32_t Kp, int32_t n_rounds, const int32_t* round_start,
+                          const int32_t* run_first, const int32_t* run_last, const int32_t* parent,
+                          const int32_t* child_start, const int32_t* child_list, const int64_t* c, int64_t c_bs,
+                          const int64_t* R, int64_t R_bs, uint16_t* arg, int64_t* w, int64_t* total,
+                          int32_t* root_choice, int32_t* plan, hipStream_t stream);
+
 hipError_t launch_mask_replicated(int32_t N, int32_t Kp, int32_t n_k, int32_t k0, const int64_t* c,
                                   const int64_t* param_bytes, const uint8_t* repl, int64_t* c_out,
                                   hipStream_t stream);

@@ -168,6 +168,38 @@ int rh_cone_merge(int32_t n_cones, int32_t n_branches, int32_t Kp, const int32_t
                                           root_choice, branch_last, static_cast<hipStream_t>(stream)));
 }
 
+int rh_tree_plan(int32_t n, const int32_t* parent, int32_t* run_first, int32_t* run_last, int32_t* round_start,
+                 int32_t* child_start, int32_t* child_list, int32_t* n_runs) {
+    if (n < 1 || n > RH_NMAX) return RH_ERR_SHAPE;
+    if (!parent || !run_first || !run_last || !round_start || !child_start || !child_list || !n_runs) return RH_ERR_NULL;
+    const int rounds = rh::plan_tree(n, parent, run_first, run_last, round_start, child_start, child_list, n_runs);
+    return rounds < 0 ? RH_ERR_SHAPE : rounds;
+}
+
+int rh_tree_dp(int32_t B, int32_t n, int32_t Kp, int32_t n_runs, int32_t n_rounds, const int32_t* round_start,
+               const int32_t* run_first, const int32_t* run_last, const int32_t* parent, const int32_t* child_start,
+               const int32_t* child_list, const int64_t* c, int64_t c_batch_stride, const int64_t* R,
+               int64_t R_batch_stride, uint16_t* arg, int64_t* w, int64_t* total, int32_t* root_choice,
+               int32_t* plan, void* stream) {
+    if (B < 0 || B > 65535 || n < 1 || n > RH_NMAX || n_runs < 1 || n_runs > n || n_rounds < 1 || n_rounds > n_runs)
+        return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (!round_start) return RH_ERR_NULL;
+    if (round_start[0] != 0 || round_start[n_rounds] != n_runs) return RH_ERR_SHAPE;
+    for (int t = 0; t < n_rounds; ++t)
+        if (round_start[t + 1] < round_start[t]) return RH_ERR_SHAPE;
+    if (B == 0) return RH_OK;
+    if (!run_first || !run_last || !parent || !child_start || !child_list || !c || !w || !total || !root_choice)
+        return RH_ERR_NULL;
+    if (n > 1 && (!R || !arg)) return RH_ERR_NULL;
+    if (c_batch_stride < 0 || R_batch_stride < 0) return RH_ERR_SHAPE;
+    if (B > 1 && c_batch_stride < (int64_t)n * Kp) return RH_ERR_SHAPE;
+    if (B > 1 && R_batch_stride != 0 && R_batch_stride < (int64_t)(n - 1) * Kp * Kp) return RH_ERR_SHAPE;
+    return from_hip(rh::launch_tree_dp(B, n, Kp, n_rounds, round_start, run_first, run_last, parent, child_start,
+                                       child_list, c, c_batch_stride, R, R_batch_stride, arg, w, total, root_choice,
+                                       plan, static_cast<hipStream_t>(stream)));
+}
+
 int rh_mask_replicated(int32_t N, int32_t Kp, int32_t n_k, int32_t k0, const int64_t* c,
                        const int64_t* param_bytes, const uint8_t* repl, int64_t* c_out, void* stream) {
     if (N < 1 || N > RH_NMAX || n_k < 0 || k0 < 0) return RH_ERR_SHAPE;
@@ -324,6 +356,6 @@ const char* rh_strerror(int code) {
 
 int rh_gang_workgroups(int32_t B, int32_t compute_units) { return rh::gang_workgroups(B, compute_units); }
 
-int rh_version(void) { return 102; }
+int rh_version(void) { return 103; }
 
 }  // extern "C"

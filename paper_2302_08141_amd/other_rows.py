@@ -270,8 +270,29 @@ def _cone_rows(dev, n_cones=1024, K=64):
             "cones_per_s": n_cones / (t * 1e-3)}
 
 
+def _tree_rows(dev, n=4096, K=64, B=8):
+    """One in-tree of operators (inner nodes join up to four inputs) searched for B problems at once."""
+    from .workloads import trees
+    parent = trees.random_tree(n, max_fan_in=4, chain_bias=0.7)
+    c, R = trees.random_tree_costs(parent, K)
+    tp = rh.TreePlan(parent, dev)
+    dc = torch.from_numpy(c[None]).to(dev).repeat(B, 1, 1).contiguous()
+    dR = torch.from_numpy(R).to(dev)
+    arg = torch.empty((B, n - 1, K), dtype=torch.int16, device=dev)
+    w = torch.empty((B, n, K), dtype=torch.int64, device=dev)
+    total = torch.empty(B, dtype=torch.int64, device=dev)
+    choice = torch.empty(B, dtype=torch.int32, device=dev)
+    plan = torch.empty((B, n), dtype=torch.int32, device=dev)
+    t = _best_ms(lambda: rh.rh_tree_dp(B, K, tp, dc, n * K, dR, 0, arg, w, total, choice, plan))
+    runs = tp.host["run_last"][:tp.n_runs] - tp.host["run_first"][:tp.n_runs] + 1
+    return {"nodes": n, "K": K, "problems": B, "depth": trees.depth(parent), "runs": tp.n_runs, "rounds": tp.n_rounds,
+            "longest_run": int(runs.max()), "dp_and_plan_ms": t, "cells_per_s": B * (n - 1) * K * K / (t * 1e-3),
+            "total_ns": int(total[0].item())}
+
+
 def measure(dev="cuda:0"):
     return {"moe_shaped_graph": _graph_rows(graphs.moe_chain(), dev),
             "gpt_like_chain": _graph_rows(graphs.gpt_chain(), dev),
             "stage_partition": _stage_rows(dev),
-            "cones": _cone_rows(dev)}
+            "cones": _cone_rows(dev),
+            "in_tree": _tree_rows(dev)}

@@ -77,3 +77,68 @@ def test_cone_without_branches_and_argument_errors():
     assert L.rh_cone_merge(-1, 0, 64, P(start), None, P(c_root), None, P(total), P(choice), None, None) == -2
     assert L.rh_cone_merge(1, 2, 64, P(start), None, P(c_root), None, P(total), P(choice), None, None) == -1
     assert L.rh_cone_merge(0, 0, 64, None, None, None, None, None, None, None, None) == 0
+
+
+def test_the_table_of_a_cone_is_the_first_row_of_the_chain_above_it():
+    # every root strategy is kept for the next level (Sec. 4.3.2): a cone whose root feeds a chain of further
+    # operators.  The cone's table takes the place of the node costs of the chain's first operator, the chain's
+    # backtrack gives the root's strategy, and that starts the branches' backtrack.  Checked against the in-tree
+    # oracle on the whole graph.
+    K = Kp = 64
+    rng = np.random.default_rng(21)
+    (branches, c_root), = wc.random_cones(1, K, max_branches=4, max_len=5, seed=99)
+    pk = wc.pack([(branches, c_root)], Kp)
+    c, R = torch.from_numpy(pk["c"]).to(DEV), torch.from_numpy(pk["R"]).to(DEV)
+    Bb, N, _ = pk["c"].shape
+    arg = torch.empty((Bb, N - 1, Kp), dtype=torch.int16, device=DEV)
+    w = torch.empty((Bb, Kp), dtype=torch.int64, device=DEV)
+    tot_b = torch.empty(Bb, dtype=torch.int64, device=DEV)
+    last_b = torch.empty(Bb, dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(Bb, N, Kp, c, N * Kp, R, (N - 1) * Kp * Kp, arg, w, tot_b, last_b)
+    table = torch.empty((1, Kp), dtype=torch.int64, device=DEV)
+    total = torch.empty(1, dtype=torch.int64, device=DEV)
+    choice = torch.empty(1, dtype=torch.int32, device=DEV)
+    rh.rh_cone_merge(1, Bb, Kp, torch.from_numpy(pk["branch_start"]).to(DEV), w, torch.from_numpy(pk["c_root"]).to(DEV),
+                     table, total, choice, None)
+    # the chain above the root: M further operators; operator 0 of that chain is the root with the table as costs
+    M = 6
+    up_c = rng.integers(0, 2000, size=(M, K)).astype(np.int64)
+    up_R = rng.integers(0, 10000, size=(M, K, K)).astype(np.int64)
+    cc = torch.cat([table, torch.from_numpy(up_c).to(DEV)]).reshape(1, M + 1, Kp).contiguous()
+    c_arg = torch.empty((1, M, Kp), dtype=torch.int16, device=DEV)
+    c_total = torch.empty(1, dtype=torch.int64, device=DEV)
+    c_last = torch.empty(1, dtype=torch.int32, device=DEV)
+    c_plan = torch.empty((1, M + 1), dtype=torch.int32, device=DEV)
+    rh.rh_minplus_chain(1, M + 1, Kp, cc, (M + 1) * Kp, torch.from_numpy(up_R[None]).to(DEV), M * Kp * Kp, c_arg, None,
+                        c_total, c_last)
+    rh.rh_backtrack(1, M + 1, Kp, c_arg, c_last, c_plan)
+    branch_last = c_plan[:, 0].expand(Bb).contiguous()       # the root's strategy, for every branch
+    plan = torch.empty((Bb, N), dtype=torch.int32, device=DEV)
+    rh.rh_backtrack(Bb, N, Kp, arg, branch_last, plan)
+    torch.cuda.synchronize()
+    # the same graph as one in-tree: the branches' nodes, the root, then the chain above it
+    lens = [cb.shape[0] for cb, _ in branches]
+    n = sum(lens) + 1 + M
+    root = sum(lens)
+    parent = np.full(n, -1, dtype=np.int32)
+    tc = np.zeros((n, K), dtype=np.int64)
+    tR = np.zeros((n - 1, K, K), dtype=np.int64)
+    at = 0
+    for cb, Rb in branches:
+        m = cb.shape[0]
+        parent[at:at + m] = np.arange(at + 1, at + m + 1)
+        parent[at + m - 1] = root
+        tc[at:at + m], tR[at:at + m] = cb, Rb
+        at += m
+    tc[root] = c_root
+    parent[root:n - 1] = np.arange(root + 1, n)
+    tc[root + 1:] = up_c
+    tR[root:] = up_R
+    o_table, o_total, o_choice, o_plan, _ = oracle.tree(parent, tc, tR)
+    assert c_total.item() == o_total and c_last.item() == o_choice
+    got = c_plan.cpu().numpy()[0]
+    assert np.array_equal(got, o_plan[root:])
+    at = 0
+    for b, m in enumerate(lens):
+        assert np.array_equal(plan[b, N - 1 - m:N - 1].cpu().numpy(), o_plan[at:at + m]), b
+        at += m
