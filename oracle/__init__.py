@@ -14,7 +14,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# ORACLE_SANITIZED=1 (set by the sanitizer test for a child process that preloads the AddressSanitizer runtime) loads a
+# build with -fsanitize=address,undefined instead; the numbers are the same, every out-of-bounds access, overflow
+# of a signed integer or misaligned pointer ends the process
+SANITIZED = os.environ.get("ORACLE_SANITIZED") == "1"
+_LIB = os.path.join(_HERE, "liboracle_san.so" if SANITIZED else "liboracle.so")
 INF = 1 << 52
 
 _lib = None
@@ -23,8 +27,10 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc -O2 (no SIMD intrinsics, OpenMP across problems only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-                               "-Wall", "-Wextra", "-o", _LIB, _SRC])
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+            if SANITIZED else ["-O2"]
+        subprocess.check_call(["gcc"] + flags + ["-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                                                 "-o", _LIB, _SRC])
     return _LIB
 
 
