@@ -115,6 +115,44 @@ def cpu_baseline(c, R, B, N, K, gpu_total, gpu_last, gpu_plan, sample_problems=4
             "parity_checked_problems": n}
 
 
+def cpu_other_rows():
+    """The oracle as it stands on bounded samples of the other workloads (part of the CPU-baseline leg): the
+    unit-counting reshard builder on edges of the MoE-shaped graph, the stage search on the stage-partition chain, the
+    interval table on a prefix of it."""
+    import numpy as np
+    import oracle
+    from paper_2302_08141_amd.workloads import graphs, synthetic as syn
+    out = {}
+    g = graphs.moe_chain()
+    e0, ne = 85, 8                                    # eight edges of the second layer
+    sl = slice(e0, e0 + ne + 1)
+    t0 = time.perf_counter()
+    oracle.build_reshard(g["m"], g["bw_bytes_per_us"], g["alpha_ns"], g["K"][sl], g["out_spec"][sl], g["in_spec"][sl],
+                         g["dims"][e0:e0 + ne], g["elem_bytes"][e0:e0 + ne])
+    dt = time.perf_counter() - t0
+    out["moe_reshard_builder"] = {"ms_per_edge": dt * 1e3 / ne, "edges_timed": ne, "of_edges": g["N"] - 1,
+                                  "K": g["Kp"], "cores": 1, "kind": "oracle (counts units per device)"}
+    w = syn.STAGE_PARTITION
+    L, S = w["L"], w["S"]
+    cost = syn.segment_costs(0, L, w["lo"], w["hi"])[None]
+    threads = host_threads()
+    t0 = time.perf_counter()
+    oracle.stage_dp(cost, S, s_query=S, nthreads=1)
+    dt = time.perf_counter() - t0
+    cells = sum((L - s + 1) * (L - s + 2) // 2 for s in range(2, S + 1))
+    out["stage_dp"] = {"ms": dt * 1e3, "L": L, "S": S, "max_min_cells_per_s": cells / dt, "cores": 1,
+                       "kind": "oracle (full scan)"}
+    Ls, K = 512, 64                                   # the interval table of the first 512 segments
+    c, R = syn.random_chain_batch([11], Ls, K, 100_000, 200_000)
+    t0 = time.perf_counter()
+    oracle.interval_costs(c[0], R[0], nthreads=threads)
+    dt = time.perf_counter() - t0
+    out["interval_table"] = {"ms": dt * 1e3, "L": Ls, "of_L": L, "K": K,
+                             "cells_per_s": sum(Ls - 1 - i for i in range(Ls)) * K * K / dt, "cores": threads,
+                             "kind": "oracle"}
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -231,6 +269,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(c, R, B, N, K, total, last, plan)
         out["parity_checked_problems"] = out["cpu_baseline"]["parity_checked_problems"]
         out["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
+        out["cpu_baseline"]["other_rows"] = cpu_other_rows()
 
     # the other rows need room of their own (one of them holds the tables of 11 meshes): every view of R goes too
     del c, R, arg, plan, probe, copy_src, fn
