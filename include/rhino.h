@@ -413,11 +413,20 @@ size_t rh_static_scratch_bytes(void);
  *   ldT  row stride of T in elements, even, >= L + 1
  *   T    [B][L][ldT] out: entry [i][j] for i < j <= L; RH_INF for j <= i; columns beyond L
  *        are not written
+ *   workspace  optional.  Row i of the table is a sweep from operator i to the end of the chain, so the
+ *        whole table costs L^2/2 sweep steps.  Given rh_workspace_size(RH_WS_INTERVAL_COSTS, B, L, Kp)
+ *        bytes (Kp = 64 and L >= 512; 0 = does not apply; 256-byte aligned, contents undefined before
+ *        and after), the same table is put together from blocks of 128 operators instead: sweeps
+ *        inside the blocks, the min-plus matrices of the blocks (the per-segment strategy tables of
+ *        Sec. 4.3.2) multiplied along the chain, and one small min-plus product per pair of blocks.
+ *        A tenth of the arithmetic at L = 4096, no chain of dependent steps longer than a block,
+ *        the same entries bit for bit.  With NULL, 0 the call needs no workspace.
  * c, R and T must be 16-byte aligned.  The plan of a chosen stage is what rh_minplus_chain and
  * rh_backtrack return for the sub-chain (pass c + i*Kp, R + i*Kp*Kp and N = j - i).
  */
 int rh_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c,
-                      const int64_t* R, int64_t ldT, int64_t* T, void* stream);
+                      const int64_t* R, int64_t ldT, int64_t* T, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 /*
  * rh_stage_dp_interval -- balanced pipeline stages (Sec. 2.1, Sec. 5.1-5.2) when the time of
@@ -471,6 +480,7 @@ int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len
 #define RH_WS_STAGE_DP_INTERVAL 3
 #define RH_WS_MINPLUS_CHAIN_SEGMENTED 4
 #define RH_WS_MINPLUS_CHAIN_SPECS 5
+#define RH_WS_INTERVAL_COSTS 6
 /* Bytes of workspace the call `which` needs for these sizes (0 if none or
  * if the sizes are invalid). */
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L,

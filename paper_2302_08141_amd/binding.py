@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "librhino.so")
 INF = 1 << 52
 KMIN, KMAX, NMAX = 16, 1024, 16384
 WS_MINPLUS_CHAIN, WS_STAGE_DP, WS_STAGE_DP_WINDOW, WS_STAGE_DP_INTERVAL, WS_MINPLUS_CHAIN_SEGMENTED = 0, 1, 2, 3, 4
-WS_MINPLUS_CHAIN_SPECS = 5
+WS_MINPLUS_CHAIN_SPECS, WS_INTERVAL_COSTS = 5, 6
 
 
 class RhinoError(RuntimeError):
@@ -73,7 +73,7 @@ def lib():
         L.rh_stage_dp_window_static.restype = ctypes.c_int
         L.rh_static_scratch_bytes.argtypes = []
         L.rh_static_scratch_bytes.restype = sz
-        L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp]
+        L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, sz, vp]
         L.rh_stage_dp_interval.argtypes = [i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_interval_costs_banded.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp, vp]
         L.rh_stage_dp_interval_banded.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
@@ -305,12 +305,16 @@ def rh_static_scratch_bytes() -> int:
     return int(lib().rh_static_scratch_bytes())
 
 
-def rh_interval_costs(B: int, L: int, Kp: int, c, R, ldT: int, T):
-    """c int64[B][L][Kp]; R int64[B][L-1][Kp][Kp] (None if L == 1); T int64[B][L][ldT] out, ldT even and > L."""
+def rh_interval_costs(B: int, L: int, Kp: int, c, R, ldT: int, T, workspace=None):
+    """c int64[B][L][Kp]; R int64[B][L-1][Kp][Kp] (None if L == 1); T int64[B][L][ldT] out, ldT even and > L;
+    workspace: optional uint8 tensor of rh_workspace_size(WS_INTERVAL_COSTS, B, L, Kp) bytes."""
     b, l, k = max(B, 0), max(L, 0), max(Kp, 0)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().rh_interval_costs(B, L, Kp, _ptr(c, torch.int64, "c", b * l * k),
                                    _ptr(R, torch.int64, "R", b * max(l - 1, 0) * k * k), ldT,
-                                   _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), _stream()), "rh_interval_costs")
+                                   _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), ws_ptr, ws_bytes, _stream()),
+           "rh_interval_costs")
 
 
 def rh_stage_dp_interval(B: int, L: int, S: int, ldT: int, T, bottleneck, cut, s_query: int, bounds, workspace):

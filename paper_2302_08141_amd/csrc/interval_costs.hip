@@ -31,54 +31,12 @@
 // L - i edges, a triangle: then blocks have 8 rows, a workgroup takes block b and
 // afterwards block (last - b), and every workgroup walks L + 8 edges.
 #include "kernels.h"
-
-#include <type_traits>
+#include "minplus_rows.h"
 
 namespace rh {
 namespace {
 
 constexpr int kPiece = 4096;                 // elements of R per LDS buffer
-constexpr double kInfD = 4503599627370495.0; // 2^52 - 1 stands for "infeasible" inside the kernel
-
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Exact for 0 <= x < 2^52 - 1 (two full-rate instructions: the integer becomes the mantissa of 2^52 + x);
-// anything from 2^52 - 1 up, which includes RH_INF, becomes the kernel's infeasible value.
-__device__ __forceinline__ double to_f64(int64_t x) {
-    uint32_t lo = (uint32_t)x, hi = (uint32_t)((uint64_t)x >> 32);
-    const bool big = hi >= 0x100000u;
-    lo = big ? 0xFFFFFFFFu : lo;
-    hi = big ? 0xFFFFFu : hi;
-    return __hiloint2double((int)(hi | 0x43300000u), (int)lo) - 4503599627370496.0;
-}
-
-// back to the interface's integers: infeasible is 2^52
-__device__ __forceinline__ int64_t to_i64(double m) { return m >= kInfD ? kInf : (int64_t)m; }
-
-__device__ __forceinline__ double bcast(double x, int lane) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), lane);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), lane);
-    return __hiloint2double(hi, lo);
-}
-
-// x of lane N of this lane's row of 16 lanes (one v_mov_b64_dpp)
-template <int N>
-__device__ __forceinline__ double row_bcast(double x) {
-    const long long v = __double_as_longlong(x);
-    return __longlong_as_double(__builtin_amdgcn_update_dpp(v, v, 0x150 + N, 0xF, 0xF, false));
-}
-
-// x of another lane of the wave
-__device__ __forceinline__ double from_lane(double x, int lane) {
-    const int lo = __builtin_amdgcn_ds_bpermute(lane << 2, __double2loint(x));
-    const int hi = __builtin_amdgcn_ds_bpermute(lane << 2, __double2hiint(x));
-    return __hiloint2double(hi, lo);
-}
-
 // x of the lane that the DPP pattern CTRL pairs this lane with (patterns that stay inside a row of 16 lanes)
 template <int CTRL>
 __device__ __forceinline__ double dpp_peer(double x) {
@@ -172,75 +130,21 @@ __device__ __forceinline__ void relax_piece(const double* __restrict__ piece, in
     }
 }
 
-// Kp = 64, the whole table of an edge in one piece: acc[q][0] = min(acc[q][0], min_a V[q][a] + piece[a][lane]) for
-// the first NA of the wave's two rows.  Lane 16 r + j: in step n its row of 16 lanes works on a = 4 n + r, and the
-// lane relaxes columns j + 16 (k ^ r), k = 0..3 (the exclusive-or spreads the four rows of lanes over the LDS
-// banks); its partial minimum for column j + 16 (k ^ r) is acc4[k].
-template <int NA, int SLOTS>
-__device__ __forceinline__ void relax_rows64(const double* __restrict__ piece, int lane, const double (&V)[SLOTS][1],
-                                             double (&acc)[SLOTS][1]) {
-    const int r = lane >> 4, j = lane & 15;
-    double src[NA], acc4[NA][4];
-#pragma unroll
-    for (int q = 0; q < NA; ++q) {
-        src[q] = from_lane(V[q][0], 4 * j + r);    // lane 16 r + n holds V[q][4 n + r]
-#pragma unroll
-        for (int k = 0; k < 4; ++k) acc4[q][k] = kInfD;
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    const double* base = piece + r * 64 + j;
-    // The values of three steps are on their way from LDS while one step is worked on (a wave may have a SIMD to
-    // itself here, so nothing else covers the trip): the registers of a step are refilled for three steps later
-    // as soon as they have been used, and the scheduler is told to keep that order.
-    double x[3][4];
-    auto load = [&](double (&xs)[4], int n) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) xs[k] = base[(4 * n) * 64 + 16 * (k ^ r)];
-    };
-    auto step = [&](auto n_tag) {
-        constexpr int N = decltype(n_tag)::value;
-        double (&xs)[4] = x[N % 3];
-#pragma unroll
-        for (int q = 0; q < NA; ++q) {
-            const double sv = row_bcast<N>(src[q]);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) acc4[q][k] = __builtin_fmin(acc4[q][k], xs[k] + sv);
-        }
-        if constexpr (N + 3 < 16) load(xs, N + 3);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    load(x[0], 0);
-    load(x[1], 1);
-    load(x[2], 2);
-    __builtin_amdgcn_sched_barrier(0);
-    step(std::integral_constant<int, 0>{});  step(std::integral_constant<int, 1>{});
-    step(std::integral_constant<int, 2>{});  step(std::integral_constant<int, 3>{});
-    step(std::integral_constant<int, 4>{});  step(std::integral_constant<int, 5>{});
-    step(std::integral_constant<int, 6>{});  step(std::integral_constant<int, 7>{});
-    step(std::integral_constant<int, 8>{});  step(std::integral_constant<int, 9>{});
-    step(std::integral_constant<int, 10>{}); step(std::integral_constant<int, 11>{});
-    step(std::integral_constant<int, 12>{}); step(std::integral_constant<int, 13>{});
-    step(std::integral_constant<int, 14>{}); step(std::integral_constant<int, 15>{});
-    // Column 16 r + j (this lane's own) is acc4[0] here, acc4[1] in the lane 16 further (its r differs in bit 0),
-    // acc4[2] and acc4[3] in the lanes 32 and 48 further: fold the four rows of lanes.
-#pragma unroll
-    for (int q = 0; q < NA; ++q) {
-        const double a0 = __builtin_fmin(acc4[q][0], from_lane(acc4[q][1], lane ^ 16));
-        const double a2 = __builtin_fmin(acc4[q][2], from_lane(acc4[q][3], lane ^ 16));
-        acc[q][0] = __builtin_fmin(acc[q][0], __builtin_fmin(a0, from_lane(a2, lane ^ 32)));
-    }
-}
-
 // WAVES waves of SLOTS rows each = WAVES * SLOTS rows per block (wave w keeps rows SLOTS w .. SLOTS w + SLOTS - 1 of
 // the block); the workgroup takes block blockIdx.x and, if PASSES == 2, block n_blocks - 1 - blockIdx.x after it.
 // STAGERS = 0: every wave takes part in staging the tables.  STAGERS > 0: that many further waves do nothing but
 // stage (fetch, convert, store to LDS) while the WAVES row waves do nothing but relax, so that the memory side and
 // the arithmetic of an edge run side by side instead of one after the other in every wave.
-template <int KP, int WAVES, int PASSES, int SLOTS, int STAGERS>
+// UNIT = false: row r is the sweep that starts at operator r with that operator's node costs (the table's row r).
+// UNIT = true: all rows start at operator 0, row r with strategy r fixed there at no cost (a unit vector): row r of
+// the output is then the least cost of the operators 0..j-1 given operator 0's strategy, its node cost left out.
+// blockIdx.y = problem * sub.n + part: the parts of a problem are sub-chains at fixed strides; sub.v_end, if
+// given, receives every row's vector at the last operator.
+template <int KP, int WAVES, int PASSES, int SLOTS, int STAGERS, bool UNIT>
 __global__ void __launch_bounds__((WAVES + STAGERS) * 64)
-interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
+interval_costs_kernel(int32_t L_full, int32_t max_len, int32_t n_blocks,
                       const int64_t* __restrict__ c, int64_t c_bs, const int64_t* __restrict__ R, int64_t R_bs,
-                      int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
+                      int64_t ldT, int64_t* __restrict__ T, int64_t T_bs, IntervalParts sub) {
     using G = Shape<KP>;
     constexpr int kThreads = (STAGERS > 0 ? STAGERS : WAVES) * 64;         // threads that stage
     constexpr int EPT = G::ELEMS / kThreads > 0 ? G::ELEMS / kThreads : 1;   // elements of a piece per thread
@@ -250,9 +154,17 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
     const bool stages = STAGERS == 0 || wave >= WAVES;                      // wave-uniform
     const bool has_rows = wave < WAVES;
     const int tid = STAGERS > 0 ? (int)threadIdx.x - WAVES * 64 : (int)threadIdx.x;   // index among the staging threads
-    c += (int64_t)blockIdx.y * c_bs;
-    R += (int64_t)blockIdx.y * R_bs;
-    T += (int64_t)blockIdx.y * T_bs;
+    const int prob = (int)blockIdx.y / sub.n, part = (int)blockIdx.y - prob * sub.n;
+    c += (int64_t)prob * c_bs + (int64_t)part * sub.c_stride;
+    R += (int64_t)prob * R_bs + (int64_t)part * sub.R_stride;
+    T += (int64_t)prob * T_bs + (int64_t)part * sub.T_stride;
+    // operators of this part: a part stops at the end of the chain (workgroup-uniform)
+    const int left = sub.ops_total - part * sub.ops_stride;
+    const int L = left < L_full ? left : L_full;
+    if (L < 1) return;
+    int64_t* v_end = (sub.v_end != nullptr && L == L_full)
+                         ? sub.v_end + (int64_t)prob * sub.v_bs + (int64_t)part * sub.v_stride : nullptr;
+    const int n_rows = UNIT ? KP : (sub.n_rows < L ? sub.n_rows : L);     // rows there are (a later one never starts)
     const bool live_lane = lane < KP;             // KP < 64: the upper lanes carry infeasible columns
     const int col = live_lane ? lane : 0;
 
@@ -262,23 +174,27 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
     if (pass > 0 && block <= (int)blockIdx.x) break;      // an odd number of blocks: the middle one has no partner
     lds_barrier();                                // the pass before has read its last piece
 
-    // rows of this wave: slot q holds the start block * WAVES * SLOTS + wave * SLOTS + q
-    int row[SLOTS];
+    // rows of this wave: slot q holds row block * WAVES * SLOTS + wave * SLOTS + q of the output (trow); it starts
+    // at operator `row` (the same number, or operator 0 for every row when UNIT); L: never starts
+    int row[SLOTS], trow[SLOTS];
 #pragma unroll
-    for (int q = 0; q < SLOTS; ++q) row[q] = has_rows ? (block * WAVES + wave) * SLOTS + q : L;   // L: never starts
+    for (int q = 0; q < SLOTS; ++q) {
+        trow[q] = (block * WAVES + wave) * SLOTS + q;
+        row[q] = (has_rows && trow[q] < n_rows) ? (UNIT ? 0 : trow[q]) : L;
+    }
 
     // entries at and left of the diagonal, and those of stages longer than max_len operators
 #pragma unroll
     for (int q = 0; q < SLOTS; ++q) {
         if (row[q] < L)
             for (int j = lane; j <= L; j += 64)
-                if (j <= row[q] || j - row[q] > max_len) T[(int64_t)row[q] * ldT + j] = kInf;
+                if (j <= row[q] || j - row[q] > max_len) T[(int64_t)trow[q] * ldT + j] = kInf;
     }
 
     constexpr int kRows = WAVES * SLOTS;          // rows of a block
-    const int l0 = block * kRows;                 // the first row of this block starts at operator l0
+    const int l0 = UNIT ? 0 : block * kRows;      // the first row of this block starts at operator l0
     // the last operator any row of this block reaches: its highest row, max_len operators on, or the chain's end
-    const int row_hi = l0 + kRows - 1 < L - 1 ? l0 + kRows - 1 : L - 1;
+    const int row_hi = l0 + (UNIT ? 0 : kRows - 1) < L - 1 ? l0 + (UNIT ? 0 : kRows - 1) : L - 1;
     const int l_last = row_hi + max_len - 1 < L - 1 ? row_hi + max_len - 1 : L - 1;
     const int n_edges = l_last - l0;              // edges l0 .. l_last - 1
     const int n_pieces = n_edges * G::NCH;
@@ -367,7 +283,8 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
         for (int q = 0; q < SLOTS; ++q) {
             if (row[q] == l) {
 #pragma unroll
-                for (int k = 0; k < G::CPT; ++k) V[q][k] = cA[k];
+                for (int k = 0; k < G::CPT; ++k)
+                    V[q][k] = UNIT ? ((live_lane && col + 64 * k == trow[q]) ? 0.0 : kInfD) : cA[k];
             }
             // (the rows of a wave start one after the other and stop one after the other, so with two slots the
             // cases are: 0 alone, both, 1 alone)
@@ -384,7 +301,7 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
                 tcol[q] = lane == (j & 63) ? m : tcol[q];
                 if ((j & 63) == 63 || j == L || j - row[q] == max_len) {
                     // columns of this block at or left of the diagonal still hold 2^52, which is their value
-                    if (lane <= (j & 63)) T[(int64_t)row[q] * ldT + (j & ~63) + lane] = to_i64(tcol[q]);
+                    if (lane <= (j & 63)) T[(int64_t)trow[q] * ldT + (j & ~63) + lane] = to_i64(tcol[q]);
                 }
             }
         }
@@ -443,46 +360,63 @@ interval_costs_kernel(int32_t L, int32_t max_len, int32_t n_blocks,
         if (g + 1 < n_pieces) one_piece(g + 1, preB, preA);
     }
     if (has_rows) arrive(l_last);                 // the entries of the last operator
+    if (v_end != nullptr) {                       // every row's vector there
+#pragma unroll
+        for (int q = 0; q < SLOTS; ++q) {
+            if (running[q] && live_lane) {
+#pragma unroll
+                for (int k = 0; k < G::CPT; ++k) v_end[(int64_t)trow[q] * KP + col + 64 * k] = to_i64(V[q][k]);
+            }
+        }
+    }
   }
 }
 
 }  // namespace
 
+// parts == nullptr: the table of B chains.  Otherwise every chain is n sub-chains at fixed strides (see kernels.h).
 hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, int64_t c_bs,
                                  const int64_t* R, int64_t R_bs, int64_t ldT, int64_t* T, int64_t T_bs,
-                                 hipStream_t stream) {
+                                 hipStream_t stream, const IntervalParts* parts, bool unit_rows) {
     if (B == 0) return hipSuccess;
     if (max_len > L) max_len = L;
+    IntervalParts sub{1, 0, 0, 0, L, nullptr, 0, 0, 0, L};
+    if (parts != nullptr) sub = *parts;
+    if (sub.n < 1) return hipSuccess;
+    if (unit_rows && Kp != 64) return hipErrorInvalidValue;
+    const int rows_total = unit_rows ? Kp : (sub.n_rows < L ? sub.n_rows : L);
     // short stages only: blocks of 16 rows, equal work, one per workgroup; else blocks of 8 rows, a long one and a
     // short one per workgroup.  At Kp = 64: 8 waves of two rows, or 8 waves of one row, and four staging waves.
     const bool equal_blocks = max_len <= L / 2;
     const size_t lds = 2 * kPiece * sizeof(double);
-#define RH_IC(KP, WAVES, PASSES, SLOTS, STAGERS)                                                                            \
+#define RH_IC(KP, WAVES, PASSES, SLOTS, STAGERS, UNIT)                                                             \
     do {                                                                                                           \
-        const int n_blocks = (L + (WAVES) * (SLOTS)-1) / ((WAVES) * (SLOTS));                                      \
-        const dim3 grid((unsigned)((n_blocks + (PASSES)-1) / (PASSES)), (unsigned)B);                              \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(interval_costs_kernel<KP, WAVES, PASSES, SLOTS, STAGERS>), \
+        const int n_blocks = (rows_total + (WAVES) * (SLOTS)-1) / ((WAVES) * (SLOTS));                             \
+        const dim3 grid((unsigned)((n_blocks + (PASSES)-1) / (PASSES)), (unsigned)(B * sub.n));                    \
+        auto kern = interval_costs_kernel<KP, WAVES, PASSES, SLOTS, STAGERS, UNIT>;                                \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                    \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                  \
         if (e != hipSuccess) return e;                                                                             \
-        hipLaunchKernelGGL((interval_costs_kernel<KP, WAVES, PASSES, SLOTS, STAGERS>), grid,                       \
-                           dim3(((WAVES) + (STAGERS)) * 64), lds, stream, L,                                       \
-                           max_len, n_blocks, c, c_bs, R, R_bs, ldT, T, T_bs);                                     \
+        hipLaunchKernelGGL(kern, grid, dim3(((WAVES) + (STAGERS)) * 64), lds, stream, L, max_len, n_blocks, c,     \
+                           c_bs, R, R_bs, ldT, T, T_bs, sub);                                                      \
     } while (0)
 #define RH_IC_KP(KP)                                                                                               \
     do {                                                                                                           \
         if (equal_blocks)                                                                                          \
-            RH_IC(KP, 16, 1, 1, 0);                                                                                   \
+            RH_IC(KP, 16, 1, 1, 0, false);                                                                         \
         else                                                                                                       \
-            RH_IC(KP, 8, 2, 1, 0);                                                                                    \
+            RH_IC(KP, 8, 2, 1, 0, false);                                                                          \
     } while (0)
     switch (Kp) {
         case 16: RH_IC_KP(16); break;
         case 32: RH_IC_KP(32); break;
         case 64:
-            if (equal_blocks)
-                RH_IC(64, 8, 1, 2, 4);
+            if (unit_rows)
+                RH_IC(64, 8, 1, 1, 4, true);
+            else if (equal_blocks)
+                RH_IC(64, 8, 1, 2, 4, false);
             else
-                RH_IC(64, 8, 2, 1, 4);
+                RH_IC(64, 8, 2, 1, 4, false);
             break;
         case 128: RH_IC_KP(128); break;
         case 256: RH_IC_KP(256); break;

@@ -103,8 +103,29 @@ hipError_t launch_stage_window(int32_t B, int32_t L, int32_t S, const int64_t* s
                                int32_t* bounds, void* workspace, hipStream_t stream);
 
 // Stage times of all intervals of B operator chains: T[p][i][j] for 0 <= i < L, 0 <= j <= L (row stride ldT).
+// With `parts`, every chain is parts->n sub-chains of L operators each: sub-chain t of problem p reads
+// c + p*c_bs + t*c_stride, R + p*R_bs + t*R_stride and writes T + p*T_bs + t*T_stride; only its first n_rows rows
+// are made; a part never reaches past the end of the chain: part t has min(L, ops_total - t * ops_stride)
+// operators (ops_stride = operators between the starts of neighbouring parts, ops_total = operators from the
+// start of part 0 to the chain's end).  v_end, if given, receives every row's vector at the last operator of every
+// part of full length ([problem][part][row][Kp] at strides v_bs, v_stride).  unit_rows (Kp = 64): the rows are
+// not start operators but the Kp strategies of operator 0, each fixed there at no cost.
+struct IntervalParts {
+    int32_t n;
+    int64_t c_stride, R_stride, T_stride;
+    int32_t n_rows;
+    int64_t* v_end;
+    int64_t v_stride, v_bs;
+    int32_t ops_stride, ops_total;
+};
 hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, int64_t c_bs, const int64_t* R,
-                                 int64_t R_bs, int64_t ldT, int64_t* T, int64_t T_bs, hipStream_t stream);
+                                 int64_t R_bs, int64_t ldT, int64_t* T, int64_t T_bs, hipStream_t stream,
+                                 const IntervalParts* parts = nullptr, bool unit_rows = false);
+
+// The same table put together from blocks of 128 operators (Kp = 64, at least four blocks; needs a workspace).
+size_t interval_blocks_workspace_bytes(int32_t B, int32_t L, int32_t Kp);   // 0 = not applicable to these sizes
+hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, const int64_t* c, const int64_t* R, int64_t ldT,
+                                         int64_t* T, void* workspace, hipStream_t stream);
 
 // Stage search over a table of interval times.
 size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S);

@@ -283,8 +283,16 @@ int rh_interval_costs_banded(int32_t B, int32_t L, int32_t Kp, int32_t max_len, 
 }
 
 int rh_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c, const int64_t* R, int64_t ldT, int64_t* T,
-                      void* stream) {
-    return rh_interval_costs_banded(B, L, Kp, L > 0 ? L : 1, c, R, ldT, T, stream);
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    if (workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RH_ERR_WORKSPACE;
+    const size_t need = workspace != nullptr && B > 0 && L >= 1 ? rh::interval_blocks_workspace_bytes(B, L, Kp) : 0;
+    if (need == 0 || workspace_bytes < need)
+        return rh_interval_costs_banded(B, L, Kp, L > 0 ? L : 1, c, R, ldT, T, stream);
+    // the same checks as the plain call, then the table by blocks
+    if (B > 65535 || ldT < (int64_t)L + 1 || (ldT & 1)) return RH_ERR_SHAPE;
+    if (!c || !T || !R) return RH_ERR_NULL;
+    if (!aligned16(c) || !aligned16(T) || !aligned16(R)) return RH_ERR_SHAPE;
+    return from_hip(rh::launch_interval_costs_blocked(B, L, c, R, ldT, T, workspace, static_cast<hipStream_t>(stream)));
 }
 
 int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* T,
@@ -317,6 +325,7 @@ size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or
     }
     if (which == RH_WS_MINPLUS_CHAIN_SEGMENTED) return rh::scan_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_MINPLUS_CHAIN_SPECS) return rh::scan_specs_workspace_bytes(B, N_or_L, Kp_or_S);
+    if (which == RH_WS_INTERVAL_COSTS) return rh::interval_blocks_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_STAGE_DP) {
         if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);
@@ -356,6 +365,6 @@ const char* rh_strerror(int code) {
 
 int rh_gang_workgroups(int32_t B, int32_t compute_units) { return rh::gang_workgroups(B, compute_units); }
 
-int rh_version(void) { return 103; }
+int rh_version(void) { return 104; }
 
 }  // extern "C"

@@ -219,6 +219,13 @@ def _interval_rows(dev, L, S, K):
     T = torch.empty((1, L, ldT), dtype=torch.int64, device=dev)
     t_tab = _best_ms(lambda: rh.rh_interval_costs(1, L, K, c, R, ldT, T))
     cells_tab = sum(L - 1 - i for i in range(L)) * K * K
+    # the same table put together from blocks of 128 operators (the call with its workspace)
+    T_rows = T.clone()
+    ws_b = torch.empty(rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, L, K), dtype=torch.uint8, device=dev)
+    t_blk = _best_ms(lambda: rh.rh_interval_costs(1, L, K, c, R, ldT, T, ws_b)) if ws_b.numel() else None
+    if t_blk is not None and not torch.equal(T[:, :, :L + 1], T_rows[:, :, :L + 1]):
+        raise RuntimeError("the table from blocks differs from the table row by row")
+    del T_rows, ws_b
     bott = torch.empty((1, S), dtype=torch.int64, device=dev)
     cut = torch.empty((1, S, L + 1), dtype=torch.int32, device=dev)
     bounds = torch.empty((1, S + 1), dtype=torch.int32, device=dev)
@@ -237,6 +244,7 @@ def _interval_rows(dev, L, S, K):
     rh.rh_stage_dp_interval(1, L, S, ldT, T, bott, cut, S, bounds, ws)
     return {"K": K, "stages_of_limited_length": banded,
             "table_ms": t_tab, "table_cells": cells_tab, "table_cells_per_s": cells_tab / (t_tab * 1e-3),
+            "table_from_blocks_ms": t_blk,
             "table_f64_lane_ops_per_s": 2 * cells_tab / (t_tab * 1e-3),
             "search_ms": t_dp, "search_cells": cells_dp, "search_cells_per_s": cells_dp / (t_dp * 1e-3),
             "search_table_read_gbps": cells_dp * 8 / (t_dp * 1e-3) / 1e9,

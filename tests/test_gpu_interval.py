@@ -149,6 +149,14 @@ def test_stage_partition_size_with_interval_times():
     h_T = T.cpu().numpy()
     assert np.array_equal(h_T[0, :, :L + 1], want_T[:, :L + 1])
     del want_T
+    # the same table from blocks of 128 operators
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, L, K), dtype=torch.uint8, device=DEV)
+    assert ws.numel() > 0
+    T2 = torch.full_like(T, -7)
+    rh.rh_interval_costs(1, L, K, torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV), ldT, T2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(T2, T)
+    del T2, ws
     want = oracle.stage_interval(h_T, S, s_query=S, nthreads=oracle.num_threads())
     got = gpu_search(T, S, S)
     for g, x in zip(got, want):
@@ -170,13 +178,69 @@ def test_longest_chain_the_interface_takes():
         assert np.array_equal(g, x)
 
 
+@pytest.mark.parametrize("L,B,seed", [(512, 1, 0), (513, 2, 1), (640, 1, 2), (641, 1, 3), (1000, 2, 4), (1153, 1, 5)])
+def test_table_put_together_from_blocks(L, B, seed):
+    # with its workspace the call builds the table from blocks of 128 operators (sweeps inside the blocks, products
+    # of the blocks' matrices, one product per pair of blocks): the same entries bit for bit.  Chains that end on a
+    # block boundary, one operator past it and in the middle of a block; ties; infeasible strategies and pairs.
+    K = Kp = 64
+    rng = np.random.default_rng(seed)
+    hi = 4 if seed % 2 else 100_000
+    c = rng.integers(0, hi, size=(B, L, Kp)).astype(np.int64)
+    R = rng.integers(0, 2 * hi, size=(B, L - 1, Kp, Kp)).astype(np.int64)
+    if seed % 3 == 0:
+        R[rng.random(R.shape) < 0.1] = INF
+        dead = rng.random(c.shape) < 0.1
+        dead[:, :, 0] = False
+        c[dead] = INF
+    if B > 1:
+        c[1, L // 2 + 7, :] = INF                            # no interval of problem 1 gets past this operator
+    need = rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, B, L, Kp)
+    assert need > 0
+    ldT = L + 2 - (L & 1)
+    d_c, d_R = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    plain = torch.full((B, L, ldT), -3, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs(B, L, Kp, d_c, d_R, ldT, plain)
+    for fill in (0x5C, 0x00):                                 # whatever the workspace and the table held before
+        ws = torch.full((need,), fill, dtype=torch.uint8, device=DEV)
+        T = torch.full((B, L, ldT), -3, dtype=torch.int64, device=DEV)
+        rh.rh_interval_costs(B, L, Kp, d_c, d_R, ldT, T, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(T[:, :, :L + 1], plain[:, :, :L + 1]), fill
+        assert bool((T[:, :, L + 1:] == -3).all())           # columns beyond L are not written
+    got = T.cpu().numpy()
+    for p in range(B):
+        want = oracle.interval_costs(np.ascontiguousarray(c[p]), np.ascontiguousarray(R[p]), ldT=ldT, nthreads=8)
+        assert np.array_equal(got[p, :, :L + 1], want[:, :L + 1]), p
+    if B > 1:
+        assert got[1, 0, L] == INF and got[1, L // 2 + 8, L] < INF
+
+
+def test_blocks_at_the_cost_ceiling():
+    # every finite cost within 2^10 of 2^36: entries of the table approach 2^47 at this length
+    L, Kp = 700, 64
+    rng = np.random.default_rng(9)
+    top = 1 << 36
+    c = rng.integers(top - 1024, top, size=(1, L, Kp), dtype=np.int64)
+    R = rng.integers(top - 1024, top, size=(1, L - 1, Kp, Kp), dtype=np.int64)
+    R[rng.random(R.shape) < 0.05] = INF
+    ldT = even_ld(L)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, L, Kp), dtype=torch.uint8, device=DEV)
+    T = torch.full((1, L, ldT), -7, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs(1, L, Kp, torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV), ldT, T, ws)
+    torch.cuda.synchronize()
+    want = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=8)
+    assert np.array_equal(T.cpu().numpy()[0, :, :L + 1], want[:, :L + 1])
+    assert want[0, L] > (2 * L - 1) * (top - 1024)
+
+
 def test_argument_errors():
     lib = rh.lib()
     t = torch.zeros(1 << 16, dtype=torch.int64, device=DEV)
     out = torch.zeros(1 << 10, dtype=torch.int64, device=DEV)
     P = lambda x: ctypes.c_void_p(x.data_ptr())
     ic = lambda **kw: lib.rh_interval_costs(kw.get("B", 1), kw.get("L", 8), kw.get("Kp", 16), kw.get("c", P(t)),
-                                            kw.get("R", P(t)), kw.get("ld", 10), kw.get("T", P(out)), None)
+                                            kw.get("R", P(t)), kw.get("ld", 10), kw.get("T", P(out)), None, 0, None)
     assert ic(L=0) == -2 and ic(B=-1) == -2 and ic(ld=9) == -2 and ic(ld=8) == -2 and ic(L=16385, ld=16386) == -2
     assert ic(Kp=48) == -3 and ic(Kp=512) == -3
     assert ic(c=None) == -1 and ic(R=None) == -1 and ic(T=None) == -1
