@@ -7,6 +7,8 @@
 // in flight per lane; dp[s-1][i] is uniform over a wave and comes through scalar loads.
 // A workgroup owns 128 consecutive j; its 4 waves take the rows i round-robin; with few problems
 // the i range is also split over several workgroups and a small kernel merges the parts.
+// When no stage may be longer than 1024 operators a column has few candidate rows and one launch
+// per stage count does it all (si_band_kernel below).
 #include "kernels.h"
 
 namespace rh {
@@ -181,6 +183,106 @@ si_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t cols, i
     if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
 }
 
+// The same stage count when no stage is longer than max_len <= kBandMaxLen operators: column j has at most max_len
+// candidate rows, so a workgroup takes TJ neighbouring columns and all their rows and finishes them itself -- one
+// launch per stage count, nothing to merge afterwards.  A wave instruction covers 64 / TJ rows of the tile's
+// columns; the rows go round-robin over the waves.  A candidate travels as one word, (max(dp, T) << 11 | row
+// relative to the tile's first row): the value is at most 2^52 and a tile has fewer than 2^11 rows, so the least
+// word is the least value at its lowest row -- the merge inside a wave and across the waves is a plain minimum.
+constexpr int kBandMaxLen = 1024;
+constexpr int kBandRowBits = 11;
+
+template <int TJ, int W, int U>
+__global__ void __launch_bounds__(W * 64)
+si_band_kernel(int32_t L, int32_t S, int32_t s, int32_t max_len, int64_t ldT, const int64_t* __restrict__ T, int64_t T_bs,
+               int64_t cols, const int64_t* __restrict__ prev_all, int64_t* __restrict__ cur_all,
+               int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+    constexpr int RPI = 64 / TJ;                 // rows per wave instruction; U rows in flight per lane
+    static_assert(W % RPI == 0 && kBandMaxLen + TJ <= (1 << kBandRowBits), "tile does not fit the packed word");
+    typedef unsigned long long u64;
+    __shared__ u64 skey[W][TJ];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int col = lane % TJ, sub = lane / TJ;
+    const int p = blockIdx.y;
+    const int64_t* Tp = T + (int64_t)p * T_bs;
+    const int64_t* prev = prev_all + (int64_t)p * 2 * cols;
+    const int j0 = blockIdx.x * TJ;
+    const int j = j0 + col;
+    const int jc = j <= L ? j : L;               // a column inside the table for the lanes past its end
+
+    // rows that can matter to this tile: max(s - 1, j0 - max_len) <= i < min(L, last column of the tile)
+    const int j_last = j0 + TJ - 1 < L ? j0 + TJ - 1 : L;
+    const int i_begin = s - 1 > j0 - max_len ? s - 1 : j0 - max_len;
+    const int n_rows = j_last > i_begin ? j_last - i_begin : 0;
+    const int n_rounds = (n_rows + W * RPI - 1) / (W * RPI);
+
+    u64 best = ~0ull;
+    for (int r0 = 0; r0 < n_rounds; r0 += U) {
+        int64_t t[U], a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (r0 + u < n_rounds) {             // uniform over the workgroup
+                const int rel = ((r0 + u) * W + wave) * RPI + sub;
+                const int i = rel < n_rows ? i_begin + rel : i_begin + n_rows - 1;      // n_rows >= 1 here
+                t[u] = Tp[(int64_t)i * ldT + jc];
+                a[u] = prev[i];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (r0 + u < n_rounds) {
+                const int rel = ((r0 + u) * W + wave) * RPI + sub;
+                const int i = i_begin + rel;
+                const int64_t tc = t[u] < kInf ? t[u] : kInf;
+                const int64_t ac = a[u] < kInf ? a[u] : kInf;
+                const int64_t m = ac > tc ? ac : tc;
+                const u64 key = ((u64)m << kBandRowBits) | (u64)rel;
+                // entries at or left of the diagonal and stages of more than max_len operators do not take part
+                const bool ok = rel < n_rows && i < j && j - i <= max_len && j <= L && key < best;
+                best = ok ? key : best;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= TJ; off >>= 1) {
+        const u64 o = __shfl_xor(best, off, 64);
+        best = o < best ? o : best;
+    }
+    if (lane < TJ) skey[wave][col] = best;
+    __syncthreads();
+    if (wave == 0) {
+        u64 k = ~0ull;
+#pragma unroll
+        for (int w = sub; w < W; w += RPI) {
+            const u64 o = skey[w][col];
+            k = o < k ? o : k;
+        }
+#pragma unroll
+        for (int off = 32; off >= TJ; off >>= 1) {
+            const u64 o = __shfl_xor(k, off, 64);
+            k = o < k ? o : k;
+        }
+        if (lane < TJ && j <= L) {
+            int64_t v = kInf;
+            int32_t bi = -1;
+            if (k != ~0ull) {
+                v = (int64_t)(k >> kBandRowBits);
+                bi = i_begin + (int32_t)(k & ((1u << kBandRowBits) - 1));
+            }
+            // every candidate infeasible: the lowest i of the whole range s-1 <= i < j holds that minimum
+            if (v >= kInf) {
+                v = kInf;
+                bi = j >= s ? s - 1 : -1;
+            }
+            cur_all[(int64_t)p * 2 * cols + j] = v;
+            cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
+            if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
+        }
+    }
+}
+
 __global__ void __launch_bounds__(64)
 si_bounds_kernel(int32_t B, int32_t L, int32_t S, int32_t s_query, const int32_t* __restrict__ cut,
                  int32_t* __restrict__ bounds) {
@@ -220,10 +322,20 @@ hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int32_t max_le
                        bottleneck, cut);
     const dim3 grid((unsigned)(lay.tiles * lay.splits), (unsigned)B);
     const dim3 merge_grid((unsigned)lay.tiles, (unsigned)B);
+    // 16 columns and 16 waves: 64 rows per round, five rounds for stages of at most 256 operators (narrower and
+    // wider tiles from 8 x 8 waves to 64 x 16 waves were timed: this shape and its neighbours are the fastest)
+    constexpr int kBandTile = 16, kBandWaves = 16, kBandInFlight = 8;
+    const bool band = max_len <= kBandMaxLen;
+    const dim3 band_grid((unsigned)((L + kBandTile) / kBandTile), (unsigned)B);
     for (int s = 2; s <= S; ++s) {
         // dp[s-1] sits in buffer (s-1) odd ? 0 : 1 of each problem
         const int64_t* prev_all = dp + (size_t)(s & 1) * cols;
         int64_t* cur_all = dp + (size_t)((s & 1) ^ 1) * cols;
+        if (band) {
+            hipLaunchKernelGGL((si_band_kernel<kBandTile, kBandWaves, kBandInFlight>), band_grid, dim3(kBandWaves * 64), 0,
+                               stream, L, S, s, max_len, ldT, T, T_bs, cols, prev_all, cur_all, bottleneck, cut);
+            continue;
+        }
         hipLaunchKernelGGL(si_step_kernel, grid, dim3(kSiWaves * 64), 0, stream, L, S, s, lay.splits, max_len, ldT, T, T_bs,
                            cols, prev_all, cur_all, pval, pidx, bottleneck, cut);
         if (lay.splits > 1)

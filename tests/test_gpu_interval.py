@@ -278,7 +278,8 @@ def test_table_with_a_limit_on_the_stage_length(L, K, Kp, B, max_len):
 
 
 @pytest.mark.parametrize("L,S,B,max_len", [(5, 5, 2, 1), (129, 16, 2, 10), (300, 33, 1, 40), (300, 7, 2, 30),
-                                           (1000, 64, 1, 100), (1000, 20, 1, 1000), (2051, 40, 1, 130)])
+                                           (1000, 64, 1, 100), (1000, 20, 1, 1000), (2051, 40, 1, 130),
+                                           (2051, 9, 2, 1024), (2051, 9, 1, 1025), (1025, 30, 1, 31), (64, 64, 3, 2)])
 def test_search_with_a_limit_on_the_stage_length(L, S, B, max_len):
     # any table: the search must ignore what it holds for longer stages; limits so tight that some stage counts
     # have no solution at all (S * max_len < L) are part of the cases
