@@ -453,7 +453,12 @@ hipError_t launch_stage_window(int32_t B, int32_t L, int32_t S, const int64_t* s
                                int32_t* bounds, void* workspace, hipStream_t stream) {
     if (B == 0) return hipSuccess;
     const StageLayout lay = layout_of(B, L, S);
-    const int splits = splits_of(B, L), tiles = tiles_of(L);
+    // A tile's rows: about (2 eps + 2) balanced stage lengths when the segments are of similar size.  Up to 1024 of
+    // them a workgroup takes them all -- a second launch per stage count to merge parts would cost more than it
+    // saves; wider windows (and bounds switched off) are split over workgroups as in the plain scan.  The choice
+    // changes the time only: the kernels handle any window with any split.
+    const double rows = eps_num < 0 ? (double)L : (2.0 * (double)eps_num / (double)eps_den + 2.0) * (double)L / (double)S;
+    const int splits = rows <= 1024.0 ? 1 : splits_of(B, L), tiles = tiles_of(L);
     char* wsb = static_cast<char*>(workspace);
     ll2* ws = reinterpret_cast<ll2*>(wsb);
     int64_t* pval = reinterpret_cast<int64_t*>(wsb + lay.pval_off);

@@ -61,6 +61,20 @@ def test_ties_zero_costs_and_no_split():
     assert check(spike, 8, None, 10, 1)[0] < INF
 
 
+def test_segments_of_very_different_size():
+    # thousands of cheap segments between a few heavy ones: whatever the tolerance suggests about the width of
+    # a stage count's window, a tile's rows here run into the thousands
+    rng = np.random.default_rng(17)
+    L, S = 5000, 16
+    cost = rng.integers(0, 3, size=(2, L)).astype(np.int64)
+    heavy = rng.choice(L, size=40, replace=False)
+    cost[0, heavy] = rng.integers(10**5, 10**6, size=40)
+    cost[1, heavy[:9]] = 10**6
+    xfer = rng.integers(0, 5000, size=(2, L + 1)).astype(np.int64)
+    for num, den in ((1, 2), (3, 1), (-1, 1)):
+        check(cost, S, xfer, num, den)
+
+
 def test_stage_partition_config_full_size_window():
     w = syn.STAGE_PARTITION
     cost = syn.segment_costs(0, w["L"], w["lo"], w["hi"])[None]
