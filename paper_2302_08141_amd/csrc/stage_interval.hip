@@ -5,8 +5,12 @@
 // system (the table of one problem, L^2 * 8 bytes, is re-read S-1 times and mostly stays in the
 // last-level cache): rows of T are read with coalesced 16-byte loads, two j per lane, eight rows
 // in flight per lane; dp[s-1][i] is uniform over a wave and comes through scalar loads.
-// A workgroup owns 128 consecutive j; its 4 waves take the rows i round-robin; with few problems
-// the i range is also split over several workgroups and a small kernel merges the parts.
+// A workgroup owns 128 consecutive j; its 4 waves take the rows i round-robin.  With few problems
+// the i range is also split over several workgroups.  Their results meet without a launch of their
+// own: per stage count and column one word (value << 6 | part) collects the parts' minima through an
+// atomic minimum -- parts hold ascending rows, so the least word names the least value and the lowest
+// part that reaches it -- each part keeps the row it found, and the next stage count's launch reads
+// dp[s-1] straight from the words and turns them into cut entries on the side.
 // When no stage may be longer than 1024 operators a column has few candidate rows and one launch
 // per stage count does it all (si_band_kernel below).
 #include "kernels.h"
@@ -20,12 +24,14 @@ constexpr int kSiWaves = 4;
 constexpr int kSiTile = 128;            // j per workgroup
 constexpr int kSiUnroll = 8;
 
+constexpr int kSiPartBits = 6;          // up to 32 parts; value <= 2^52, so a word stays below 2^59
+
 struct SiLayout {
-    size_t dp_off, pval_off, pidx_off, total;
+    size_t dp_off, key_off, pidx_off, total;
     int splits, tiles;
 };
 
-__host__ inline SiLayout si_layout(int32_t B, int32_t L) {
+__host__ inline SiLayout si_layout(int32_t B, int32_t L, int32_t S) {
     SiLayout s;
     s.tiles = (L + 1 + kSiTile - 1) / kSiTile;
     int splits = 1;
@@ -34,18 +40,31 @@ __host__ inline SiLayout si_layout(int32_t B, int32_t L) {
     s.splits = splits;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t cols = (size_t)s.tiles * kSiTile;
+    // dp: two buffers per problem (the route of limited stage length); keys: one row of words per stage count and
+    // problem; pidx: the parts' rows, two sets that alternate with the stage count
     s.dp_off = 0;
-    s.pval_off = up((size_t)B * 2 * cols * sizeof(int64_t));
-    s.pidx_off = s.pval_off + up((size_t)B * splits * cols * sizeof(int64_t));
-    s.total = s.pidx_off + up((size_t)B * splits * cols * sizeof(int32_t));
+    s.key_off = up((size_t)B * 2 * cols * sizeof(int64_t));
+    s.pidx_off = s.key_off + up((size_t)B * (size_t)S * cols * sizeof(int64_t));
+    s.total = s.pidx_off + up(2 * (size_t)B * splits * cols * sizeof(int32_t));
     return s;
+}
+
+typedef unsigned long long u64;
+
+// dp value held by a word: words that no part has touched (all ones) and infeasible minima read as "infeasible"
+__device__ __forceinline__ int64_t key_value(u64 k) {
+    const u64 v = k >> kSiPartBits;
+    return (int64_t)(v < (u64)kInf ? v : (u64)kInf);
 }
 
 __global__ void __launch_bounds__(256)
 si_init_kernel(int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* __restrict__ T, int64_t T_bs, int64_t cols,
-               int64_t* __restrict__ dp, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+               int64_t* __restrict__ dp, u64* __restrict__ keys, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
     const int p = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= cols) return;
+    if (keys != nullptr)                                   // no part has reported anything for s >= 2 yet
+        for (int s = 2; s <= S; ++s) keys[((int64_t)p * S + (s - 1)) * cols + j] = ~0ull;
     if (j > L) return;
     const int64_t* row0 = T + (int64_t)p * T_bs;
     int64_t v = kInf;
@@ -53,17 +72,34 @@ si_init_kernel(int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t
         v = row0[j];
         v = v < kInf ? v : kInf;
     }
-    dp[(int64_t)p * 2 * cols + j] = v;                      // buffer 0 = dp[1]
+    if (keys != nullptr) keys[(int64_t)p * S * cols + j] = (u64)v << kSiPartBits;      // dp[1]
+    else dp[(int64_t)p * 2 * cols + j] = v;                 // buffer 0 = dp[1]
     cut[(int64_t)p * S * (L + 1) + j] = j >= 1 ? 0 : -1;
     if (j == L) bottleneck[(int64_t)p * S] = v;
+}
+
+// What the parts of stage count s left for column j, turned into dp[s][j]'s cut entry (and the bottleneck).
+__device__ __forceinline__ void si_decode(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t cols, int p, int j,
+                                          const u64* __restrict__ keys, const int32_t* __restrict__ pidx,
+                                          int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+    const u64 k = keys[((int64_t)p * S + (s - 1)) * cols + j];
+    const int64_t v = key_value(k);
+    int32_t bi = -1;
+    if (v < kInf) {
+        const int part = (int)(k & ((1u << kSiPartBits) - 1));
+        bi = pidx[(((int64_t)(s & 1) * gridDim.y + p) * splits + part) * cols + j];
+    } else {
+        bi = j >= s ? s - 1 : -1;       // every candidate infeasible: the lowest i of the range holds that minimum
+    }
+    cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
+    if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
 }
 
 // One stage count s for the tile blockIdx.x / splits of problem blockIdx.y, rows of split blockIdx.x % splits.
 __global__ void __launch_bounds__(kSiWaves * 64)
 si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int32_t max_len, int64_t ldT, const int64_t* __restrict__ T,
-               int64_t T_bs, int64_t cols, const int64_t* __restrict__ prev_all, int64_t* __restrict__ cur_all,
-               int64_t* __restrict__ pval, int32_t* __restrict__ pidx, int64_t* __restrict__ bottleneck,
-               int32_t* __restrict__ cut) {
+               int64_t T_bs, int64_t cols, u64* __restrict__ keys, int32_t* __restrict__ pidx,
+               int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
     __shared__ int64_t sval[kSiWaves][kSiTile];
     __shared__ int32_t sidx[kSiWaves][kSiTile];
     const int tid = threadIdx.x;
@@ -72,7 +108,7 @@ si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int32_t max_len,
     const int tile = blockIdx.x / splits, split = blockIdx.x % splits;
     const int p = blockIdx.y;
     const int64_t* Tp = T + (int64_t)p * T_bs;
-    const int64_t* prev = prev_all + (int64_t)p * 2 * cols;
+    const u64* prev = keys + ((int64_t)p * S + (s - 2)) * cols;     // the words of stage count s - 1
     const int j0 = tile * kSiTile + 2 * lane;               // this lane's j0 and j0 + 1
     const bool in_range = j0 <= L;                          // then j0 + 1 < ldT (ldT is even and > L)
 
@@ -109,13 +145,16 @@ si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int32_t max_len,
             for (int u = 0; u < kSiUnroll; ++u) {
                 const int r = i + u * kSiWaves;
                 t[u] = *reinterpret_cast<const ll2*>(col + (int64_t)r * ldT);
-                a[u] = prev[r];
+                a[u] = key_value(prev[r]);
             }
 #pragma unroll
             for (int u = 0; u < kSiUnroll; ++u) relax(i + u * kSiWaves, t[u], a[u]);
         }
-        for (; i < hi; i += kSiWaves) relax(i, *reinterpret_cast<const ll2*>(col + (int64_t)i * ldT), prev[i]);
+        for (; i < hi; i += kSiWaves) relax(i, *reinterpret_cast<const ll2*>(col + (int64_t)i * ldT), key_value(prev[i]));
     }
+    // the cut entries of stage count s - 1, whose parts all reported before this launch began
+    if (split == 0 && s > 2 && splits > 1 && tid < kSiTile && tile * kSiTile + tid <= L)
+        si_decode(L, S, s - 1, splits, cols, p, tile * kSiTile + tid, keys, pidx, bottleneck, cut);
     sval[wave][2 * lane] = best0;
     sval[wave][2 * lane + 1] = best1;
     sidx[wave][2 * lane] = idx0;
@@ -134,53 +173,30 @@ si_step_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int32_t max_len,
             bi = take ? vi : bi;
         }
         const int j = tile * kSiTile + tid;
+        u64* mine = keys + ((int64_t)p * S + (s - 1)) * cols + j;
         if (splits > 1) {
-            const int64_t at = ((int64_t)p * splits + split) * cols + j;
-            pval[at] = b;
-            pidx[at] = bi;
+            if (bi >= 0 && j <= L) {
+                pidx[(((int64_t)(s & 1) * gridDim.y + p) * splits + split) * cols + j] = bi;
+                atomicMin(mine, ((u64)b << kSiPartBits) | (u64)split);
+            }
         } else if (j <= L) {
             const int64_t v = bi >= 0 ? b : kInf;
             // every candidate infeasible: the lowest i of the whole range s-1 <= i < j holds that minimum
             if (v >= kInf) bi = j >= s ? s - 1 : -1;
-            cur_all[(int64_t)p * 2 * cols + j] = v;
+            *mine = (u64)v << kSiPartBits;
             cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
             if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
         }
     }
 }
 
-__global__ void __launch_bounds__(kSiTile)
-si_merge_kernel(int32_t L, int32_t S, int32_t s, int32_t splits, int64_t cols, int64_t* __restrict__ cur_all,
-                const int64_t* __restrict__ pval, const int32_t* __restrict__ pidx,
-                int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
+// The cut entries of the last stage count, then the boundaries of the requested one.
+__global__ void __launch_bounds__(256)
+si_finish_kernel(int32_t L, int32_t S, int32_t splits, int64_t cols, const u64* __restrict__ keys,
+                 const int32_t* __restrict__ pidx, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
     const int p = blockIdx.y;
-    const int j = blockIdx.x * kSiTile + threadIdx.x;
-    if (j > L) return;
-    int64_t b = INT64_MAX;
-    int32_t bi = -1;
-    // splits hold ascending row ranges: the first strict minimum wins; eight parts are fetched at a time
-    for (int k0 = 0; k0 < splits; k0 += 8) {
-        int64_t v[8];
-        int32_t vi[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int k = k0 + u < splits ? k0 + u : splits - 1;     // a repeated part changes nothing
-            const int64_t at = ((int64_t)p * splits + k) * cols + j;
-            v[u] = pval[at];
-            vi[u] = pidx[at];
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const bool take = vi[u] >= 0 && (bi < 0 || v[u] < b);
-            b = take ? v[u] : b;
-            bi = take ? vi[u] : bi;
-        }
-    }
-    const int64_t v = bi >= 0 ? b : kInf;
-    if (v >= kInf) bi = j >= s ? s - 1 : -1;      // every candidate infeasible: the lowest i of the range holds that minimum
-    cur_all[(int64_t)p * 2 * cols + j] = v;
-    cut[((int64_t)p * S + (s - 1)) * (L + 1) + j] = bi;
-    if (j == L) bottleneck[(int64_t)p * S + (s - 1)] = v;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j <= L) si_decode(L, S, S, splits, cols, p, j, keys, pidx, bottleneck, cut);
 }
 
 // The same stage count when no stage is longer than max_len <= kBandMaxLen operators: column j has at most max_len
@@ -301,47 +317,43 @@ si_bounds_kernel(int32_t B, int32_t L, int32_t S, int32_t s_query, const int32_t
 
 }  // namespace
 
-size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S) {
-    (void)S;
-    return si_layout(B, L).total;
-}
+size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S) { return si_layout(B, L, S).total; }
 
 hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* T, int64_t* bottleneck,
                                  int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                                  hipStream_t stream) {
     if (B == 0) return hipSuccess;
-    const SiLayout lay = si_layout(B, L);
+    const SiLayout lay = si_layout(B, L, S);
     if (max_len > L) max_len = L;
     const int64_t cols = (int64_t)lay.tiles * kSiTile;
     const int64_t T_bs = (int64_t)L * ldT;
     char* ws = static_cast<char*>(workspace);
     int64_t* dp = reinterpret_cast<int64_t*>(ws + lay.dp_off);
-    int64_t* pval = reinterpret_cast<int64_t*>(ws + lay.pval_off);
+    u64* keys = reinterpret_cast<u64*>(ws + lay.key_off);
     int32_t* pidx = reinterpret_cast<int32_t*>(ws + lay.pidx_off);
-    hipLaunchKernelGGL(si_init_kernel, dim3((L + 256) / 256, B), dim3(256), 0, stream, L, S, max_len, ldT, T, T_bs, cols, dp,
-                       bottleneck, cut);
-    const dim3 grid((unsigned)(lay.tiles * lay.splits), (unsigned)B);
-    const dim3 merge_grid((unsigned)lay.tiles, (unsigned)B);
     // 16 columns and 16 waves: 64 rows per round, five rounds for stages of at most 256 operators (narrower and
     // wider tiles from 8 x 8 waves to 64 x 16 waves were timed: this shape and its neighbours are the fastest)
     constexpr int kBandTile = 16, kBandWaves = 16, kBandInFlight = 8;
     const bool band = max_len <= kBandMaxLen;
+    hipLaunchKernelGGL(si_init_kernel, dim3((unsigned)((cols + 255) / 256), B), dim3(256), 0, stream, L, S, max_len, ldT, T,
+                       T_bs, cols, dp, band ? nullptr : keys, bottleneck, cut);
+    const dim3 grid((unsigned)(lay.tiles * lay.splits), (unsigned)B);
     const dim3 band_grid((unsigned)((L + kBandTile) / kBandTile), (unsigned)B);
     for (int s = 2; s <= S; ++s) {
-        // dp[s-1] sits in buffer (s-1) odd ? 0 : 1 of each problem
-        const int64_t* prev_all = dp + (size_t)(s & 1) * cols;
-        int64_t* cur_all = dp + (size_t)((s & 1) ^ 1) * cols;
         if (band) {
+            // dp[s-1] sits in buffer (s-1) odd ? 0 : 1 of each problem
+            const int64_t* prev_all = dp + (size_t)(s & 1) * cols;
+            int64_t* cur_all = dp + (size_t)((s & 1) ^ 1) * cols;
             hipLaunchKernelGGL((si_band_kernel<kBandTile, kBandWaves, kBandInFlight>), band_grid, dim3(kBandWaves * 64), 0,
                                stream, L, S, s, max_len, ldT, T, T_bs, cols, prev_all, cur_all, bottleneck, cut);
             continue;
         }
         hipLaunchKernelGGL(si_step_kernel, grid, dim3(kSiWaves * 64), 0, stream, L, S, s, lay.splits, max_len, ldT, T, T_bs,
-                           cols, prev_all, cur_all, pval, pidx, bottleneck, cut);
-        if (lay.splits > 1)
-            hipLaunchKernelGGL(si_merge_kernel, merge_grid, dim3(kSiTile), 0, stream, L, S, s, lay.splits, cols,
-                               cur_all, pval, pidx, bottleneck, cut);
+                           cols, keys, pidx, bottleneck, cut);
     }
+    if (!band && lay.splits > 1 && S >= 2)
+        hipLaunchKernelGGL(si_finish_kernel, dim3((unsigned)((L + 256) / 256), (unsigned)B), dim3(256), 0, stream, L, S,
+                           lay.splits, cols, keys, pidx, bottleneck, cut);
     if (s_query > 0 && bounds != nullptr)
         hipLaunchKernelGGL(si_bounds_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, B, L, S, s_query, cut, bounds);
     return hipGetLastError();
