@@ -57,11 +57,28 @@ inline StageLayout layout_of(int32_t B, int32_t L, int32_t S_window = 0) {
     return o;
 }
 
+// Exclusive prefix sum of one value per thread over the kScanThreads threads of a workgroup (inside a wave by
+// shuffles, the four wave totals through LDS).
+__device__ __forceinline__ int64_t scan_exclusive(int64_t mine, int64_t* wave_sum) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t o = __shfl_up(incl, off, 64);
+        incl += lane >= off ? o : 0;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int64_t base = 0;
+    for (int w = 0; w < wave; ++w) base += wave_sum[w];
+    return base + incl - mine;
+}
+
 // P and the s = 1 row.  One workgroup per problem; thread t sums a contiguous slice.
 __global__ void __launch_bounds__(kScanThreads)
 stage_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, ll2* __restrict__ ws,
                   int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
-    __shared__ int64_t part[kScanThreads];
+    __shared__ int64_t part[kScanThreads / 64];
     const int p = blockIdx.x, t = threadIdx.x;
     const int64_t* cs = cost + (int64_t)p * L;
     ll2* buf0 = ws + (size_t)p * pairs_per_problem(L);
@@ -72,18 +89,7 @@ stage_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, ll2* _
     const int hi = lo + per < L ? lo + per : L;
     int64_t s = 0;
     for (int l = lo; l < hi; ++l) s += cs[l];
-    part[t] = s;
-    __syncthreads();
-    if (t == 0) {
-        int64_t run = 0;
-        for (int k = 0; k < kScanThreads; ++k) {
-            const int64_t x = part[k];
-            part[k] = run;
-            run += x;
-        }
-    }
-    __syncthreads();
-    int64_t run = part[t];
+    int64_t run = scan_exclusive(s, part);
     if (t == 0) {
         ll2 z; z.x = 0; z.y = 0;
         buf0[0] = z; buf1[0] = z;
@@ -106,29 +112,30 @@ stage_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, ll2* _
 // for the stage count s they reduce to "i >= first_i[s]" and "j <= last_j[s]".
 typedef __int128 i128;
 
-__device__ inline int64_t floor_div(i128 a, i128 b) {   // b > 0
-    i128 q = a / b;
-    if (a % b != 0 && a < 0) --q;
-    return (int64_t)q;
-}
-
-// lowest / highest stage segment l may sit in; lo = S means "none"
-__device__ inline void stage_bounds_of(int64_t Pl, int64_t PL, int32_t S, int64_t num, int64_t den, int32_t* lo,
-                                       int32_t* hi) {
-    *lo = 0;
-    *hi = S - 1;
-    if (num < 0 || PL <= 0) return;
+// Segment l, whose earliest start is Pl = P(l), may sit in stage t only if lo(l) <= t <= hi(l) with
+//     lo(l) = floor(Pl S / PL - eps) cut off to [0, S] (S = "none"),  hi(l) = ceil(Pl S / PL + eps) cut off to [0, S-1].
+// The searches below only ask "hi(l) >= t" and "lo(l) <= t" for 0 <= t <= S-1; with x = Pl S den, e = num PL,
+// d = PL den (all below 2^86) these are the division-free comparisons
+//     hi(l) >= t  <=>  t = 0 or ceil((x + e) / d) >= t   <=>  t = 0 or x + e > (t - 1) d
+//     lo(l) <= t  <=>  floor((x - e) / d) <= t           <=>  x - e < (t + 1) d
+// (the cut-offs change neither: hi is cut to S-1 >= t, lo to 0 <= t or to S > t).  A negative eps or a chain
+// without any work switches the bounds off.
+__device__ inline bool hi_at_least(int64_t Pl, int64_t PL, int32_t S, int64_t num, int64_t den, int32_t t) {
+    if (num < 0 || PL <= 0 || t <= 0) return true;
     const i128 x = (i128)Pl * S * den, e = (i128)num * PL, d = (i128)PL * den;
-    const int64_t f = floor_div(x - e, d), c = -floor_div(-(x + e), d);
-    *lo = (int32_t)(f < 0 ? 0 : (f > S - 1 ? S : f));
-    *hi = (int32_t)(c > S - 1 ? S - 1 : (c < 0 ? 0 : c));
+    return x + e > (i128)(t - 1) * d;
+}
+__device__ inline bool lo_at_most(int64_t Pl, int64_t PL, int32_t S, int64_t num, int64_t den, int32_t t) {
+    if (num < 0 || PL <= 0) return true;
+    const i128 x = (i128)Pl * S * den, e = (i128)num * PL, d = (i128)PL * den;
+    return x - e < (i128)(t + 1) * d;
 }
 
 __global__ void __launch_bounds__(kScanThreads)
 stage_window_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost, const int64_t* __restrict__ xfer,
                          int64_t eps_num, int64_t eps_den, ll2* __restrict__ ws, int64_t* __restrict__ pfull,
                          int32_t* __restrict__ win, int64_t* __restrict__ bottleneck, int32_t* __restrict__ cut) {
-    __shared__ int64_t part[kScanThreads];
+    __shared__ int64_t part[kScanThreads / 64];
     const int p = blockIdx.x, t = threadIdx.x;
     const int64_t* cs = cost + (int64_t)p * L;
     const int64_t* xf = xfer != nullptr ? xfer + (int64_t)p * (L + 1) : nullptr;
@@ -142,19 +149,7 @@ stage_window_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost,
     const int hi = lo + per < L ? lo + per : L;
     int64_t sum = 0;
     for (int l = lo; l < hi; ++l) sum += cs[l];
-    part[t] = sum;
-    __syncthreads();
-    if (t == 0) {
-        int64_t run = 0;
-        for (int k = 0; k < kScanThreads; ++k) {
-            const int64_t x = part[k];
-            part[k] = run;
-            run += x;
-        }
-        part[0] = 0;
-    }
-    __syncthreads();
-    int64_t run = part[t];
+    int64_t run = scan_exclusive(sum, part);
     if (t == 0) Pp[0] = 0;
     for (int l = lo; l < hi; ++l) {
         run += cs[l];
@@ -167,17 +162,13 @@ stage_window_init_kernel(int32_t L, int32_t S, const int64_t* __restrict__ cost,
         int a = 0, b = L;                       // first i in [0, L] with hi(i) >= st (hi grows with i)
         while (a < b) {
             const int m = (a + b) / 2;
-            int32_t l_, h_;
-            stage_bounds_of(Pp[m], PL, S, eps_num, eps_den, &l_, &h_);
-            if (h_ >= st) b = m; else a = m + 1;
+            if (hi_at_least(Pp[m], PL, S, eps_num, eps_den, st)) b = m; else a = m + 1;
         }
         wp[2 * st] = a;
         int a2 = -1, b2 = L - 1;                // last l in [-1, L-1] with lo(l) <= st (lo grows with l)
         while (a2 < b2) {
             const int m = (a2 + b2 + 1) / 2;
-            int32_t l_, h_;
-            stage_bounds_of(Pp[m], PL, S, eps_num, eps_den, &l_, &h_);
-            if (l_ <= st) a2 = m; else b2 = m - 1;
+            if (lo_at_most(Pp[m], PL, S, eps_num, eps_den, st)) a2 = m; else b2 = m - 1;
         }
         wp[2 * st + 1] = a2 + 1;
     }
