@@ -463,12 +463,16 @@ int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT,
  *     cut as rh_stage_dp_interval: where no candidate is feasible, dp = RH_INF and cut = s-1
  * i.e. exactly what the unlimited calls return on a table whose entries with j - i > max_len are
  * RH_INF (the search ignores whatever T holds there).  max_len >= 1; max_len >= L is no limit.
- * With max_len <= L/2 the table costs about (max_len + 15) / (L/2) of the full one.
+ * With max_len <= L/2 the table costs about (max_len + 15) / (L/2) of the full one row by row.
+ * The optional workspace of rh_interval_costs serves here too (same size, same conditions, and
+ * max_len > 128): the table is then put together from blocks, and only pairs of blocks that an
+ * interval of max_len operators can span are multiplied.
  * All other arguments as rh_interval_costs / rh_stage_dp_interval.
  */
 int rh_interval_costs_banded(int32_t B, int32_t L, int32_t Kp, int32_t max_len,
                              const int64_t* c, const int64_t* R, int64_t ldT,
-                             int64_t* T, void* stream);
+                             int64_t* T, void* workspace, size_t workspace_bytes,
+                             void* stream);
 int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len,
                                 int64_t ldT, const int64_t* T, int64_t* bottleneck,
                                 int32_t* cut, int32_t s_query, int32_t* bounds,

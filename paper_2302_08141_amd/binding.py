@@ -75,7 +75,7 @@ def lib():
         L.rh_static_scratch_bytes.restype = sz
         L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, sz, vp]
         L.rh_stage_dp_interval.argtypes = [i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
-        L.rh_interval_costs_banded.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp, vp]
+        L.rh_interval_costs_banded.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp, vp, sz, vp]
         L.rh_stage_dp_interval_banded.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_interval_costs_banded.restype = L.rh_stage_dp_interval_banded.restype = ctypes.c_int
         L.rh_workspace_size.argtypes = [i32, i32, i32, i32]
@@ -330,12 +330,15 @@ def rh_stage_dp_interval(B: int, L: int, S: int, ldT: int, T, bottleneck, cut, s
                                       ws_bytes, _stream()), "rh_stage_dp_interval")
 
 
-def rh_interval_costs_banded(B: int, L: int, Kp: int, max_len: int, c, R, ldT: int, T):
-    """rh_interval_costs with no stage longer than max_len operators: T[i][j] = RH_INF for j - i > max_len."""
+def rh_interval_costs_banded(B: int, L: int, Kp: int, max_len: int, c, R, ldT: int, T, workspace=None):
+    """rh_interval_costs with no stage longer than max_len operators: T[i][j] = RH_INF for j - i > max_len.
+    workspace: optional uint8 tensor of rh_workspace_size(WS_INTERVAL_COSTS, B, L, Kp) bytes."""
     b, l, k = max(B, 0), max(L, 0), max(Kp, 0)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().rh_interval_costs_banded(B, L, Kp, max_len, _ptr(c, torch.int64, "c", b * l * k),
                                           _ptr(R, torch.int64, "R", b * max(l - 1, 0) * k * k), ldT,
-                                          _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), _stream()),
+                                          _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), ws_ptr, ws_bytes, _stream()),
            "rh_interval_costs_banded")
 
 

@@ -32,10 +32,10 @@ constexpr int kLds = kTile + 2;              // row stride of a staged tile in L
 
 // C[i][n] = min_x A[i][x] + Bm[x][n] (saturated) for i < m, n < nn (both <= 64), x < 64.  256 threads; thread
 // (tx, ty) keeps a 4 x 4 corner of the tile.  As (transposed, [x][i]) and Bs ([x][n]) are LDS tiles of kK * kLds
-// doubles.
+// doubles.  With a limit on the interval length (the tiles of T only) entries beyond it are stored as infeasible.
 __device__ __forceinline__ void mm_tile(const int64_t* __restrict__ A, int64_t lda, int m, const int64_t* __restrict__ Bm,
                                         int64_t ldb, int nn, int64_t* __restrict__ C, int64_t ldc, double* As,
-                                        double* Bs) {
+                                        double* Bs, int len0 = 0, int max_len = INT32_MAX) {
     const int tid = threadIdx.x;
     const int lx = tid & 63, l4 = tid >> 6;
 #pragma unroll 4
@@ -74,19 +74,24 @@ __device__ __forceinline__ void mm_tile(const int64_t* __restrict__ A, int64_t l
         for (int k = 0; k < 4; ++k) {
             const int n = 4 * tx + k;
             const double v = __builtin_fmin(acc[r][k], kInfD);
-            if (i < m && n < nn) C[(int64_t)i * ldc + n] = to_i64(v);
+            // entry (i, n) stands for an interval of len0 + n - i operators: longer than max_len counts as infeasible
+            if (i < m && n < nn) C[(int64_t)i * ldc + n] = len0 + n - i > max_len ? kInf : to_i64(v);
         }
     }
 }
 
 // T[i][j] = infeasible for the columns left of row i's own block (the row sweeps write the rest of the columns at
-// and left of the diagonal themselves).
+// and left of the diagonal themselves) and, when intervals are limited in length, for the columns right of the
+// last block that the row's pairs of blocks reach (dq = how many blocks lie between the two of a pair at most).
 __global__ void __launch_bounds__(256)
-ib_fill_kernel(int32_t L, int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
+ib_fill_kernel(int32_t L, int32_t dq, int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
     const int i = blockIdx.x;
-    const int n = (i / kBlk) * kBlk;
+    const int pb = i / kBlk;
+    const int n = pb * kBlk;
     int64_t* row = T + (int64_t)blockIdx.y * T_bs + (int64_t)i * ldT;
     for (int j = threadIdx.x; j < n; j += 256) row[j] = kInf;
+    const int64_t reach = ((int64_t)pb + dq + 2) * kBlk;          // the pairs (pb, pb .. pb + dq) end at this column
+    for (int64_t j = reach + 1 + threadIdx.x; j <= L; j += 256) row[j] = kInf;
 }
 
 // Chain p: P[p][q] = P[p][q-1] (x) M[q] for q = p + 2 .. nb - 2, with P[p][p+1] = M[p+1].  The rows of a product only
@@ -96,7 +101,7 @@ ib_fill_kernel(int32_t L, int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
 constexpr int kPrefixWaves = 8;
 constexpr int kPrefixSplit = 4;
 __global__ void __launch_bounds__(kPrefixWaves * 64)
-ib_prefix_kernel(int32_t nb, const int64_t* __restrict__ M, int64_t* __restrict__ P, int64_t ws_bs) {
+ib_prefix_kernel(int32_t nb, int32_t dq, const int64_t* __restrict__ M, int64_t* __restrict__ P, int64_t ws_bs) {
     constexpr int kThreads = kPrefixWaves * 64, kPairs = kK / kPrefixSplit / kPrefixWaves / 2, kEpt = kK * kK / kThreads;
     static_assert(kPairs >= 1, "two rows per wave at least");
     extern __shared__ double tiles[];             // two tables of Kp x Kp
@@ -106,7 +111,7 @@ ib_prefix_kernel(int32_t nb, const int64_t* __restrict__ M, int64_t* __restrict_
     M += (int64_t)blockIdx.y * ws_bs;
     P += (int64_t)blockIdx.y * ws_bs;
     const int64_t mat = (int64_t)kK * kK;
-    const int q0 = p + 2, q1 = nb - 2;
+    const int q0 = p + 2, q1 = p + dq < nb - 2 ? p + dq : nb - 2;   // products beyond p + dq serve no pair
     if (q0 > q1) return;
     const int row0 = (part * kPrefixWaves + wave) * 2 * kPairs;   // this wave's rows: row0 .. row0 + 2 kPairs - 1
     double V[kPairs][2][1];
@@ -169,9 +174,10 @@ ib_left_kernel(int32_t nb, const int32_t* __restrict__ pair_p, const int32_t* __
 __global__ void __launch_bounds__(256)
 ib_tiles_kernel(int32_t L, int32_t nb, const int32_t* __restrict__ pair_p, const int32_t* __restrict__ pair_q,
                 const int64_t* __restrict__ A, const int64_t* __restrict__ U, const int64_t* __restrict__ Z,
-                int64_t ws_bs, int64_t ldT, int64_t* __restrict__ T, int64_t T_bs) {
+                int64_t ws_bs, int64_t ldT, int64_t* __restrict__ T, int64_t T_bs, int32_t max_len) {
     extern __shared__ double tiles[];
     const int p = pair_p[blockIdx.y], q = pair_q[blockIdx.y];
+    if (p < 0 || q < p) return;                   // an unused slot of the pair list
     const int ti = blockIdx.x >> 1, tj = blockIdx.x & 1;
     const int col0 = (q + 1) * kBlk;              // B(q+1)
     const int n_t = L - col0 < kBlk ? L - col0 : kBlk;        // columns col0 + 1 .. col0 + n_t
@@ -182,7 +188,8 @@ ib_tiles_kernel(int32_t L, int32_t nb, const int32_t* __restrict__ pair_p, const
                                : U + off + (((int64_t)p * nb + q) * kBlk + ti * kTile) * kK;
     const int64_t* Zq = Z + off + (int64_t)(q + 1) * kK * kLdz + 1 + tj * kTile;   // entry t = 1 + n of every row z
     int64_t* Tt = T + (int64_t)blockIdx.z * T_bs + ((int64_t)p * kBlk + ti * kTile) * ldT + col0 + 1 + tj * kTile;
-    mm_tile(Up, kK, kTile, Zq, kLdz, nn, Tt, ldT, tiles, tiles + kK * kLds);
+    mm_tile(Up, kK, kTile, Zq, kLdz, nn, Tt, ldT, tiles, tiles + kK * kLds,
+            col0 + 1 + tj * kTile - (p * kBlk + ti * kTile), max_len);
 }
 
 struct IbLayout {
@@ -194,7 +201,7 @@ struct IbLayout {
 IbLayout ib_layout(int32_t B, int32_t L) {
     IbLayout o{};
     o.nb = (L + kBlk - 1) / kBlk;
-    o.n_pairs = (o.nb - 1) * o.nb / 2;            // 0 <= p <= q <= nb - 2
+    o.n_pairs = (o.nb - 1) * (o.nb - 1);          // slots (p, p + d), 0 <= p <= nb - 2, 0 <= d <= nb - 2, at most
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t nb = (size_t)o.nb, mat = (size_t)kK * kK * 8;
     o.a_off = 0;
@@ -208,20 +215,16 @@ IbLayout ib_layout(int32_t B, int32_t L) {
     return o;
 }
 
-// the pair lists (p, q), 0 <= p <= q <= nb - 2, written by the device itself: nothing is copied from the host
+// the pair lists, written by the device itself (nothing is copied from the host): slot t stands for p = t / (dq + 1),
+// q = p + t % (dq + 1); a slot whose q lies beyond the last-but-one block is marked (-1, -1) and skipped by the kernels
 __global__ void __launch_bounds__(256)
-ib_pairs_kernel(int32_t nb, int32_t n_pairs, int32_t* __restrict__ pair_p, int32_t* __restrict__ pair_q) {
+ib_pairs_kernel(int32_t nb, int32_t dq, int32_t n_pairs, int32_t* __restrict__ pair_p, int32_t* __restrict__ pair_q) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= n_pairs) return;
-    // pairs in the order p = 0: q = 0 .. nb-2; p = 1: q = 1 .. nb-2; ...
-    int p = 0, first = 0, len = nb - 1;
-    while (t >= first + len) {
-        first += len;
-        --len;
-        ++p;
-    }
-    pair_p[t] = p;
-    pair_q[t] = p + (t - first);
+    const int p = t / (dq + 1), q = p + t % (dq + 1);
+    const bool ok = q <= nb - 2;
+    pair_p[t] = ok ? p : -1;
+    pair_q[t] = ok ? q : -1;
 }
 
 }  // namespace
@@ -232,11 +235,17 @@ size_t interval_blocks_workspace_bytes(int32_t B, int32_t L, int32_t Kp) {
     return ib_layout(B, L).total;
 }
 
-hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, const int64_t* c, const int64_t* R, int64_t ldT,
-                                         int64_t* T, void* workspace, hipStream_t stream) {
+hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, int32_t max_len, const int64_t* c, const int64_t* R,
+                                         int64_t ldT, int64_t* T, void* workspace, hipStream_t stream) {
     if (B == 0) return hipSuccess;
+    if (max_len < kBlk + 1) return hipErrorInvalidValue;      // the sweeps inside a block run to its end
     const IbLayout lay = ib_layout(B, L);
     const int nb = lay.nb;
+    // Rows of block p and columns of block q + 1 are at least (q - p) kBlk + 2 operators apart: pairs further
+    // apart hold no interval within the limit.
+    int dq = (int)(((int64_t)max_len - 2) / kBlk);
+    dq = dq < nb - 2 ? dq : nb - 2;
+    const int n_pairs = (nb - 1) * (dq + 1);
     char* ws = static_cast<char*>(workspace);
     int64_t* A = reinterpret_cast<int64_t*>(ws + lay.a_off);
     int64_t* Z = reinterpret_cast<int64_t*>(ws + lay.z_off);
@@ -244,15 +253,15 @@ hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, const int64_t* c,
     int64_t* P = reinterpret_cast<int64_t*>(ws + lay.p_off);
     int64_t* U = reinterpret_cast<int64_t*>(ws + lay.u_off);
     int32_t* pair_p = reinterpret_cast<int32_t*>(ws + lay.pair_off);
-    int32_t* pair_q = pair_p + lay.n_pairs;
+    int32_t* pair_q = pair_p + lay.n_pairs;       // (room for the largest list)
     const int64_t ws_bs = (int64_t)(lay.per_problem / 8);
     const int64_t c_bs = (int64_t)L * kK, R_bs = (int64_t)(L - 1) * kK * kK, T_bs = (int64_t)L * ldT;
     const int64_t c_st = (int64_t)kBlk * kK, R_st = (int64_t)kBlk * kK * kK;
     hipError_t e;
 
-    hipLaunchKernelGGL(ib_pairs_kernel, dim3((unsigned)((lay.n_pairs + 255) / 256)), dim3(256), 0, stream, nb,
-                       lay.n_pairs, pair_p, pair_q);
-    hipLaunchKernelGGL(ib_fill_kernel, dim3((unsigned)L, (unsigned)B), dim3(256), 0, stream, L, ldT, T, T_bs);
+    hipLaunchKernelGGL(ib_pairs_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, stream, nb, dq, n_pairs,
+                       pair_p, pair_q);
+    hipLaunchKernelGGL(ib_fill_kernel, dim3((unsigned)L, (unsigned)B), dim3(256), 0, stream, L, dq, ldT, T, T_bs);
     // row sweeps inside the blocks, one operator into the next block: the table's entries there, and A (the last
     // block stops at the chain's end and leaves no A)
     IntervalParts rows{nb, c_st, R_st, (int64_t)kBlk * (ldT + 1), kBlk, A, (int64_t)kBlk * kK, ws_bs, kBlk, L};
@@ -272,13 +281,14 @@ hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, const int64_t* c,
         e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(lds > lds_prefix ? lds : lds_prefix));
         if (e != hipSuccess) return e;
     }
-    if (nb > 3)
+    if (nb > 3 && dq >= 2)
         hipLaunchKernelGGL(ib_prefix_kernel, dim3((unsigned)((nb - 3) * kPrefixSplit), (unsigned)B), dim3(kPrefixWaves * 64), lds_prefix,
-                           stream, nb, M, P, ws_bs);
-    hipLaunchKernelGGL(ib_left_kernel, dim3(kBlk / kTile, (unsigned)lay.n_pairs, (unsigned)B), dim3(256), lds, stream,
-                       nb, pair_p, pair_q, A, M, P, U, ws_bs);
-    hipLaunchKernelGGL(ib_tiles_kernel, dim3(4, (unsigned)lay.n_pairs, (unsigned)B), dim3(256), lds, stream, L, nb,
-                       pair_p, pair_q, A, U, Z, ws_bs, ldT, T, T_bs);
+                           stream, nb, dq, M, P, ws_bs);
+    if (dq >= 1)
+        hipLaunchKernelGGL(ib_left_kernel, dim3(kBlk / kTile, (unsigned)n_pairs, (unsigned)B), dim3(256), lds, stream, nb,
+                           pair_p, pair_q, A, M, P, U, ws_bs);
+    hipLaunchKernelGGL(ib_tiles_kernel, dim3(4, (unsigned)n_pairs, (unsigned)B), dim3(256), lds, stream, L, nb, pair_p,
+                       pair_q, A, U, Z, ws_bs, ldT, T, T_bs, max_len);
     return hipGetLastError();
 }
 

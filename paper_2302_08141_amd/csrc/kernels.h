@@ -124,8 +124,8 @@ hipError_t launch_interval_costs(int32_t B, int32_t L, int32_t Kp, int32_t max_l
 
 // The same table put together from blocks of 128 operators (Kp = 64, at least four blocks; needs a workspace).
 size_t interval_blocks_workspace_bytes(int32_t B, int32_t L, int32_t Kp);   // 0 = not applicable to these sizes
-hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, const int64_t* c, const int64_t* R, int64_t ldT,
-                                         int64_t* T, void* workspace, hipStream_t stream);
+hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, int32_t max_len, const int64_t* c, const int64_t* R,
+                                         int64_t ldT, int64_t* T, void* workspace, hipStream_t stream);
 
 // Stage search over a table of interval times.
 size_t stage_interval_workspace_bytes(int32_t B, int32_t L, int32_t S);

@@ -271,28 +271,28 @@ int rh_stage_dp_window_static(int32_t B, int32_t L, int32_t S, const int64_t* se
 size_t rh_static_scratch_bytes(void) { return RH_STATIC_SCRATCH_BYTES; }
 
 int rh_interval_costs_banded(int32_t B, int32_t L, int32_t Kp, int32_t max_len, const int64_t* c, const int64_t* R,
-                             int64_t ldT, int64_t* T, void* stream) {
+                             int64_t ldT, int64_t* T, void* workspace, size_t workspace_bytes, void* stream) {
     if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX || max_len < 1) return RH_ERR_SHAPE;
     if (Kp != 16 && Kp != 32 && Kp != 64 && Kp != 128 && Kp != 256) return RH_ERR_K_RANGE;
     if (ldT < (int64_t)L + 1 || (ldT & 1)) return RH_ERR_SHAPE;
+    if (workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RH_ERR_WORKSPACE;
     if (B == 0) return RH_OK;
     if (!c || !T || (L > 1 && !R)) return RH_ERR_NULL;
     if (!aligned16(c) || !aligned16(T) || (R && !aligned16(R))) return RH_ERR_SHAPE;
+    if (max_len > L) max_len = L;
+    // from blocks of 128 operators where that applies: the caller brought the workspace, and an interval may be
+    // longer than a block
+    const size_t need = workspace != nullptr ? rh::interval_blocks_workspace_bytes(B, L, Kp) : 0;
+    if (need > 0 && workspace_bytes >= need && max_len > 128)
+        return from_hip(rh::launch_interval_costs_blocked(B, L, max_len, c, R, ldT, T, workspace,
+                                                          static_cast<hipStream_t>(stream)));
     return from_hip(rh::launch_interval_costs(B, L, Kp, max_len, c, (int64_t)L * Kp, R, (int64_t)(L - 1) * Kp * Kp,
                                               ldT, T, (int64_t)L * ldT, static_cast<hipStream_t>(stream)));
 }
 
 int rh_interval_costs(int32_t B, int32_t L, int32_t Kp, const int64_t* c, const int64_t* R, int64_t ldT, int64_t* T,
                       void* workspace, size_t workspace_bytes, void* stream) {
-    if (workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RH_ERR_WORKSPACE;
-    const size_t need = workspace != nullptr && B > 0 && L >= 1 ? rh::interval_blocks_workspace_bytes(B, L, Kp) : 0;
-    if (need == 0 || workspace_bytes < need)
-        return rh_interval_costs_banded(B, L, Kp, L > 0 ? L : 1, c, R, ldT, T, stream);
-    // the same checks as the plain call, then the table by blocks
-    if (B > 65535 || ldT < (int64_t)L + 1 || (ldT & 1)) return RH_ERR_SHAPE;
-    if (!c || !T || !R) return RH_ERR_NULL;
-    if (!aligned16(c) || !aligned16(T) || !aligned16(R)) return RH_ERR_SHAPE;
-    return from_hip(rh::launch_interval_costs_blocked(B, L, c, R, ldT, T, workspace, static_cast<hipStream_t>(stream)));
+    return rh_interval_costs_banded(B, L, Kp, L > 0 ? L : 1, c, R, ldT, T, workspace, workspace_bytes, stream);
 }
 
 int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len, int64_t ldT, const int64_t* T,
@@ -365,6 +365,6 @@ const char* rh_strerror(int code) {
 
 int rh_gang_workgroups(int32_t B, int32_t compute_units) { return rh::gang_workgroups(B, compute_units); }
 
-int rh_version(void) { return 104; }
+int rh_version(void) { return 105; }
 
 }  // extern "C"

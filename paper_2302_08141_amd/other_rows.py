@@ -236,8 +236,14 @@ def _interval_rows(dev, L, S, K):
     max_len = 4 * L // S
     t_tab_b = _best_ms(lambda: rh.rh_interval_costs_banded(1, L, K, max_len, c, R, ldT, T))
     cells_tab_b = sum(min(L - 1 - i, max_len - 1) for i in range(L)) * K * K
+    T_rows = T.clone()
+    ws_b = torch.empty(rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, L, K), dtype=torch.uint8, device=dev)
+    t_blk_b = _best_ms(lambda: rh.rh_interval_costs_banded(1, L, K, max_len, c, R, ldT, T, ws_b)) if ws_b.numel() else None
+    if t_blk_b is not None and not torch.equal(T[:, :, :L + 1], T_rows[:, :, :L + 1]):
+        raise RuntimeError("the limited table from blocks differs from the limited table row by row")
+    del T_rows, ws_b
     t_dp_b = _best_ms(lambda: rh.rh_stage_dp_interval_banded(1, L, S, max_len, ldT, T, bott, cut, S, bounds, ws))
-    banded = {"max_len": max_len, "table_ms": t_tab_b, "table_cells": cells_tab_b,
+    banded = {"max_len": max_len, "table_ms": t_tab_b, "table_from_blocks_ms": t_blk_b, "table_cells": cells_tab_b,
               "table_cells_per_s": cells_tab_b / (t_tab_b * 1e-3), "search_ms": t_dp_b,
               "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
     rh.rh_interval_costs(1, L, K, c, R, ldT, T)

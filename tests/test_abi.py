@@ -53,7 +53,7 @@ def test_host_only_calls():
     assert L.rh_interval_costs(1, 8, 48, None, None, 10, None, None, 0, None) == -3
     assert L.rh_interval_costs(1, 8, 64, None, None, 9, None, None, 0, None) == -2      # odd row stride
     assert L.rh_stage_dp_interval(1, 8, 9, 10, None, None, None, 0, None, None, 0, None) == -2
-    assert L.rh_interval_costs_banded(1, 8, 64, 0, None, None, 10, None, None) == -2      # a stage holds an operator at least
+    assert L.rh_interval_costs_banded(1, 8, 64, 0, None, None, 10, None, None, 0, None) == -2      # a stage holds an operator at least
     assert L.rh_stage_dp_interval_banded(1, 8, 4, 0, 10, None, None, None, 0, None, None, 0, None) == -2
     assert rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, 4096, 64) > 2 * 4097 * 8
     # the table by blocks: Kp = 64 and at least four blocks of 128 operators

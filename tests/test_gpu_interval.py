@@ -216,6 +216,35 @@ def test_table_put_together_from_blocks(L, B, seed):
         assert got[1, 0, L] == INF and got[1, L // 2 + 8, L] < INF
 
 
+@pytest.mark.parametrize("L,max_len,B", [(640, 129, 1), (640, 130, 2), (700, 256, 1), (1100, 257, 1), (1100, 384, 2),
+                                         (900, 386, 1), (1100, 1099, 1), (600, 128, 1), (513, 5000, 1)])
+def test_limited_table_put_together_from_blocks(L, max_len, B):
+    # with the workspace only the pairs of blocks that an interval of max_len operators can span are multiplied;
+    # everything longer is RH_INF (a limit of a block or less goes row by row whatever the workspace)
+    Kp = 64
+    rng = np.random.default_rng(L + max_len)
+    c = rng.integers(0, 5 if B == 2 else 100_000, size=(B, L, Kp)).astype(np.int64)
+    R = rng.integers(0, 5 if B == 2 else 200_000, size=(B, L - 1, Kp, Kp)).astype(np.int64)
+    R[rng.random(R.shape) < 0.03] = INF
+    c[:, :, 60:] = INF
+    ldT = even_ld(L)
+    d_c, d_R = torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV)
+    ws = torch.full((rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, B, L, Kp),), 0x3B, dtype=torch.uint8, device=DEV)
+    assert ws.numel() > 0
+    T = torch.full((B, L, ldT), -3, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs_banded(B, L, Kp, max_len, d_c, d_R, ldT, T, ws)
+    plain = torch.full((B, L, ldT), -3, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs_banded(B, L, Kp, max_len, d_c, d_R, ldT, plain)
+    torch.cuda.synchronize()
+    assert torch.equal(T[:, :, :L + 1], plain[:, :, :L + 1])
+    assert bool((T[:, :, L + 1:] == -3).all())               # columns beyond L are not written
+    got = T.cpu().numpy()
+    for p in range(B):
+        want = oracle.interval_costs(np.ascontiguousarray(c[p]), np.ascontiguousarray(R[p]), ldT=ldT, nthreads=8,
+                                     max_len=min(max_len, L))
+        assert np.array_equal(got[p, :, :L + 1], want[:, :L + 1]), p
+
+
 def test_blocks_at_the_cost_ceiling():
     # every finite cost within 2^10 of 2^36: entries of the table approach 2^47 at this length
     L, Kp = 700, 64
@@ -311,7 +340,13 @@ def test_limited_table_and_search_at_full_size():
     ldT = even_ld(L)
     d_T = torch.full((1, L, ldT), -7, dtype=torch.int64, device=DEV)
     rh.rh_interval_costs_banded(1, L, K, max_len, torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV), ldT, d_T)
+    ws = torch.empty(rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, L, K), dtype=torch.uint8, device=DEV)
+    from_blocks = torch.full((1, L, ldT), -7, dtype=torch.int64, device=DEV)
+    rh.rh_interval_costs_banded(1, L, K, max_len, torch.from_numpy(c).to(DEV), torch.from_numpy(R).to(DEV), ldT,
+                                from_blocks, ws)
     torch.cuda.synchronize()
+    assert torch.equal(from_blocks[:, :, :L + 1], d_T[:, :, :L + 1])
+    del from_blocks, ws
     T = d_T.cpu().numpy()
     for i in (0, 1, 15, 16, 17, 1000, 2047, 3839, 3840, 3841, 4000, 4095):
         j_end = min(L, i + max_len)

@@ -141,7 +141,9 @@ def table_case(rng):
     dc = torch.from_numpy(c).to(DEV)
     dR = torch.from_numpy(R).to(DEV) if L > 1 else None
     if mode == 2:
-        rh.rh_interval_costs_banded(B, L, Kp, max_len, dc, dR, ldT, dT)
+        need = rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, B, L, Kp) if rng.random() < 0.5 else 0
+        rh.rh_interval_costs_banded(B, L, Kp, max_len, dc, dR, ldT, dT,
+                                    torch.empty(need, dtype=torch.uint8, device=DEV) if need else None)
     else:
         need = rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, B, L, Kp) if mode == 1 else 0
         rh.rh_interval_costs(B, L, Kp, dc, dR, ldT, dT, torch.empty(need, dtype=torch.uint8, device=DEV) if need else None)
