@@ -201,7 +201,7 @@ struct IbLayout {
 IbLayout ib_layout(int32_t B, int32_t L) {
     IbLayout o{};
     o.nb = (L + kBlk - 1) / kBlk;
-    o.n_pairs = (o.nb - 1) * (o.nb - 1);          // slots (p, p + d), 0 <= p <= nb - 2, 0 <= d <= nb - 2, at most
+    o.n_pairs = (o.nb - 1) * o.nb / 2;            // 0 <= p <= q <= nb - 2: the longest list
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t nb = (size_t)o.nb, mat = (size_t)kK * kK * 8;
     o.a_off = 0;
@@ -215,16 +215,20 @@ IbLayout ib_layout(int32_t B, int32_t L) {
     return o;
 }
 
-// the pair lists, written by the device itself (nothing is copied from the host): slot t stands for p = t / (dq + 1),
-// q = p + t % (dq + 1); a slot whose q lies beyond the last-but-one block is marked (-1, -1) and skipped by the kernels
+// the pair lists (p, q), 0 <= p <= q <= min(p + dq, nb - 2), in the order p = 0: q = 0 .. ; p = 1: q = 1 .. ; ...,
+// written by the device itself: nothing is copied from the host
 __global__ void __launch_bounds__(256)
 ib_pairs_kernel(int32_t nb, int32_t dq, int32_t n_pairs, int32_t* __restrict__ pair_p, int32_t* __restrict__ pair_q) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= n_pairs) return;
-    const int p = t / (dq + 1), q = p + t % (dq + 1);
-    const bool ok = q <= nb - 2;
-    pair_p[t] = ok ? p : -1;
-    pair_q[t] = ok ? q : -1;
+    int p = 0, first = 0;
+    for (; p < nb - 2; ++p) {
+        const int len = (dq < nb - 2 - p ? dq : nb - 2 - p) + 1;
+        if (t < first + len) break;
+        first += len;
+    }
+    pair_p[t] = p;
+    pair_q[t] = p + (t - first);
 }
 
 }  // namespace
@@ -245,7 +249,8 @@ hipError_t launch_interval_costs_blocked(int32_t B, int32_t L, int32_t max_len, 
     // apart hold no interval within the limit.
     int dq = (int)(((int64_t)max_len - 2) / kBlk);
     dq = dq < nb - 2 ? dq : nb - 2;
-    const int n_pairs = (nb - 1) * (dq + 1);
+    int n_pairs = 0;                              // pairs (p, q), p <= q <= min(p + dq, nb - 2)
+    for (int p = 0; p <= nb - 2; ++p) n_pairs += (dq < nb - 2 - p ? dq : nb - 2 - p) + 1;
     char* ws = static_cast<char*>(workspace);
     int64_t* A = reinterpret_cast<int64_t*>(ws + lay.a_off);
     int64_t* Z = reinterpret_cast<int64_t*>(ws + lay.z_off);
