@@ -23,6 +23,30 @@ def test_header_symbols_are_exported():
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header compiles as C99 on its own, and a C program that names every entry point
+    # links against the library (no device is touched: only host-side calls are made)
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    assert gcc is not None
+    hdr = os.path.join(ROOT, "include", "rhino.h")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                   check=True)
+    src = tmp_path / "use.c"
+    names = declared_functions()
+    src.write_text('#include "rhino.h"\n#include <stdio.h>\nint main(void) {\n'
+                   + "".join(f"    if ((void*)&{n} == 0) return 2;\n" for n in names)
+                   + '    printf("%d %s\\n", rh_version(), rh_strerror(0));\n'
+                   + "    return rh_workspace_size(RH_WS_STAGE_DP, 1, 64, 8) > 0 ? 0 : 1;\n}\n")
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(rh.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-Wall", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:" + os.path.basename(rh.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == rh.rh_version() and out[1] == "ok"
+
+
 def test_host_only_calls():
     assert rh.rh_version() >= 100
     assert rh.strerror(0) == "ok" and "NULL" in rh.strerror(-1)
