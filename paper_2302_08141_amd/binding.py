@@ -12,7 +12,8 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "librhino.so")
+# RHINO_LIBRARY names another build of the same library (the CPU-side sanitizer leg of the tests uses it)
+LIB_PATH = os.environ.get("RHINO_LIBRARY") or os.path.join(_PKG, "librhino.so")
 
 INF = 1 << 52
 KMIN, KMAX, NMAX = 16, 1024, 16384

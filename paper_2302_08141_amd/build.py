@@ -35,6 +35,21 @@ def build_all(verbose: bool = False) -> None:
             print(log)
 
 
+def build_host_sanitized(out: str) -> str:
+    """librhino with its HOST code (argument checks, planners, launch set-up) under the address and
+    undefined-behaviour sanitizers; the device code is compiled as usual.  For CPU-side tests only."""
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS] + ["-g"] + san
+    _run([HIPCC] + flags + ["-o", out] + RHINO_SOURCES)
+    return out
+
+
+def host_sanitizer_runtime() -> str:
+    """The shared AddressSanitizer runtime of the compiler that hipcc drives (to be preloaded by the test process)."""
+    return _run([HIPCC, "-print-file-name=libclang_rt.asan-x86_64.so"]).strip().splitlines()[-1]
+
+
 if __name__ == "__main__":
     build_all(verbose=True)
     print("built", LIBRHINO, LIBSYNTH)

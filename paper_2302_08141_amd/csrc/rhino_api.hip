@@ -319,6 +319,7 @@ int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int
 }
 
 size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or_S) {
+    if (B < 1) return 0;                          // no problem, no workspace (and nothing below divides by B)
     if (which == RH_WS_MINPLUS_CHAIN) {
         const size_t scan = B <= 2 ? rh::scan_workspace_bytes(B, N_or_L, Kp_or_S) : 0;
         return scan != 0 ? scan : rh::gang_workspace_bytes(B, N_or_L, Kp_or_S);
@@ -327,15 +328,15 @@ size_t rh_workspace_size(int32_t which, int32_t B, int32_t N_or_L, int32_t Kp_or
     if (which == RH_WS_MINPLUS_CHAIN_SPECS) return rh::scan_specs_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_INTERVAL_COSTS) return rh::interval_blocks_workspace_bytes(B, N_or_L, Kp_or_S);
     if (which == RH_WS_STAGE_DP) {
-        if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
+        if (B > 65535 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_workspace_bytes(B, N_or_L, Kp_or_S);
     }
     if (which == RH_WS_STAGE_DP_WINDOW) {
-        if (B < 0 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
+        if (B > 65535 || N_or_L < 1 || N_or_L > 65536 || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_window_workspace_bytes(B, N_or_L, Kp_or_S);
     }
     if (which == RH_WS_STAGE_DP_INTERVAL) {
-        if (B < 0 || N_or_L < 1 || N_or_L > RH_NMAX || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
+        if (B > 65535 || N_or_L < 1 || N_or_L > RH_NMAX || Kp_or_S < 1 || Kp_or_S > N_or_L) return 0;
         return rh::stage_interval_workspace_bytes(B, N_or_L, Kp_or_S);
     }
     return 0;

@@ -49,6 +49,8 @@ def test_header_is_plain_c(tmp_path):
 
 def test_host_only_calls():
     assert rh.rh_version() >= 100
+    for which in range(8):                                   # no problems: no workspace (and no division by B)
+        assert rh.rh_workspace_size(which, 0, 4096, 64) == 0 and rh.rh_workspace_size(which, -1, 4096, 64) == 0
     assert rh.strerror(0) == "ok" and "NULL" in rh.strerror(-1)
     assert rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, 4096, 512, 128) == 0
     # one or two long chains: room for the segment matrices (two thirds + whole), at least a Kp x Kp table each
