@@ -49,6 +49,11 @@ for which in range(8):
         for N in (-5, 0, 1, 63, 64, 127, 128, 511, 512, 4096, 16384, 16385, 1 << 30):
             for K in (-1, 0, 1, 15, 16, 48, 64, 128, 256, 512, 1024, 2048):
                 rh.rh_workspace_size(which, B, N, K)
+for which in (0, 3, 4, 5, 6):                      # the planners behind the sizes, over the whole range of lengths
+    for N in list(range(1, 700)) + list(range(700, 16386, 37)):
+        for K in (64, 128, 256):
+            for B in (1, 2, 3, 32):
+                rh.rh_workspace_size(which, B, N, K if which != 3 else min(N, 64))
 for B in (-3, 0, 1, 31, 32, 33, 64, 65, 1 << 30):
     for cus in (-1, 0, 1, 8, 104, 256, 304, 1 << 30):
         assert rh.rh_gang_workgroups(B, cus) in (0, 4, 8)
