@@ -115,3 +115,13 @@ def test_single_node_long_runs_and_no_plan():
                   (n - 1) * 64 * 64, arg, w, total, choice, None)
     torch.cuda.synchronize()
     assert total.item() == oracle.tree(parent, c, R)[1]
+
+
+def test_the_bench_tree_at_full_size():
+    # 4096 nodes, 64 strategies, inner nodes joining up to four inputs: the tree the timing row uses, two problems
+    # sharing its tables (the second with halved node costs), every output against the oracle
+    n, K = 4096, 64
+    parent = trees.random_tree(n, max_fan_in=4, chain_bias=0.7)
+    c, R = trees.random_tree_costs(parent, K)
+    tp, total = check(parent, np.stack([c, c // 2]), R, shared_R=True)
+    assert tp.n_rounds >= 20 and trees.depth(parent) >= 40 and (total < INF).all()
