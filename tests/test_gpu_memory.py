@@ -29,8 +29,9 @@ def gpu_sweep(c, R, param_bytes, repl, mem, limit, n_k, k0=0, use_workspace=Fals
     last = torch.empty(n_k, dtype=torch.int32, device=DEV)
     plan = torch.empty((n_k, N), dtype=torch.int32, device=DEV)
     ws = None
-    if use_workspace:
-        ws = torch.empty(rh.rh_workspace_size(rh.WS_MINPLUS_CHAIN, n_k, N, Kp), dtype=torch.uint8, device=DEV)
+    if use_workspace:                             # True: the default kind; else the kind named
+        kind = rh.WS_MINPLUS_CHAIN if use_workspace is True else use_workspace
+        ws = torch.empty(rh.rh_workspace_size(kind, n_k, N, Kp), dtype=torch.uint8, device=DEV)
     rh.rh_minplus_chain(n_k, N, Kp, cm, N * Kp, dR, 0, arg, None, total, last, ws)
     rh.rh_backtrack(n_k, N, Kp, arg, last, plan)
     plan_mem = torch.full((n_k,), -7, dtype=torch.int64, device=DEV)
@@ -87,19 +88,42 @@ def test_gpt_like_chain_sweep():
     assert 0 < first <= n_params and np.all(np.diff(totals) >= 0)
 
 
+_moe = {}
+
+
+def moe_tables():
+    """The MoE-shaped graph with its tables from the oracle (host) and from rh_build_reshard (device), once."""
+    if not _moe:
+        g = graphs.moe_chain()
+        N, Kp = g["N"], g["Kp"]
+        R = torch.empty((N - 1, Kp, Kp), dtype=torch.int64, device=DEV)
+        rh.rh_build_reshard(rh.Mesh.make(g["m"], g["bw_bytes_per_us"], g["alpha_ns"]), N - 1, Kp, dev(g["K"]),
+                            dev(g["out_spec"].view(np.int32)), dev(g["in_spec"].view(np.int32)), dev(g["dims"]),
+                            dev(g["elem_bytes"]), R)
+        torch.cuda.synchronize()
+        R_host = oracle.build_reshard(g["m"], g["bw_bytes_per_us"], g["alpha_ns"], g["K"], g["out_spec"], g["in_spec"],
+                                      g["dims"], g["elem_bytes"])
+        assert np.array_equal(R.cpu().numpy(), R_host)
+        _moe.update(g=g, R=R, R_host=R_host)
+    return _moe["g"], _moe["R"], _moe["R_host"]
+
+
 def test_moe_shaped_graph_sweep_chunk():
-    g = graphs.moe_chain()
-    N, Kp = g["N"], g["Kp"]
-    R = torch.empty((N - 1, Kp, Kp), dtype=torch.int64, device=DEV)
-    rh.rh_build_reshard(rh.Mesh.make(g["m"], g["bw_bytes_per_us"], g["alpha_ns"]), N - 1, Kp, dev(g["K"]),
-                        dev(g["out_spec"].view(np.int32)), dev(g["in_spec"].view(np.int32)), dev(g["dims"]),
-                        dev(g["elem_bytes"]), R)
-    torch.cuda.synchronize()
+    g, R, R_host = moe_tables()
     limit = 64 << 30
     # k = 190 .. 193 of the 480 parameters, once per kernel family (one workgroup per problem, then eight)
     for use_ws in (False, True):
-        check(g["c"], R.cpu().numpy(), g["param_bytes"], g["repl"], g["mem"], limit, 4, k0=190, R_dev=R,
-              use_workspace=use_ws)
+        check(g["c"], R_host, g["param_bytes"], g["repl"], g["mem"], limit, 4, k0=190, R_dev=R, use_workspace=use_ws)
+
+
+def test_moe_shaped_graph_sweep_of_the_timing_row():
+    # 16 values of k from 176 under a limit of 2^40 bytes per device, all chains cut into segments (the workspace of
+    # exactly the segmented size): the sweep ends at a feasible k
+    g, R, R_host = moe_tables()
+    totals, first = check(g["c"], R_host, g["param_bytes"], g["repl"], g["mem"], 1 << 40, 16, k0=176, R_dev=R,
+                          use_workspace=rh.WS_MINPLUS_CHAIN_SEGMENTED)
+    assert first == 10 and totals[first] < INF
+    _moe.clear()
 
 
 def test_argument_errors():
