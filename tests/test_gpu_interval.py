@@ -115,8 +115,9 @@ def test_table_and_search_together_and_the_plan_of_a_stage():
     ldT = even_ld(L)
     T = gpu_table(c, R, ldT)
     h_T = T.cpu().numpy()
-    assert np.array_equal(h_T[0, :, :L + 1], oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=4)[:, :L + 1])
-    want = oracle.stage_interval(h_T, S, s_query=S, nthreads=4)
+    o_T = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=4)
+    assert np.array_equal(h_T[0, :, :L + 1], o_T[:, :L + 1])
+    want = oracle.stage_interval(o_T[None], S, s_query=S, nthreads=4)     # the oracle's own table
     got = gpu_search(T, S, S)
     for g, w in zip(got, want):
         assert np.array_equal(g, w)
@@ -148,7 +149,6 @@ def test_stage_partition_size_with_interval_times():
     want_T = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=oracle.num_threads())
     h_T = T.cpu().numpy()
     assert np.array_equal(h_T[0, :, :L + 1], want_T[:, :L + 1])
-    del want_T
     # the same table from blocks of 128 operators
     ws = torch.empty(rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, L, K), dtype=torch.uint8, device=DEV)
     assert ws.numel() > 0
@@ -157,7 +157,7 @@ def test_stage_partition_size_with_interval_times():
     torch.cuda.synchronize()
     assert torch.equal(T2, T)
     del T2, ws
-    want = oracle.stage_interval(h_T, S, s_query=S, nthreads=oracle.num_threads())
+    want = oracle.stage_interval(want_T[None], S, s_query=S, nthreads=oracle.num_threads())   # the oracle's own table
     got = gpu_search(T, S, S)
     for g, x in zip(got, want):
         assert np.array_equal(g, x)
@@ -171,8 +171,8 @@ def test_longest_chain_the_interface_takes():
     want_T = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=oracle.num_threads())
     h_T = T.cpu().numpy()
     assert np.array_equal(h_T[0, :, :L + 1], want_T[:, :L + 1])
-    del want_T
-    want = oracle.stage_interval(h_T, S, s_query=S, nthreads=oracle.num_threads())
+    del h_T
+    want = oracle.stage_interval(want_T[None], S, s_query=S, nthreads=oracle.num_threads())   # the oracle's own table
     got = gpu_search(T, S, S)
     for g, x in zip(got, want):
         assert np.array_equal(g, x)
@@ -333,8 +333,8 @@ def test_search_with_a_limit_on_the_stage_length(L, S, B, max_len):
 
 
 def test_limited_table_and_search_at_full_size():
-    # the bench shape: 4096 operators, 64 strategies, 64 stages, no stage longer than 256 operators; the table is
-    # checked on sampled rows (each an oracle sweep of its own), the search in full on the GPU's own table
+    # 4096 operators, 64 strategies, 64 stages, no stage longer than 256 operators: the whole table and the whole
+    # search against the oracle
     L, K, S, max_len = 4096, 64, 64, 256
     c, R = syn.random_chain_batch([11], L, K, 100_000, 200_000)
     ldT = even_ld(L)
@@ -348,12 +348,14 @@ def test_limited_table_and_search_at_full_size():
     assert torch.equal(from_blocks[:, :, :L + 1], d_T[:, :, :L + 1])
     del from_blocks, ws
     T = d_T.cpu().numpy()
-    for i in (0, 1, 15, 16, 17, 1000, 2047, 3839, 3840, 3841, 4000, 4095):
+    o_T = oracle.interval_costs(c[0], R[0], ldT=ldT, nthreads=oracle.num_threads(), max_len=max_len)
+    assert np.array_equal(T[0, :, :L + 1], o_T[:, :L + 1])
+    for i in (0, 1, 15, 16, 17, 1000, 2047, 3839, 3840, 3841, 4000, 4095):     # and each of these rows as a sweep of its own
         j_end = min(L, i + max_len)
         sub = oracle.interval_costs(c[0, i:j_end].copy(), R[0, i:max(j_end - 1, i)].copy())
         assert np.array_equal(T[0, i, i + 1:j_end + 1], sub[0, 1:j_end - i + 1]), i
         assert (T[0, i, :i + 1] == INF).all() and (T[0, i, j_end + 1:L + 1] == INF).all(), i
-    want = oracle.stage_interval(T, S, s_query=S, nthreads=8)
+    want = oracle.stage_interval(o_T[None], S, s_query=S, nthreads=8)          # the oracle's own table
     bott = torch.empty((1, S), dtype=torch.int64, device=DEV)
     cut = torch.empty((1, S, L + 1), dtype=torch.int32, device=DEV)
     bounds = torch.empty((1, S + 1), dtype=torch.int32, device=DEV)

@@ -110,7 +110,7 @@ def test_graph_of_the_stage_searches():
     want_T = T.clone()
     o_T = oracle.interval_costs(hc[0], hR[0], ldT=ldT)
     assert np.array_equal(want_T.cpu().numpy()[0, :, :L + 1], o_T[:, :L + 1])
-    o_b, o_c, o_d = oracle.stage_interval(want_T.cpu().numpy(), S, s_query=S)
+    o_b, o_c, o_d = oracle.stage_interval(o_T[None], S, s_query=S)
     assert np.array_equal(want["b1"].cpu().numpy(), o_b) and np.array_equal(want["d1"].cpu().numpy(), o_d)
     assert np.array_equal(want["b3"].cpu().numpy(), oracle.stage_dp(costb.cpu().numpy(), 4)[0])
 
