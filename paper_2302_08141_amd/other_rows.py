@@ -75,6 +75,7 @@ def _fused_rows(g, dev):
     n_dev = g["m"][0] * g["m"][1]
     shapes = [(1 << k, n_dev >> k) for k in range(n_dev.bit_length())]
     out = {"mesh_shapes": len(shapes)}
+    whole = {}                                    # totals of the whole-chain kernel per batch size
     for B in (1, len(shapes), 256):
         meshes = [rh.Mesh.make(shapes[(p + len(shapes) // 2) % len(shapes)], g["bw_bytes_per_us"], g["alpha_ns"])
                   for p in range(min(B, len(shapes)))]
@@ -86,6 +87,7 @@ def _fused_rows(g, dev):
                                                        total, last), reps=2)
         cells = B * (N - 1) * Kp * Kp
         out[f"B{B}"] = {"ms": t, "cells_per_s": cells / (t * 1e-3), "tables_not_stored_gb": cells * 8 / 1e9}
+        whole[B] = [int(x) for x in total.tolist()]
     # the segmented route with every table entry computed from the spec words (no table in memory either)
     for B in (1, len(shapes)):
         meshes = [rh.Mesh.make(shapes[(p + len(shapes) // 2) % len(shapes)], g["bw_bytes_per_us"], g["alpha_ns"])
@@ -119,6 +121,10 @@ def _fused_rows(g, dev):
     out["B11_totals_ns"] = [int(x) for x in total.tolist()]
     if out["B11_totals_ns"] != seg_totals:
         raise RuntimeError("the two routes over the 11 mesh shapes disagree")
+    # problem p of every batch is the graph on mesh shape p mod 11: the whole-chain kernel must agree with both
+    for Bw, got in whole.items():
+        if got != [seg_totals[p % B] for p in range(Bw)]:
+            raise RuntimeError(f"the whole-chain kernel on {Bw} problems disagrees with the segmented routes")
     return out
 
 
