@@ -62,8 +62,8 @@ def chain_case(rng):
 
 
 def tree_case(rng):
-    Kp = int(rng.choice([16, 32, 64, 128, 256]))
-    n = int(rng.integers(1, 400 if Kp <= 64 else 120))
+    Kp = int(rng.choice([16, 32, 64, 128, 256, 512, 1024]))
+    n = int(rng.integers(1, 400 if Kp <= 64 else (120 if Kp <= 256 else 12)))
     B = int(rng.integers(1, 4))
     K = int(rng.integers(max(1, Kp // 2), Kp + 1))
     seed = int(rng.integers(0, 1 << 30))
@@ -102,8 +102,10 @@ def stage_case(rng):
 
 def search_case(rng):
     L = int(rng.integers(1, 1500))
+    B = int(rng.choice([1, 2, 3, 40]))                       # 40 problems: the rows of a column stay in one workgroup
+    if B == 40:
+        L = min(L, 300)
     S = int(rng.integers(1, min(L, 64) + 1))
-    B = int(rng.integers(1, 4))
     ldT = L + 2 - (L & 1)
     max_len = int(rng.choice([L, L, int(rng.integers(1, L + 1)), 1024, 1025, 300]))
     T = rng.integers(0, 6 if rng.random() < 0.4 else 100000, size=(B, L, ldT)).astype(np.int64)
@@ -129,9 +131,9 @@ def search_case(rng):
 
 
 def table_case(rng):
-    Kp = int(rng.choice([16, 64, 64, 64, 128]))
-    L = int(rng.integers(1, 900 if Kp == 64 else 200))
-    B = int(rng.integers(1, 3))
+    Kp = int(rng.choice([16, 32, 64, 64, 64, 128, 256]))
+    L = int(rng.integers(1, 900 if Kp == 64 else (200 if Kp < 256 else 60)))
+    B = int(rng.integers(1, 4))
     K = int(rng.integers(max(1, Kp // 2), Kp + 1))
     ldT = L + 2 - (L & 1)
     c, R = rand_chain(rng, B, L, K, Kp, rng.random() < 0.3, float(rng.choice([0, 0.05])))
