@@ -478,6 +478,33 @@ int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len
                                 int32_t* cut, int32_t s_query, int32_t* bounds,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * rh_stage_plans -- the plans of the chosen stages, all at once.  Sec. 3 plans every stage's
+ * subgraph on its own: once rh_stage_dp_interval (or any of the stage searches) has fixed the
+ * boundaries, stage t of a chain holds the operators bounds[t] .. bounds[t+1]-1 and its plan is
+ * what rh_minplus_chain and rh_backtrack return for that sub-chain (the edges between its
+ * operators only; an edge that crosses a stage boundary belongs to no stage):
+ *     stage_total[t] = T[bounds[t]][bounds[t+1]] of rh_interval_costs,
+ *     stage_last[t]  = the lowest best strategy of the stage's last operator,
+ *     plan[i]        = strategy of operator i, the chain DP's tie rule inside every stage.
+ * One launch for the sweeps of all stages of all chains (a ragged batch), one for the walks back.
+ *
+ *   0 <= B <= 65535, 1 <= S <= L <= RH_NMAX, S <= 1024, Kp a power of two in [16, 1024]
+ *   bounds      [B][S+1] device, as the stage searches write them.  A pair that describes no
+ *               stage (negative, not increasing, beyond L: what a search without a feasible
+ *               split leaves) gives stage_total = RH_INF, stage_last = 0 and no plan entries.
+ *   c [B][L][Kp], R [B][L-1][Kp][Kp] (dense; R may be NULL if L == 1), as rh_interval_costs
+ *   arg         [B][L-1][Kp] out: rows of the edges inside stages as rh_minplus_chain writes
+ *               them; rows of edges between stages are not written.  May be NULL if L == 1.
+ *   stage_total [B][S] out, stage_last [B][S] out
+ *   plan        [B][L] out; operators that no stage holds get -1.  May be NULL: totals only.
+ * c, R and arg must be 16-byte aligned.  A stage without a feasible plan returns RH_INF, last 0
+ * and a plan of zeros, as rh_minplus_chain does.
+ */
+int rh_stage_plans(int32_t B, int32_t L, int32_t Kp, int32_t S, const int32_t* bounds,
+                   const int64_t* c, const int64_t* R, uint16_t* arg, int64_t* stage_total,
+                   int32_t* stage_last, int32_t* plan, void* stream);
+
 #define RH_WS_MINPLUS_CHAIN 0
 #define RH_WS_STAGE_DP 1
 #define RH_WS_STAGE_DP_WINDOW 2

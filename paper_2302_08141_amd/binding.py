@@ -76,6 +76,8 @@ def lib():
         L.rh_static_scratch_bytes.restype = sz
         L.rh_interval_costs.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, sz, vp]
         L.rh_stage_dp_interval.argtypes = [i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.rh_stage_plans.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.rh_stage_plans.restype = ctypes.c_int
         L.rh_interval_costs_banded.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp, vp, sz, vp]
         L.rh_stage_dp_interval_banded.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp]
         L.rh_interval_costs_banded.restype = L.rh_stage_dp_interval_banded.restype = ctypes.c_int
@@ -341,6 +343,19 @@ def rh_interval_costs_banded(B: int, L: int, Kp: int, max_len: int, c, R, ldT: i
                                           _ptr(R, torch.int64, "R", b * max(l - 1, 0) * k * k), ldT,
                                           _ptr(T, torch.int64, "T", b * l * max(ldT, 0)), ws_ptr, ws_bytes, _stream()),
            "rh_interval_costs_banded")
+
+
+def rh_stage_plans(B: int, L: int, Kp: int, S: int, bounds, c, R, arg, stage_total, stage_last, plan):
+    """bounds int32[B][S+1]; c int64[B][L][Kp]; R int64[B][L-1][Kp][Kp] (None if L == 1); arg int16[B][L-1][Kp] out;
+    stage_total int64[B][S] out; stage_last int32[B][S] out; plan int32[B][L] out or None."""
+    b, l, k, s_ = max(B, 0), max(L, 0), max(Kp, 0), max(S, 0)
+    _check(lib().rh_stage_plans(B, L, Kp, S, _ptr(bounds, torch.int32, "bounds", b * (s_ + 1)),
+                                _ptr(c, torch.int64, "c", b * l * k),
+                                _ptr(R, torch.int64, "R", b * max(l - 1, 0) * k * k),
+                                _ptr(arg, torch.int16, "arg", b * max(l - 1, 0) * k),
+                                _ptr(stage_total, torch.int64, "stage_total", b * s_),
+                                _ptr(stage_last, torch.int32, "stage_last", b * s_),
+                                _ptr(plan, torch.int32, "plan", b * l), _stream()), "rh_stage_plans")
 
 
 def rh_stage_dp_interval_banded(B: int, L: int, S: int, max_len: int, ldT: int, T, bottleneck, cut, s_query: int,

@@ -16,7 +16,7 @@ LIBRHINO = os.path.join(_PKG, "librhino.so")
 LIBSYNTH = os.path.join(_PKG, "workloads", "libsynthfill.so")
 
 RHINO_SOURCES = [os.path.join(_CSRC, f) for f in
-                 ("rhino_api.hip", "chain_dp.hip", "chain_gang.hip", "chain_scan.hip", "chain_fused.hip", "backtrack.hip", "reshard.hip", "stage_dp.hip", "stage_fast.hip", "interval_costs.hip", "interval_blocks.hip", "stage_interval.hip", "cone.hip", "tree.hip", "memory.hip")]
+                 ("rhino_api.hip", "chain_dp.hip", "chain_gang.hip", "chain_scan.hip", "chain_fused.hip", "backtrack.hip", "reshard.hip", "stage_dp.hip", "stage_fast.hip", "interval_costs.hip", "interval_blocks.hip", "stage_interval.hip", "stage_plans.hip", "cone.hip", "tree.hip", "memory.hip")]
 SYNTH_SOURCES = [os.path.join(_PKG, "workloads", "csrc", "synth_fill.hip")]
 
 

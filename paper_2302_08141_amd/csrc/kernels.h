@@ -133,6 +133,11 @@ hipError_t launch_stage_interval(int32_t B, int32_t L, int32_t S, int32_t max_le
                                  int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace,
                                  hipStream_t stream);
 
+// The plans of S stages of every chain at once (a ragged batch of sub-chains; stage_plans.hip).
+hipError_t launch_stage_plans(int32_t B, int32_t L, int32_t Kp, int32_t S, const int32_t* bounds, const int64_t* c,
+                              const int64_t* R, uint16_t* arg, int64_t* stage_total, int32_t* stage_last,
+                              int32_t* plan, hipStream_t stream);
+
 hipError_t launch_check_costs(const int64_t* x, int64_t n, int64_t* violations, hipStream_t stream);
 
 }  // namespace rh

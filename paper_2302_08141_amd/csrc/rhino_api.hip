@@ -311,6 +311,19 @@ int rh_stage_dp_interval_banded(int32_t B, int32_t L, int32_t S, int32_t max_len
                                               static_cast<hipStream_t>(stream)));
 }
 
+int rh_stage_plans(int32_t B, int32_t L, int32_t Kp, int32_t S, const int32_t* bounds, const int64_t* c,
+                   const int64_t* R, uint16_t* arg, int64_t* stage_total, int32_t* stage_last, int32_t* plan,
+                   void* stream) {
+    if (B < 0 || B > 65535 || L < 1 || L > RH_NMAX || S < 1 || S > L || S > 1024) return RH_ERR_SHAPE;
+    if (!valid_kp(Kp)) return RH_ERR_K_RANGE;
+    if (B == 0) return RH_OK;
+    if (!bounds || !c || !stage_total || !stage_last) return RH_ERR_NULL;
+    if (L > 1 && (!R || !arg)) return RH_ERR_NULL;
+    if (!aligned16(c) || (R && !aligned16(R)) || (arg && !aligned16(arg))) return RH_ERR_SHAPE;
+    return from_hip(rh::launch_stage_plans(B, L, Kp, S, bounds, c, R, arg, stage_total, stage_last, plan,
+                                           static_cast<hipStream_t>(stream)));
+}
+
 int rh_stage_dp_interval(int32_t B, int32_t L, int32_t S, int64_t ldT, const int64_t* T, int64_t* bottleneck,
                          int32_t* cut, int32_t s_query, int32_t* bounds, void* workspace, size_t workspace_bytes,
                          void* stream) {
@@ -366,6 +379,6 @@ const char* rh_strerror(int code) {
 
 int rh_gang_workgroups(int32_t B, int32_t compute_units) { return rh::gang_workgroups(B, compute_units); }
 
-int rh_version(void) { return 105; }
+int rh_version(void) { return 106; }
 
 }  // extern "C"

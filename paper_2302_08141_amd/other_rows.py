@@ -254,7 +254,15 @@ def _interval_rows(dev, L, S, K):
               "bottleneck_ns_at_S": int(bott[0, S - 1].item())}
     rh.rh_interval_costs(1, L, K, c, R, ldT, T)
     rh.rh_stage_dp_interval(1, L, S, ldT, T, bott, cut, S, bounds, ws)
-    return {"K": K, "stages_of_limited_length": banded,
+    # the plans of the S chosen stages, all at once
+    arg = torch.empty((1, L - 1, K), dtype=torch.int16, device=dev)
+    st_total = torch.empty((1, S), dtype=torch.int64, device=dev)
+    st_last = torch.empty((1, S), dtype=torch.int32, device=dev)
+    plan = torch.empty((1, L), dtype=torch.int32, device=dev)
+    t_plans = _best_ms(lambda: rh.rh_stage_plans(1, L, K, S, bounds, c, R, arg, st_total, st_last, plan))
+    if int(st_total.max().item()) != int(bott[0, S - 1].item()) or int(plan.min().item()) < 0:
+        raise RuntimeError("the stages' own plans do not reach the bottleneck the search found")
+    return {"K": K, "stages_of_limited_length": banded, "stage_plans_ms": t_plans,
             "table_ms": t_tab, "table_cells": cells_tab, "table_cells_per_s": cells_tab / (t_tab * 1e-3),
             "table_from_blocks_ms": t_blk,
             "table_f64_lane_ops_per_s": 2 * cells_tab / (t_tab * 1e-3),

@@ -81,6 +81,8 @@ def test_host_only_calls():
     assert L.rh_stage_dp_interval(1, 8, 9, 10, None, None, None, 0, None, None, 0, None) == -2
     assert L.rh_interval_costs_banded(1, 8, 64, 0, None, None, 10, None, None, 0, None) == -2      # a stage holds an operator at least
     assert L.rh_stage_dp_interval_banded(1, 8, 4, 0, 10, None, None, None, 0, None, None, 0, None) == -2
+    assert L.rh_stage_plans(1, 8, 64, 9, None, None, None, None, None, None, None, None) == -2      # more stages than operators
+    assert L.rh_stage_plans(1, 8, 64, 2, None, None, None, None, None, None, None, None) == -1
     assert rh.rh_workspace_size(rh.WS_STAGE_DP_INTERVAL, 1, 4096, 64) > 2 * 4097 * 8
     # the table by blocks: Kp = 64 and at least four blocks of 128 operators
     assert rh.rh_workspace_size(rh.WS_INTERVAL_COSTS, 1, 4096, 64) > 32 * 32 * 64 * 64 * 8

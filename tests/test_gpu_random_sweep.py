@@ -8,6 +8,7 @@ import torch
 import oracle
 import test_gpu_fused
 import test_gpu_stage
+import test_gpu_stage_plans
 import test_gpu_stage_window
 import test_gpu_tree
 from paper_2302_08141_amd import binding as rh
@@ -160,6 +161,22 @@ def table_case(rng):
         assert np.array_equal(got[p][upper], want[upper]), p
 
 
+def plans_case(rng):
+    Kp = int(rng.choice([16, 32, 64, 128, 256]))
+    L = int(rng.integers(1, 500 if Kp <= 64 else 120))
+    S = int(rng.integers(1, min(L, 40) + 1))
+    B = int(rng.integers(1, 4))
+    K = int(rng.integers(max(1, Kp // 2), Kp + 1))
+    c, R = rand_chain(rng, B, L, K, Kp, rng.random() < 0.4, float(rng.choice([0, 0.1])))
+    bounds = np.zeros((B, S + 1), np.int32)
+    for p in range(B):
+        cuts = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False)) if S > 1 else np.zeros(0, np.int32)
+        bounds[p] = np.concatenate([[0], cuts, [L]])
+    if rng.random() < 0.2:
+        bounds[0] = -1                                        # no split found for the first chain
+    test_gpu_stage_plans.check(bounds, c, R)
+
+
 def specs_case(rng):
     Kp = int(rng.choice([64, 128, 256]))
     N = int(rng.integers(2, 400 if Kp == 64 else (200 if Kp == 128 else 100)))
@@ -185,7 +202,7 @@ def specs_case(rng):
     test_gpu_fused.check(g, meshes, cs, segmented=(False, True) if seg else (False,))
 
 
-CASES = [chain_case, chain_case, tree_case, window_case, stage_case, search_case, table_case, specs_case]
+CASES = [chain_case, chain_case, tree_case, window_case, stage_case, search_case, table_case, specs_case, plans_case]
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13, 14])

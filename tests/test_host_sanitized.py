@@ -78,6 +78,7 @@ assert L.rh_interval_costs(1, 8, 64, N_, N_, 10, N_, N_, 0, N_) < 0
 assert L.rh_interval_costs_banded(1, 8, 64, 0, N_, N_, 10, N_, N_, 0, N_) < 0
 assert L.rh_stage_dp_interval(1, 8, 4, 10, N_, N_, N_, 0, N_, N_, 0, N_) < 0
 assert L.rh_stage_dp_interval_banded(1, 8, 4, 3, 10, N_, N_, N_, 0, N_, N_, 0, N_) < 0
+assert L.rh_stage_plans(1, 8, 64, 2, N_, N_, N_, N_, N_, N_, N_, N_) < 0
 assert L.rh_cone_merge(2, 3, 64, N_, N_, N_, N_, N_, N_, N_, N_) < 0
 rs = np.array([0, 1], np.int32)
 assert L.rh_tree_dp(1, 4, 64, 1, 1, hp(rs), N_, N_, N_, N_, N_, N_, 256, N_, 0, N_, N_, N_, N_, N_, N_) < 0
