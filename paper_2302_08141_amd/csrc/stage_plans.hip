@@ -62,19 +62,53 @@ stage_chains_kernel(int32_t L, int32_t S, const int32_t* __restrict__ bounds, co
     c += (int64_t)p * L * KP;
     R += (int64_t)p * (L - 1) * KP * KP;
     arg += (int64_t)p * (L - 1) * KP;
+    // Narrow tables (at most 16 rows per thread): the rows of the next edge and the node cost that goes with them
+    // wait in registers while this edge is relaxed -- a trip to memory takes longer than an edge.
+    constexpr int NR = KP >= SL ? KP / SL : 1;  // rows of an edge table per thread (slices beyond KP rows idle)
+    constexpr bool kAhead = NR <= 16;
+    int64_t ahead[kAhead ? NR : 1], c_ahead = 0;
+    auto fetch = [&](int i) {                   // edge i, f <= i <= e1 - 2
+        if constexpr (kAhead) {
+            const int64_t* Ri = R + (int64_t)i * KP * KP;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int a = slice + r * SL < KP ? slice + r * SL : KP - 1;
+                ahead[r] = __builtin_nontemporal_load(Ri + (int64_t)a * KP + b);
+            }
+            c_ahead = tid < KP ? c[(int64_t)(i + 1) * KP + b] : 0;
+        }
+    };
+    if (f + 1 < e1) fetch(f);
     if (tid < KP) v[b] = sat(c[(int64_t)f * KP + b]);
     lds_barrier();
     for (int i = f; i + 1 < e1; ++i) {
-        const int64_t* Ri = R + (int64_t)i * KP * KP;
-        const int64_t c_next = tid < KP ? c[(int64_t)(i + 1) * KP + b] : 0;
+        int64_t c_next;
         int64_t best = INT64_MAX;
         int besta = 0;
+        if constexpr (kAhead) {
+            int64_t rows[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rows[r] = ahead[r];
+            c_next = c_ahead;
+            if (i + 2 < e1) fetch(i + 1);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int a = slice + r * SL;
+                const int64_t x = v[a < KP ? a : KP - 1] + rows[r];                          // both <= 2^52
+                const bool lt = a < KP && x < best;
+                best = lt ? x : best;
+                besta = lt ? a : besta;
+            }
+        } else {
+            const int64_t* Ri = R + (int64_t)i * KP * KP;
+            c_next = tid < KP ? c[(int64_t)(i + 1) * KP + b] : 0;
 #pragma unroll 4
-        for (int a = slice; a < KP; a += SL) {
-            const int64_t x = v[a] + __builtin_nontemporal_load(Ri + (int64_t)a * KP + b);   // both <= 2^52
-            const bool lt = x < best;
-            best = lt ? x : best;
-            besta = lt ? a : besta;
+            for (int a = slice; a < KP; a += SL) {
+                const int64_t x = v[a] + __builtin_nontemporal_load(Ri + (int64_t)a * KP + b);   // both <= 2^52
+                const bool lt = x < best;
+                best = lt ? x : best;
+                besta = lt ? a : besta;
+            }
         }
         pv[slice][b] = best;
         pa[slice][b] = (uint16_t)besta;
