@@ -23,6 +23,13 @@ constexpr int kTreeThreads = 512;
 
 __device__ __forceinline__ int64_t sat(int64_t x) { return x < kInf ? x : kInf; }
 
+// A barrier that orders LDS traffic only: loads of the next edge's rows and the stores of arg stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // One run of one problem.  Thread t: column b = t % KP, rows a = t / KP, t / KP + S, ... (S = threads / KP slices);
 // the slices' (value, lowest a) candidates meet in LDS, lowest a first among equal values.
 template <int KP>
@@ -47,6 +54,23 @@ tree_run_kernel(int32_t n, int32_t run0, const int32_t* __restrict__ run_first, 
     arg += (int64_t)p * (n - 1) * KP;
     w += (int64_t)p * n * KP;
 
+    // Narrow tables (at most 16 rows per thread): the rows of the next edge of the run wait in registers while this
+    // edge is relaxed.
+    constexpr int NR = KP >= S ? KP / S : 1;    // rows of an edge table per thread (slices beyond KP rows idle)
+    constexpr bool kAhead = NR <= 16;
+    int64_t ahead[kAhead ? NR : 1];
+    auto fetch = [&](int i) {                   // edge i <= n - 2
+        if constexpr (kAhead) {
+            const int64_t* Ri = R + (int64_t)i * KP * KP;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int a = slice + r * S < KP ? slice + r * S : KP - 1;
+                ahead[r] = __builtin_nontemporal_load(Ri + (int64_t)a * KP + b);
+            }
+        }
+    };
+    if (f < n - 1) fetch(f);
+
     // v_f = c_f + what every input of f hands up (inputs in ascending order; saturating)
     if (tid < KP) {
         int64_t x = sat(c[(int64_t)f * KP + b]);
@@ -59,7 +83,7 @@ tree_run_kernel(int32_t n, int32_t run0, const int32_t* __restrict__ run_first, 
         }
         v[b] = x;
     }
-    __syncthreads();
+    lds_barrier();
 
     for (int i = f; i <= e; ++i) {
         if (i == n - 1) {                       // the root: its vector is the table
@@ -87,16 +111,31 @@ tree_run_kernel(int32_t n, int32_t run0, const int32_t* __restrict__ run_first, 
         const int64_t c_next = (i < e && tid < KP) ? c[(int64_t)(i + 1) * KP + b] : 0;
         int64_t best = INT64_MAX;
         int besta = 0;
+        if constexpr (kAhead) {
+            int64_t rows[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rows[r] = ahead[r];
+            if (i < e && i + 1 < n - 1) fetch(i + 1);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int a = slice + r * S;
+                const int64_t x = v[a < KP ? a : KP - 1] + rows[r];                          // both <= 2^52
+                const bool lt = a < KP && x < best;
+                best = lt ? x : best;
+                besta = lt ? a : besta;
+            }
+        } else {
 #pragma unroll 4
-        for (int a = slice; a < KP; a += S) {
-            const int64_t x = v[a] + __builtin_nontemporal_load(Ri + (int64_t)a * KP + b);   // both <= 2^52
-            const bool lt = x < best;
-            best = lt ? x : best;
-            besta = lt ? a : besta;
+            for (int a = slice; a < KP; a += S) {
+                const int64_t x = v[a] + __builtin_nontemporal_load(Ri + (int64_t)a * KP + b);   // both <= 2^52
+                const bool lt = x < best;
+                best = lt ? x : best;
+                besta = lt ? a : besta;
+            }
         }
         pv[slice][b] = best;
         pa[slice][b] = (uint16_t)besta;
-        __syncthreads();                        // every read of v_i is done, the candidates are in LDS
+        lds_barrier();                          // every read of v_i is done, the candidates are in LDS
         if (tid < KP) {
             int64_t m = pv[0][b];
             int ma = pa[0][b];
@@ -114,7 +153,7 @@ tree_run_kernel(int32_t n, int32_t run0, const int32_t* __restrict__ run_first, 
             if (i < e) v[b] = sat(sat(c_next) + m);       // node i + 1 has node i as its only input
             else w[(int64_t)i * KP + b] = m;              // handed to the run of i's parent
         }
-        __syncthreads();
+        lds_barrier();
     }
 }
 
