@@ -5,7 +5,7 @@
 // system (the table of one problem, L^2 * 8 bytes, is re-read S-1 times and mostly stays in the
 // last-level cache): rows of T are read with coalesced 16-byte loads, two j per lane, eight rows
 // in flight per lane; dp[s-1][i] is uniform over a wave and comes through scalar loads.
-// A workgroup owns 128 consecutive j; its 4 waves take the rows i round-robin.  With few problems
+// A workgroup owns 128 consecutive j; its 8 waves take the rows i round-robin.  With few problems
 // the i range is also split over several workgroups.  Their results meet without a launch of their
 // own: per stage count and column one word (value << 6 | part) collects the parts' minima through an
 // atomic minimum -- parts hold ascending rows, so the least word names the least value and the lowest
@@ -20,7 +20,7 @@ namespace {
 
 typedef long long ll2 __attribute__((ext_vector_type(2)));
 
-constexpr int kSiWaves = 4;
+constexpr int kSiWaves = 8;
 constexpr int kSiTile = 128;            // j per workgroup
 constexpr int kSiUnroll = 8;
 
