@@ -14,11 +14,24 @@
  *
  * All costs are int64 nanoseconds.  All pointers are DEVICE pointers unless a
  * parameter says "host".  The caller owns every buffer; the library allocates
- * nothing and keeps no state.  Every call only enqueues kernels on `stream`
+ * nothing and keeps no state between calls (one entry point,
+ * rh_stage_dp_window_static, works on a static device array of its own
+ * instead of a workspace: see there).  Every call only enqueues kernels on `stream`
  * (a hipStream_t passed as void*, NULL = the default stream) and returns; the
  * caller synchronises.  Calls on different streams may run concurrently.
  * Return value: RH_OK or a negative RH_ERR_* code; argument errors are found
  * on the host before anything is launched, so a failing call writes nothing.
+ *
+ * Entry points, in the order of a search:
+ *   rh_build_reshard                      edge tables from sharding specs
+ *   rh_minplus_chain, rh_backtrack        chain DP and its plan (tables in memory)
+ *   rh_minplus_chain_specs                chain DP straight from the specs
+ *   rh_cone_merge, rh_tree_plan/_dp       cones and in-trees
+ *   rh_mask_replicated, rh_plan_memory    search under a memory limit
+ *   rh_stage_dp, rh_stage_dp_window       pipeline stages from segment costs
+ *   rh_interval_costs, rh_stage_dp_interval (and _banded), rh_stage_plans
+ *                                         stages timed by their own plans
+ *   rh_workspace_size, rh_check_costs, rh_gang_workgroups, rh_strerror, rh_version
  *
  * Cost contract: a finite cost lies in [0, 2^36) ns; RH_INF (2^52) means
  * "infeasible"; any sum that reaches RH_INF is RH_INF.  N <= 2^14 keeps every
